@@ -1,0 +1,169 @@
+"""ctypes front end of the float64 CPU oracle (oracle/esrnn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: argument marshalling around the C oracle, which is
+the statement of the method (see esrnn_oracle.h for the passages of the paper
+it follows).  Nothing here imports the HIP package.  The configuration is any
+object with the fields B, T, n_seas, m1, m2, I, H, hidden, blocks (tuple of
+tuples of dilations), tau, lambda_lv, param_space.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from types import SimpleNamespace
+
+import numpy as np
+
+from . import build as _build
+
+_dp = C.POINTER(C.c_double)
+
+
+class _Config(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("T", C.c_int32),
+        ("n_seas", C.c_int32), ("m1", C.c_int32), ("m2", C.c_int32),
+        ("I", C.c_int32), ("H", C.c_int32),
+        ("hidden", C.c_int32),
+        ("n_blocks", C.c_int32),
+        ("layers_in_block", C.c_int32 * 4),
+        ("dilation", (C.c_int32 * 4) * 4),
+        ("param_space", C.c_int32),
+        ("tau", C.c_double), ("lambda_lv", C.c_double),
+        ("n_pin", C.c_double), ("n_lv", C.c_double),
+    ]
+
+
+class _Tape(C.Structure):
+    _fields_ = [(n, _dp) for n in ("alpha", "gamma1", "gamma2", "l", "S1", "S2", "u", "v",
+                                   "X", "Z", "gates", "c", "h", "blk", "a", "o")] + \
+               [(n, C.c_double) for n in ("sum_pin", "sum_lv", "n_pin", "n_lv")]
+
+
+class _Adjoint(C.Structure):
+    _fields_ = [(n, _dp) for n in ("gO", "gR", "gX", "gu", "gv")]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        _lib = C.CDLL(path)
+        _lib.eso_es_param_rows.restype = C.c_int
+        _lib.eso_weight_count.restype = C.c_int64
+        _lib.eso_num_layers.restype = C.c_int
+        _lib.eso_max_threads.restype = C.c_int
+        _lib.eso_forward.restype = C.c_int
+        _lib.eso_backward.restype = C.c_int
+    return _lib
+
+
+def max_threads() -> int:
+    return int(lib().eso_max_threads())
+
+
+def _c_config(cfg, n_pin=0.0, n_lv=0.0, B=None) -> _Config:
+    c = _Config()
+    c.B, c.T = int(cfg.B if B is None else B), int(cfg.T)
+    c.n_seas, c.m1, c.m2 = int(cfg.n_seas), int(cfg.m1), int(cfg.m2)
+    c.I, c.H, c.hidden = int(cfg.I), int(cfg.H), int(cfg.hidden)
+    c.n_blocks = len(cfg.blocks)
+    for k, blk in enumerate(cfg.blocks):
+        c.layers_in_block[k] = len(blk)
+        for j, d in enumerate(blk):
+            c.dilation[k][j] = int(d)
+    c.param_space = int(cfg.param_space)
+    c.tau, c.lambda_lv = float(cfg.tau), float(cfg.lambda_lv)
+    c.n_pin, c.n_lv = float(n_pin), float(n_lv)
+    return c
+
+
+def _ptr(a):
+    return a.ctypes.data_as(_dp)
+
+
+def forward(cfg, y, lengths, es_params, weights, n_pin=0.0, n_lv=0.0, want_forecasts=True):
+    """Run the oracle forward.  Inputs are converted to float64; returns a
+    namespace with loss, forecasts [P,B,H] and every intermediate (series-major
+    arrays, see esrnn_oracle.h)."""
+    L_ = lib()
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    es_params = np.ascontiguousarray(es_params, dtype=np.float64)
+    weights = np.ascontiguousarray(weights, dtype=np.float64)
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    T, B = y.shape
+    cc = _c_config(cfg, n_pin, n_lv, B=B)
+    assert T == cfg.T
+    K = L_.eso_es_param_rows(C.byref(cc))
+    nw = L_.eso_weight_count(C.byref(cc))
+    nl = L_.eso_num_layers(C.byref(cc))
+    if K < 0:
+        raise ValueError("oracle: invalid configuration")
+    assert es_params.shape == (K, B), (es_params.shape, K, B)
+    assert weights.shape == (nw,), (weights.shape, nw)
+    h, I, H = cfg.hidden, cfg.I, cfg.H
+    P = T - I - H + 1
+    nb = len(cfg.blocks)
+    r = SimpleNamespace()
+    r.alpha, r.gamma1, r.gamma2 = (np.zeros(B) for _ in range(3))
+    r.l, r.S1, r.S2, r.u, r.v = (np.zeros((B, T)) for _ in range(5))
+    r.X = np.zeros((B, P, I))
+    r.Z = np.zeros((B, P, H))
+    r.gates = np.zeros((nl, B, P, 4, h))
+    r.c = np.zeros((nl, B, P, h))
+    r.h = np.zeros((nl, B, P, h))
+    r.blk = np.zeros((nb, B, P, h))
+    r.a = np.zeros((B, P, h))
+    r.o = np.zeros((B, P, H))
+    r.forecasts = np.zeros((P, B, H)) if want_forecasts else None
+    tape = _Tape()
+    for name in ("alpha", "gamma1", "gamma2", "l", "S1", "S2", "u", "v", "X", "Z", "gates", "c", "h",
+                 "blk", "a", "o"):
+        setattr(tape, name, _ptr(getattr(r, name)))
+    loss = C.c_double(0.0)
+    rc = L_.eso_forward(C.byref(cc), _ptr(y), lengths.ctypes.data_as(C.POINTER(C.c_int32)),
+                        _ptr(es_params), _ptr(weights), C.byref(tape), C.byref(loss),
+                        _ptr(r.forecasts) if want_forecasts else None)
+    if rc != 0:
+        raise ValueError(f"oracle forward failed with code {rc}")
+    r.loss = loss.value
+    r.sum_pin, r.sum_lv, r.n_pin, r.n_lv = tape.sum_pin, tape.sum_lv, tape.n_pin, tape.n_lv
+    r._tape, r._cc = tape, cc
+    r._inputs = (y, lengths, es_params, weights)
+    r.P, r.K, r.n_layers = P, K, nl
+    return r
+
+
+def backward(cfg, fwd, want_adjoints=True):
+    """Reverse mode for the forward result ``fwd``; returns grad_es_params
+    [K,B], grad_weights (flat) and, optionally, the adjoint intermediates."""
+    L_ = lib()
+    y, lengths, es_params, weights = fwd._inputs
+    T, B = y.shape
+    h, I, H, P = cfg.hidden, cfg.I, cfg.H, fwd.P
+    g = SimpleNamespace()
+    g.grad_es_params = np.zeros_like(es_params)
+    g.grad_weights = np.zeros_like(weights)
+    adj = _Adjoint()
+    if want_adjoints:
+        g.gO = np.zeros((B, P, H))
+        g.gR = np.zeros((B, P, h))
+        g.gX = np.zeros((B, P, I))
+        g.gu = np.zeros((B, T))
+        g.gv = np.zeros((B, T))
+        for name in ("gO", "gR", "gX", "gu", "gv"):
+            setattr(adj, name, _ptr(getattr(g, name)))
+    rc = L_.eso_backward(C.byref(fwd._cc), _ptr(y), lengths.ctypes.data_as(C.POINTER(C.c_int32)),
+                         _ptr(es_params), _ptr(weights), C.byref(fwd._tape),
+                         C.byref(adj) if want_adjoints else None,
+                         _ptr(g.grad_es_params), _ptr(g.grad_weights))
+    if rc != 0:
+        raise ValueError(f"oracle backward failed with code {rc}")
+    return g
+
+
+def loss_only(cfg, y, lengths, es_params, weights, **kw) -> float:
+    return forward(cfg, y, lengths, es_params, weights, want_forecasts=False, **kw).loss
