@@ -1,0 +1,162 @@
+/*
+ * esrnn.h - C ABI of the MI355X (gfx950) ES-RNN training-step library.
+ *
+ * One call of esrnn_forward followed by one call of esrnn_backward is one
+ * batched training step of the hybrid exponential-smoothing / recurrent
+ * network model of arXiv 1907.03329 over B series at once:
+ *
+ *   Section 3.1, Eq. (1), (3)   per-series multiplicative smoothing of level
+ *                               and seasonality (no trend, text after Eq. (4)),
+ *                               sequential in time, parallel over series;
+ *                               Section 8.2: two seasonalities, or none
+ *   Section 5.3, Eq. (6)        sliding input / target windows, divided by the
+ *                               level at the window end and by the seasonal
+ *                               factors (natural log of the ratios)
+ *   Section 3.2, Table 1        blocks of dilated LSTM layers with residual
+ *                               connections between blocks
+ *   Section 3.4                 tanh layer and linear layer
+ *   Section 3.5, Section 8.4    pinball loss over unmasked outputs plus a
+ *                               penalty on second differences of the log level
+ *   Eq. (5)                     forecasts = exp(output) * level * seasonality
+ *   Section 3.3                 gradients with respect to the per-series
+ *                               smoothing parameters and the shared weights
+ *
+ * Conventions
+ *   - Every function returns an esrnn_status; 0 is success.  Nothing throws or
+ *     aborts.  Configuration errors are reported before any kernel is launched.
+ *   - All array arguments are DEVICE pointers owned by the caller; the library
+ *     reads inputs and writes only outputs and the workspace.  It allocates no
+ *     device memory.  All work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream); no call synchronises with the host.
+ *   - fp32 throughout.  Series values must be strictly positive inside their
+ *     length; values past the length are ignored.
+ *   - A handle may be used by one thread at a time.  A workspace belongs to one
+ *     forward/backward pair at a time.
+ */
+#ifndef ESRNN_H
+#define ESRNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ESRNN_MAX_BLOCKS 4
+#define ESRNN_MAX_LAYERS_PER_BLOCK 4
+#define ESRNN_MAX_HIDDEN 64
+#define ESRNN_MAX_WINDOW 64   /* limit for both I and H */
+
+typedef enum {
+    ESRNN_OK = 0,
+    ESRNN_ERR_NULL = 1,       /* a required pointer is NULL */
+    ESRNN_ERR_CONFIG = 2,     /* configuration outside the supported range */
+    ESRNN_ERR_WORKSPACE = 3,  /* workspace pointer misaligned (256 bytes required) */
+    ESRNN_ERR_ORDER = 4,      /* esrnn_backward without a preceding esrnn_forward on the handle */
+    ESRNN_ERR_HIP = 5         /* a HIP runtime call or kernel launch failed */
+} esrnn_status;
+
+typedef enum {
+    ESRNN_PARAMS_DIRECT = 0,  /* alpha, gamma in [0,1] and s_init > 0 are given as such; gradients are with respect to them */
+    ESRNN_PARAMS_LOGIT = 1    /* alpha, gamma = sigmoid(theta), s_init = exp(theta); gradients are with respect to theta
+                                 (Section 3.1: smoothing coefficients lie between zero and one) */
+} esrnn_param_space;
+
+typedef struct {
+    int32_t B, T;             /* number of series; padded length (rows of y) */
+    int32_t n_seas, m1, m2;   /* 0: level only; 1: one seasonality of period m1; 2: periods m1 and m2 (Section 8.2) */
+    int32_t I, H;             /* input window and horizon (= output window), Section 3.1 */
+    int32_t hidden;           /* LSTM state size (Table 1) */
+    int32_t n_blocks;         /* 1..ESRNN_MAX_BLOCKS residual blocks */
+    int32_t layers_in_block[ESRNN_MAX_BLOCKS];
+    int32_t dilation[ESRNN_MAX_BLOCKS][ESRNN_MAX_LAYERS_PER_BLOCK];  /* Table 1 */
+    float tau;                /* pinball quantile in (0,1) */
+    float lambda_lv;          /* weight of the level penalty; 0 disables it */
+    int32_t param_space;      /* esrnn_param_space */
+} esrnn_config;
+
+typedef struct esrnn_handle esrnn_handle;
+
+/* Validates the configuration (I + H <= T, periods <= T, dilations >= 1, sizes
+ * within the ESRNN_MAX_* limits, 0 < tau < 1) and builds the launch plan.
+ * Host-only; touches no device. */
+esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out);
+esrnn_status esrnn_destroy(esrnn_handle *h);
+
+/* Sizes the caller needs to allocate buffers. */
+esrnn_status esrnn_workspace_bytes(const esrnn_handle *h, size_t *bytes);
+esrnn_status esrnn_es_param_rows(const esrnn_handle *h, int32_t *K);   /* K = 1 + n_seas + m1 + m2 (Section 3.3) */
+esrnn_status esrnn_weight_count(const esrnn_handle *h, size_t *n);     /* length of the flat weight vector */
+const char *esrnn_status_string(esrnn_status s);
+
+/*
+ * Forward pass: smoothing recursions, windows, network, loss, forecasts.
+ *
+ *   y          [T][B] time-major.  Series b occupies t = 0 .. lengths[b]-1.
+ *   lengths    [B] int32, I + H <= lengths[b] <= T (values outside are clamped).
+ *   es_params  [K][B]; rows in this order, absent ones omitted: alpha, gamma1,
+ *              gamma2, s1_init[0..m1), s2_init[0..m2).
+ *   weights    flat.  Per LSTM layer, in stack order: W [4*hidden][in+hidden]
+ *              row-major, gate rows in the order input, forget, candidate,
+ *              output, columns first the layer input (in = I for the first
+ *              layer, hidden otherwise) then the recurrent state; bias
+ *              [4*hidden].  Then Wa [hidden][hidden], ba [hidden] (tanh layer),
+ *              Wo [H][hidden], bo [H] (linear layer).
+ *   workspace  >= esrnn_workspace_bytes, 256-byte aligned; afterwards holds
+ *              everything esrnn_backward needs.
+ *   loss       one float: mean pinball loss over unmasked outputs + lambda_lv *
+ *              mean squared second difference of the log level.
+ *   forecasts  [P][B][H] with P = T - I - H + 1, original scale, zero where the
+ *              window does not fit into the series; may be NULL.
+ */
+esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengths,
+                           const float *es_params, const float *weights, void *workspace,
+                           float *loss, float *forecasts, void *stream);
+
+/*
+ * Reverse pass for the forward pass last run on this handle with the same
+ * inputs and workspace.  grad_es_params [K][B] and grad_weights (flat, packed
+ * like weights) are overwritten, not accumulated into.
+ */
+esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *lengths,
+                            const float *es_params, const float *weights, void *workspace,
+                            float *grad_es_params, float *grad_weights, void *stream);
+
+/*
+ * Where an intermediate lives inside the workspace, for tests and profiling.
+ * Layout kinds:
+ *   ESRNN_LAYOUT_TIME_MAJOR  [T][Bp], Bp = 16 * ceil(B / 16)
+ *   ESRNN_LAYOUT_TILE        [P][Bp/16][R][16]: element (p, b, r) at
+ *                            ((p * Bp/16 + b/16) * R + r) * 16 + b%16; rows past
+ *                            the logical count are padding
+ *   ESRNN_LAYOUT_GATE_TILE   as TILE with a trailing [4] (activated input,
+ *                            forget, candidate, output gate of hidden unit r)
+ * dims = {T or P, Bp, R (padded rows), logical rows}.
+ */
+typedef enum {
+    ESRNN_BUF_LEVEL = 0, ESRNN_BUF_S1, ESRNN_BUF_S2, ESRNN_BUF_U, ESRNN_BUF_V,   /* time-major */
+    ESRNN_BUF_X, ESRNN_BUF_Z,                                                    /* tile */
+    ESRNN_BUF_GATES,                                                             /* gate tile, index = layer */
+    ESRNN_BUF_C, ESRNN_BUF_HID,                                                  /* tile, index = layer */
+    ESRNN_BUF_BLOCK_OUT,                                                         /* tile, index = block */
+    ESRNN_BUF_A, ESRNN_BUF_O,                                                    /* tile */
+    ESRNN_BUF_GRAD_O, ESRNN_BUF_GRAD_TOP, ESRNN_BUF_GRAD_X,                      /* tile (after backward) */
+    ESRNN_BUF_GRAD_U, ESRNN_BUF_GRAD_V,                                          /* time-major (after backward) */
+    ESRNN_BUF_COUNT_
+} esrnn_buffer;
+
+typedef enum { ESRNN_LAYOUT_TIME_MAJOR = 0, ESRNN_LAYOUT_TILE = 1, ESRNN_LAYOUT_GATE_TILE = 2 } esrnn_layout;
+
+typedef struct {
+    size_t offset_bytes;
+    int32_t layout;
+    int32_t dims[4];
+} esrnn_buffer_view;
+
+esrnn_status esrnn_workspace_buffer(const esrnn_handle *h, int32_t which, int32_t index, esrnn_buffer_view *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

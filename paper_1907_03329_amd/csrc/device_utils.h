@@ -1,0 +1,53 @@
+// Device helpers shared by the kernels: the 16x16x4 fp32 MFMA tile, LDS-only
+// barrier, activation functions, wave reductions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace esrnn {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// D = A(16x4) * B(4x16) + C(16x16), fp32.  Lane l supplies A[l%16][l/16] and
+// B[l/16][l%16]; it holds D[4*(l/16) + r][l%16] in component r.
+__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// Workgroup barrier that orders LDS traffic only: global loads and stores in
+// flight are not waited for.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+__device__ __forceinline__ float sigmoid_f(float x)
+{
+    return fast_rcp(1.0f + __expf(-x));
+}
+
+// tanh(x) = 1 - 2 / (1 + exp(2x)); saturates correctly at both ends.
+__device__ __forceinline__ float tanh_f(float x)
+{
+    return 1.0f - 2.0f * fast_rcp(1.0f + __expf(2.0f * x));
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// sum over the 16 lanes that share lane/16
+__device__ __forceinline__ float group16_sum(float v)
+{
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+}  // namespace esrnn

@@ -1,0 +1,640 @@
+// Streaming kernels of the training step: loss normalisers, operand packing,
+// exponential-smoothing recursions (forward and adjoint), window extraction
+// (forward and adjoint), loss reduction and weight-gradient reduction.
+#include "device_utils.h"
+#include "esrnn_internal.h"
+
+namespace esrnn {
+
+namespace {
+
+__device__ __forceinline__ int clamp_len(int len, int T) { return len < 0 ? 0 : (len > T ? T : len); }
+
+// ---------------------------------------------------------------------------
+// Loss normalisers (Section 3.5: padded outputs are masked out of the loss).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) prep_kernel(const int32_t *__restrict__ lengths, int B, int T, int I, int H,
+                                                    Scalars *__restrict__ sc)
+{
+    __shared__ double s_pin[256], s_lv[256];
+    double np_ = 0.0, nl = 0.0;
+    for (int b = threadIdx.x; b < B; b += 256) {
+        const int len = clamp_len(lengths[b], T);
+        const int Pb = len - I - H + 1;
+        if (Pb > 0) np_ += (double)Pb * H;
+        if (len > 2) nl += (double)(len - 2);
+    }
+    s_pin[threadIdx.x] = np_;
+    s_lv[threadIdx.x] = nl;
+    __syncthreads();
+    for (int off = 128; off >= 1; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            s_pin[threadIdx.x] += s_pin[threadIdx.x + off];
+            s_lv[threadIdx.x] += s_lv[threadIdx.x + off];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        sc->inv_n_pin = s_pin[0] > 0.0 ? (float)(1.0 / s_pin[0]) : 0.0f;
+        sc->inv_n_lv = s_lv[0] > 0.0 ? (float)(1.0 / s_lv[0]) : 0.0f;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Operand packing: weights rearranged into the per-lane operand order of the
+// 16x16x4 MFMA (lane l supplies A[l%16][l/16]) so that every wave loads its
+// register-resident slice with coalesced reads.
+// ---------------------------------------------------------------------------
+struct PackLstmArgs {
+    const float *W, *b;
+    float *fwd, *bias, *bwd;
+    int h, in_dim, HT, KXT;
+};
+
+__global__ void __launch_bounds__(256) pack_lstm_kernel(PackLstmArgs a)
+{
+    const int KT = a.KXT + a.HT, MB = (KT + 3) / 4, ld = a.in_dim + a.h;
+    const int n_fwd = a.HT * KT * 64, n_bias = a.HT * 16, n_bwd = MB * 4 * a.HT * 64;
+    for (int idx = blockIdx.x * 256 + threadIdx.x; idx < n_fwd + n_bias + n_bwd; idx += gridDim.x * 256) {
+        if (idx < n_fwd) {
+            // gate contraction: row 4g+r of unit tile mt is gate r of unit 4mt+g
+            const int lane = idx & 63, ks = (idx >> 6) % KT, mt = (idx >> 6) / KT;
+            const int i = lane & 15, kk = lane >> 4;
+            const int unit = 4 * mt + (i >> 2), gate = i & 3;
+            int col = -1;
+            if (ks < a.KXT) { const int xc = 4 * ks + kk; if (xc < a.in_dim) col = xc; }
+            else { const int hu = 4 * (ks - a.KXT) + kk; if (hu < a.h) col = a.in_dim + hu; }
+            a.fwd[idx] = (unit < a.h && col >= 0) ? a.W[(size_t)(gate * a.h + unit) * ld + col] : 0.0f;
+        } else if (idx < n_fwd + n_bias) {
+            const int j = idx - n_fwd;
+            const int gate = j & 3, unit = j >> 2;   // (mt*4+g)*4 + r  ->  unit = 4mt+g
+            a.bias[j] = unit < a.h ? a.b[gate * a.h + unit] : 0.0f;
+        } else {
+            // transposed contraction: k-step 4mt+gate, lane group = unit within tile;
+            // output row 4g+r of tile mb is row g of input unit tile 4mb+r
+            const int j = idx - n_fwd - n_bias;
+            const int lane = j & 63, ks = (j >> 6) % (4 * a.HT), mb = (j >> 6) / (4 * a.HT);
+            const int i = lane & 15, gk = lane >> 4;
+            const int mt = ks >> 2, gate = ks & 3;
+            const int unit = 4 * mt + gk;
+            const int q = 4 * mb + (i & 3), gi = i >> 2;
+            int col = -1;
+            if (q < a.KXT) { const int xc = 4 * q + gi; if (xc < a.in_dim) col = xc; }
+            else if (q < KT) { const int hu = 4 * (q - a.KXT) + gi; if (hu < a.h) col = a.in_dim + hu; }
+            a.bwd[j] = (unit < a.h && col >= 0) ? a.W[(size_t)(gate * a.h + unit) * ld + col] : 0.0f;
+        }
+    }
+}
+
+struct PackHeadArgs {
+    const float *Wa, *ba, *Wo, *bo;
+    float *WaF, *baF, *WoF, *boF, *WoT, *WaT;
+    int h, H, HT, MA, MO, OT;
+};
+
+__global__ void __launch_bounds__(256) pack_head_kernel(PackHeadArgs a)
+{
+    const int nWaF = a.MA * a.HT * 64, nbaF = a.MA * 16, nWoF = a.MO * a.HT * 64, nboF = a.MO * 16;
+    const int nWoT = a.MA * a.OT * 64, nWaT = a.MA * a.HT * 64;
+    const int total = nWaF + nbaF + nWoF + nboF + nWoT + nWaT;
+    for (int idx = blockIdx.x * 256 + threadIdx.x; idx < total; idx += gridDim.x * 256) {
+        int j = idx;
+        if (j < nWaF) {
+            const int lane = j & 63, q = (j >> 6) % a.HT, ma = (j >> 6) / a.HT;
+            const int i = lane & 15, kk = lane >> 4;
+            const int out = 4 * (4 * ma + (i & 3)) + (i >> 2), in = 4 * q + kk;
+            a.WaF[j] = (out < a.h && in < a.h) ? a.Wa[out * a.h + in] : 0.0f;
+            continue;
+        }
+        j -= nWaF;
+        if (j < nbaF) {
+            const int r = j & 3, g = (j >> 2) & 3, ma = j >> 4;
+            const int unit = 4 * (4 * ma + r) + g;
+            a.baF[j] = unit < a.h ? a.ba[unit] : 0.0f;
+            continue;
+        }
+        j -= nbaF;
+        if (j < nWoF) {
+            const int lane = j & 63, q = (j >> 6) % a.HT, mo = (j >> 6) / a.HT;
+            const int row = 16 * mo + (lane & 15), in = 4 * q + (lane >> 4);
+            a.WoF[j] = (row < a.H && in < a.h) ? a.Wo[row * a.h + in] : 0.0f;
+            continue;
+        }
+        j -= nWoF;
+        if (j < nboF) {
+            const int row = 16 * (j >> 4) + (j & 15);   // 4g + r within the tile
+            a.boF[j] = row < a.H ? a.bo[row] : 0.0f;
+            continue;
+        }
+        j -= nboF;
+        if (j < nWoT) {
+            const int lane = j & 63, ks = (j >> 6) % a.OT, ma = (j >> 6) / a.OT;
+            const int i = lane & 15, kk = lane >> 4;
+            const int unit = 4 * (4 * ma + (i & 3)) + (i >> 2), row = 4 * ks + kk;
+            a.WoT[j] = (unit < a.h && row < a.H) ? a.Wo[row * a.h + unit] : 0.0f;
+            continue;
+        }
+        j -= nWoT;
+        {
+            const int lane = j & 63, q = (j >> 6) % a.HT, ma = (j >> 6) / a.HT;
+            const int i = lane & 15, kk = lane >> 4;
+            const int unit = 4 * (4 * ma + (i & 3)) + (i >> 2), row = 4 * q + kk;
+            a.WaT[j] = (unit < a.h && row < a.h) ? a.Wa[row * a.h + unit] : 0.0f;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Exponential-smoothing recursions, Section 3.1 Eq. (1) and (3) without trend;
+// Section 8.2 variants (two seasonalities, none).  One lane per series, time
+// sequential; every load and store is one contiguous row segment of a
+// time-major array.  The seasonal factors that will apply m steps ahead live
+// in a per-lane ring in LDS (slot t mod m holds the factor for time t until
+// step t has used it, then the factor for time t + m).
+// ---------------------------------------------------------------------------
+struct EsArgs {
+    const float *y;           // [T][B]
+    const int32_t *lengths;
+    const float *es;          // [K][B]
+    float *lvl, *S1, *S2, *u, *v;   // [T][Bp]
+    float *lv_partial;        // [gridDim.x]
+    int B, Bp, T, n_seas, m1, m2, logit;
+    int row_gamma1, row_gamma2, row_s1, row_s2;
+};
+
+__global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
+{
+    extern __shared__ float ring[];   // [m1 + m2][64]
+    const int lane = threadIdx.x;
+    const int b = blockIdx.x * 64 + lane;
+    const bool in_batch = b < a.B;
+    const int len = in_batch ? clamp_len(a.lengths[b], a.T) : 0;
+    float *ring1 = ring, *ring2 = ring + (size_t)a.m1 * 64;
+
+    float alpha = 0.5f, g1 = 0.0f, g2 = 0.0f;
+    if (in_batch) {
+        alpha = a.es[b];
+        if (a.n_seas >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
+        if (a.n_seas >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
+        if (a.logit) {
+            alpha = 1.0f / (1.0f + expf(-alpha));
+            g1 = 1.0f / (1.0f + expf(-g1));
+            g2 = 1.0f / (1.0f + expf(-g2));
+        }
+    }
+    if (a.n_seas >= 1)
+        for (int k = 0; k < a.m1; ++k) {
+            float s = in_batch ? a.es[(size_t)(a.row_s1 + k) * a.B + b] : 1.0f;
+            ring1[k * 64 + lane] = (a.logit && in_batch) ? expf(s) : s;
+        }
+    if (a.n_seas >= 2)
+        for (int k = 0; k < a.m2; ++k) {
+            float s = in_batch ? a.es[(size_t)(a.row_s2 + k) * a.B + b] : 1.0f;
+            ring2[k * 64 + lane] = (a.logit && in_batch) ? expf(s) : s;
+        }
+    const bool store = b < a.Bp;
+    float l_prev = 1.0f, u1 = 0.0f, u2 = 0.0f, lv_sum = 0.0f;
+    int i1 = 0, i2 = 0;
+    const float one_m_alpha = 1.0f - alpha;
+    float y_next = (0 < len) ? a.y[b] : 1.0f;
+    for (int t = 0; t < a.T; ++t) {
+        const bool live = t < len;
+        const float yt = y_next;
+        if (t + 1 < a.T) y_next = (t + 1 < len) ? a.y[(size_t)(t + 1) * a.B + b] : 1.0f;
+        float s1 = 1.0f, s2 = 1.0f;
+        if (a.n_seas >= 1) s1 = ring1[i1 * 64 + lane];
+        if (a.n_seas >= 2) s2 = ring2[i2 * 64 + lane];
+        const float q = yt / (s1 * s2);
+        // reading for the state before the first observation: l_{-1} = y_0 / S[0]
+        const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
+        if (t >= 1) {
+            // Eq. (3): divide by the previous level (and the other factor)
+            if (a.n_seas >= 1) ring1[i1 * 64 + lane] = g1 * (yt / (l_prev * s2)) + (1.0f - g1) * s1;
+            if (a.n_seas >= 2) ring2[i2 * 64 + lane] = g2 * (yt / (l_prev * s1)) + (1.0f - g2) * s2;
+        }
+        const float ut = live ? logf(lt) : 0.0f;
+        const float vt = live ? logf(yt) - logf(s1 * s2) : 0.0f;
+        if (store) {
+            const size_t o = (size_t)t * a.Bp + b;
+            a.lvl[o] = live ? lt : 1.0f;
+            a.u[o] = ut;
+            a.v[o] = vt;
+            if (a.n_seas >= 1) a.S1[o] = live ? s1 : 1.0f;
+            if (a.n_seas >= 2) a.S2[o] = live ? s2 : 1.0f;
+        }
+        // Section 8.4: squared second difference of the log level
+        if (live && t >= 2) {
+            const float e = ut - 2.0f * u1 + u2;
+            lv_sum += e * e;
+        }
+        u2 = u1; u1 = ut;
+        if (live) l_prev = lt;
+        if (a.n_seas >= 1 && ++i1 == a.m1) i1 = 0;
+        if (a.n_seas >= 2 && ++i2 == a.m2) i2 = 0;
+    }
+    const float tot = wave_sum(lv_sum);
+    if (lane == 0) a.lv_partial[blockIdx.x] = tot;
+}
+
+// ---------------------------------------------------------------------------
+// Windows, Section 5.3 and Eq. (6): with u = ln(level), v = ln y - ln(seasonal
+// factors), input x[p][i] = v[p+i] - u[t], target z[p][j] = v[t+j] - u[t],
+// t = p + I - 1.  One wave writes one (p, 16-series) tile; every store
+// instruction covers 4 rows x 16 series = 256 contiguous bytes.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) window_forward_kernel(const float *__restrict__ u, const float *__restrict__ v,
+                                                              float *__restrict__ X, float *__restrict__ Z,
+                                                              int P, int NB, int Bp, int I, int H, int xrows, int zrows)
+{
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 4, n = lane & 15;
+    const long long tile = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= (long long)P * NB) return;
+    const int p = (int)(tile / NB), bt = (int)(tile % NB);
+    const int col = bt * 16 + n;
+    const int t = p + I - 1;
+    const float ut = u[(size_t)t * Bp + col];
+    float *xo = X + (size_t)tile * xrows * 16 + lane;
+    for (int r = g; r < xrows; r += 4) {
+        xo[(r - g) * 16] = (r < I) ? v[(size_t)(p + r) * Bp + col] - ut : 0.0f;
+    }
+    float *zo = Z + (size_t)tile * zrows * 16 + lane;
+    for (int r = g; r < zrows; r += 4) {
+        zo[(r - g) * 16] = (r < H) ? v[(size_t)(t + 1 + r) * Bp + col] - ut : 0.0f;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Loss: sum of the per-workgroup partial sums in double, then
+// loss = pinball_sum / n_pin + lambda * level_sum / n_lv.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) loss_finalize_kernel(const float *__restrict__ partial, int n_pin_parts, int n_lv_parts,
+                                                             const Scalars *__restrict__ sc, float lambda, float *__restrict__ loss)
+{
+    __shared__ double s_a[256], s_b[256];
+    double a = 0.0, b = 0.0;
+    for (int i = threadIdx.x; i < n_pin_parts; i += 256) a += (double)partial[i];
+    for (int i = threadIdx.x; i < n_lv_parts; i += 256) b += (double)partial[n_pin_parts + i];
+    s_a[threadIdx.x] = a;
+    s_b[threadIdx.x] = b;
+    __syncthreads();
+    for (int off = 128; off >= 1; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            s_a[threadIdx.x] += s_a[threadIdx.x + off];
+            s_b[threadIdx.x] += s_b[threadIdx.x + off];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        *loss = (float)(s_a[0] * (double)sc->inv_n_pin + (double)lambda * s_b[0] * (double)sc->inv_n_lv);
+}
+
+// ---------------------------------------------------------------------------
+// Window adjoint in gather form (no atomics): every x and z is v[.] - u[t], so
+//   gv[k] = sum_i gX[k-i][i] + sum_j gZ[k-(I-1)-j][j],  gu[t] = -(sum of row p = t-I+1),
+// with gZ = -gO, plus the gradient of the level penalty (Section 8.4).
+// One thread per (t, series).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) window_backward_kernel(const float *__restrict__ gX, const float *__restrict__ gO,
+                                                               const float *__restrict__ u, const int32_t *__restrict__ lengths,
+                                                               const Scalars *__restrict__ sc, float lambda,
+                                                               float *__restrict__ gu, float *__restrict__ gv,
+                                                               int P, int NB, int B, int Bp, int T, int I, int H, int xrows, int zrows)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)T * Bp) return;
+    const int t = (int)(idx / Bp), col = (int)(idx % Bp);
+    const int bt = col >> 4, n = col & 15;
+    float sv = 0.0f, su = 0.0f;
+    for (int i = 0; i < I; ++i) {
+        const int p = t - i;
+        if (p >= 0 && p < P) sv += gX[((size_t)(p * NB + bt) * xrows + i) * 16 + n];
+    }
+    for (int j = 1; j <= H; ++j) {
+        const int p = t - (I - 1) - j;
+        if (p >= 0 && p < P) sv -= gO[((size_t)(p * NB + bt) * zrows + (j - 1)) * 16 + n];
+    }
+    {
+        const int p = t - I + 1;
+        if (p >= 0 && p < P) {
+            for (int i = 0; i < I; ++i) su -= gX[((size_t)(p * NB + bt) * xrows + i) * 16 + n];
+            for (int j = 0; j < H; ++j) su += gO[((size_t)(p * NB + bt) * zrows + j) * 16 + n];
+        }
+    }
+    if (lambda != 0.0f) {
+        const int len = col < B ? clamp_len(lengths[col], T) : 0;
+        // e[k] = u[k] - 2u[k-1] + u[k-2] for 2 <= k < len; d/du[t] of sum e^2 = 2(e[t] - 2e[t+1] + e[t+2])
+        float acc = 0.0f;
+#pragma unroll
+        for (int dk = 0; dk <= 2; ++dk) {
+            const int k = t + dk;
+            if (k >= 2 && k < len) {
+                const float e = u[(size_t)k * Bp + col] - 2.0f * u[(size_t)(k - 1) * Bp + col] + u[(size_t)(k - 2) * Bp + col];
+                acc += (dk == 1 ? -2.0f : 1.0f) * e;
+            }
+        }
+        su += lambda * 2.0f * sc->inv_n_lv * acc;
+    }
+    gu[idx] = su;
+    gv[idx] = sv;
+}
+
+// ---------------------------------------------------------------------------
+// Adjoint of the smoothing recursions: reverse sweep over time, one lane per
+// series.  Lb is the adjoint of the level; the adjoints of the seasonal factors
+// sit in a per-lane LDS ring (slot t mod m holds the adjoint of the factor for
+// time t + m when step t starts, and that of time t when it ends).
+// ---------------------------------------------------------------------------
+struct EsBwdArgs {
+    const float *y;
+    const int32_t *lengths;
+    const float *es;
+    const float *lvl, *S1, *S2, *gu, *gv;   // [T][Bp]
+    float *grad_es;                          // [K][B]
+    int B, Bp, T, n_seas, m1, m2, logit;
+    int row_gamma1, row_gamma2, row_s1, row_s2;
+};
+
+__global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
+{
+    extern __shared__ float ring[];
+    const int lane = threadIdx.x;
+    const int b = blockIdx.x * 64 + lane;
+    if (b >= a.B) return;   // no barriers in this kernel
+    const int len = clamp_len(a.lengths[b], a.T);
+    float *ring1 = ring, *ring2 = ring + (size_t)a.m1 * 64;
+    float alpha = a.es[b], g1 = 0.0f, g2 = 0.0f;
+    if (a.n_seas >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
+    if (a.n_seas >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
+    if (a.logit) {
+        alpha = 1.0f / (1.0f + expf(-alpha));
+        g1 = 1.0f / (1.0f + expf(-g1));
+        g2 = 1.0f / (1.0f + expf(-g2));
+    }
+    for (int k = 0; k < a.m1; ++k) ring1[k * 64 + lane] = 0.0f;
+    for (int k = 0; k < a.m2; ++k) ring2[k * 64 + lane] = 0.0f;
+    float ab = 0.0f, g1b = 0.0f, g2b = 0.0f;
+    float Lb_carry = 0.0f;      // contributions to the adjoint of l[t] from later steps
+    int i1 = 0, i2 = 0;
+    if (len > 0) {
+        if (a.n_seas >= 1) i1 = (len - 1) % a.m1;
+        if (a.n_seas >= 2) i2 = (len - 1) % a.m2;
+    }
+    for (int t = len - 1; t >= 1; --t) {
+        const size_t o = (size_t)t * a.Bp + b;
+        const float yt = a.y[(size_t)t * a.B + b];
+        const float lt = a.lvl[o], lp = a.lvl[o - a.Bp];
+        const float s1 = a.n_seas >= 1 ? a.S1[o] : 1.0f;
+        const float s2 = a.n_seas >= 2 ? a.S2[o] : 1.0f;
+        const float gvt = a.gv[o];
+        const float Lb = a.gu[o] / lt + Lb_carry;
+        float S1b = a.n_seas >= 1 ? -gvt / s1 : 0.0f;
+        float S2b = a.n_seas >= 2 ? -gvt / s2 : 0.0f;
+        float Lb_prev = 0.0f;
+        if (a.n_seas >= 1) {
+            const float A = (t + a.m1 <= len - 1) ? ring1[i1 * 64 + lane] : 0.0f;
+            const float r = yt / (lp * s2);
+            g1b += A * (r - s1);
+            Lb_prev -= A * g1 * r / lp;
+            S2b -= A * g1 * r / s2;
+            S1b += A * (1.0f - g1);
+        }
+        if (a.n_seas >= 2) {
+            const float A = (t + a.m2 <= len - 1) ? ring2[i2 * 64 + lane] : 0.0f;
+            const float r = yt / (lp * s1);
+            g2b += A * (r - s2);
+            Lb_prev -= A * g2 * r / lp;
+            S1b -= A * g2 * r / s1;
+            S2b += A * (1.0f - g2);
+        }
+        const float q = yt / (s1 * s2);
+        ab += Lb * (q - lp);
+        S1b -= Lb * alpha * q / s1;
+        S2b -= Lb * alpha * q / s2;
+        Lb_prev += Lb * (1.0f - alpha);
+        if (a.n_seas >= 1) { ring1[i1 * 64 + lane] = S1b; if (--i1 < 0) i1 = a.m1 - 1; }
+        if (a.n_seas >= 2) { ring2[i2 * 64 + lane] = S2b; if (--i2 < 0) i2 = a.m2 - 1; }
+        Lb_carry = Lb_prev;
+    }
+    if (len >= 1) {
+        // t = 0: l[0] = y0 / (S1[0] S2[0]); the first produced factors equal the initial ones
+        const size_t o = b;
+        const float l0 = a.lvl[o];
+        const float Lb = a.gu[o] / l0 + Lb_carry;
+        const float gv0 = a.gv[o];
+        if (a.n_seas >= 1) {
+            const float s1 = a.S1[o];
+            const float A = (a.m1 <= len - 1) ? ring1[lane] : 0.0f;
+            ring1[lane] = -gv0 / s1 + A - Lb * l0 / s1;
+        }
+        if (a.n_seas >= 2) {
+            const float s2 = a.S2[o];
+            const float A = (a.m2 <= len - 1) ? ring2[lane] : 0.0f;
+            ring2[lane] = -gv0 / s2 + A - Lb * l0 / s2;
+        }
+    }
+    a.grad_es[b] = a.logit ? ab * alpha * (1.0f - alpha) : ab;
+    if (a.n_seas >= 1) {
+        a.grad_es[(size_t)a.row_gamma1 * a.B + b] = a.logit ? g1b * g1 * (1.0f - g1) : g1b;
+        for (int k = 0; k < a.m1; ++k) {
+            float gs = (k < len) ? ring1[k * 64 + lane] : 0.0f;
+            if (a.logit) gs *= (k < len) ? a.S1[(size_t)k * a.Bp + b] : 0.0f;
+            a.grad_es[(size_t)(a.row_s1 + k) * a.B + b] = gs;
+        }
+    }
+    if (a.n_seas >= 2) {
+        a.grad_es[(size_t)a.row_gamma2 * a.B + b] = a.logit ? g2b * g2 * (1.0f - g2) : g2b;
+        for (int k = 0; k < a.m2; ++k) {
+            float gs = (k < len) ? ring2[k * 64 + lane] : 0.0f;
+            if (a.logit) gs *= (k < len) ? a.S2[(size_t)k * a.Bp + b] : 0.0f;
+            a.grad_es[(size_t)(a.row_s2 + k) * a.B + b] = gs;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Weight-gradient reduction: sums the per-workgroup (LSTM) and per-wave (head)
+// partial tiles in a fixed order and writes the caller's packing.
+// ---------------------------------------------------------------------------
+struct ReduceLstmArgs {
+    const float *dw_partial, *db_partial;
+    float *gW, *gb;
+    int NB, h, in_dim, HT, KXT;
+};
+
+__global__ void __launch_bounds__(256) reduce_lstm_kernel(ReduceLstmArgs a)
+{
+    const int KT = a.KXT + a.HT, MB = (KT + 3) / 4, ld = a.in_dim + a.h;
+    const int nW = 4 * a.h * ld, nb = 4 * a.h;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx < nW) {
+        const int row = idx / ld, col = idx % ld;
+        const int gate = row / a.h, unit = row % a.h;
+        const int mt = unit >> 2, g = unit & 3;
+        const int xr = col < a.in_dim ? col : 4 * a.KXT + (col - a.in_dim);
+        const int nbk = xr >> 4, c = xr & 15;
+        // tile (mt, nbk): row 4*gate + g  ->  lane group = gate, component = g; column c
+        const size_t stride = (size_t)a.HT * MB * 256;
+        const float *src = a.dw_partial + ((size_t)(mt * MB + nbk) * 4 + g) * 64 + gate * 16 + c;
+        double s = 0.0;
+        for (int w = 0; w < a.NB; ++w) s += (double)src[w * stride];
+        a.gW[idx] = (float)s;
+    } else if (idx < nW + nb) {
+        const int j = idx - nW;
+        const int gate = j / a.h, unit = j % a.h;
+        const size_t stride = (size_t)a.HT * 16;
+        const float *src = a.db_partial + unit * 4 + gate;
+        double s = 0.0;
+        for (int w = 0; w < a.NB; ++w) s += (double)src[w * stride];
+        a.gb[j] = (float)s;
+    }
+}
+
+struct ReduceHeadArgs {
+    const float *partial;
+    float *gWa, *gba, *gWo, *gbo;
+    int n_waves, stride, h, H, HT, MA, MO, OT;
+};
+
+__global__ void __launch_bounds__(256) reduce_head_kernel(ReduceHeadArgs a)
+{
+    const int nWa = a.h * a.h, nba = a.h, nWo = a.H * a.h, nbo = a.H;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nWa + nba + nWo + nbo) return;
+    // partial block of one wave: dWo tiles [MO*MA][4][64], dWa tiles [MA*MA][4][64], dbo [4*OT], dba [4*HT]
+    const int offWa = a.MO * a.MA * 256, offbo = offWa + a.MA * a.MA * 256, offba = offbo + 4 * a.OT;
+    int src_off;
+    float *dst;
+    if (idx < nWa) {
+        const int row = idx / a.h, col = idx % a.h;       // dWa[row][col] = sum dpre[row] * r[col]
+        const int mt = row >> 4, i = row & 15, nt = col >> 4, c = col & 15;
+        src_off = offWa + ((mt * a.MA + nt) * 4 + (i & 3)) * 64 + (i >> 2) * 16 + c;
+        dst = a.gWa + idx;
+    } else if (idx < nWa + nba) {
+        const int j = idx - nWa;
+        src_off = offba + j;
+        dst = a.gba + j;
+    } else if (idx < nWa + nba + nWo) {
+        const int j = idx - nWa - nba;
+        const int row = j / a.h, col = j % a.h;           // dWo[row][col] = sum gO[row] * a[col]
+        const int mt = row >> 4, i = row & 15, nt = col >> 4, c = col & 15;
+        src_off = ((mt * a.MA + nt) * 4 + (i & 3)) * 64 + (i >> 2) * 16 + c;
+        dst = a.gWo + j;
+    } else {
+        const int j = idx - nWa - nba - nWo;
+        src_off = offbo + j;
+        dst = a.gbo + j;
+    }
+    double s = 0.0;
+    for (int w = 0; w < a.n_waves; ++w) s += (double)a.partial[(size_t)w * a.stride + src_off];
+    *dst = (float)s;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+hipError_t launch_prep(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st)
+{
+    prep_kernel<<<1, 256, 0, st>>>(lengths, pl.B, pl.T, pl.I, pl.H, reinterpret_cast<Scalars *>(ws + pl.scalars));
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_weights(const Plan &pl, const float *weights, float *ws, hipStream_t st)
+{
+    for (int l = 0; l < pl.L; ++l) {
+        const LayerPlan &lp = pl.layer[l];
+        PackLstmArgs a{weights + lp.w_off, weights + lp.b_off, ws + lp.wpack_fwd, ws + lp.bias_pack, ws + lp.wpack_bwd,
+                       pl.h, lp.in_dim, pl.HT, lp.KXT};
+        const int KT = lp.KXT + pl.HT, MB = (KT + 3) / 4;
+        const int total = pl.HT * KT * 64 + pl.HT * 16 + MB * 4 * pl.HT * 64;
+        pack_lstm_kernel<<<(total + 255) / 256, 256, 0, st>>>(a);
+    }
+    const HeadPack hp = head_pack_layout(pl);
+    float *f = ws + pl.head_fwd_pack, *b = ws + pl.head_bwd_pack;
+    PackHeadArgs a{weights + pl.Wa_off, weights + pl.ba_off, weights + pl.Wo_off, weights + pl.bo_off,
+                   f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, b + hp.WoT, b + hp.WaT,
+                   pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
+    const int total = pl.MA * pl.HT * 64 * 2 + pl.MA * 16 + pl.MO * pl.HT * 64 + pl.MO * 16 + pl.MA * pl.OT * 64;
+    pack_head_kernel<<<(total + 255) / 256, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *lengths, const float *es, float *ws,
+                             hipStream_t st)
+{
+    const esrnn_config &c = pl.cfg;
+    EsArgs a{y, lengths, es, ws + pl.lvl, ws + pl.S1, ws + pl.S2, ws + pl.u, ws + pl.v,
+             ws + pl.loss_partial + (pl.n_loss_partial - pl.es_blocks),
+             pl.B, pl.Bp, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
+             c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
+    const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(es_forward_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    es_forward_kernel<<<pl.es_blocks, 64, lds, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st)
+{
+    const long long tiles = (long long)pl.P * pl.NB;
+    window_forward_kernel<<<(unsigned)((tiles + 3) / 4), 256, 0, st>>>(ws + pl.u, ws + pl.v, ws + pl.X, ws + pl.Z,
+                                                                      pl.P, pl.NB, pl.Bp, pl.I, pl.H, 4 * pl.IT, pl.OP);
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStream_t st)
+{
+    loss_finalize_kernel<<<1, 256, 0, st>>>(ws + pl.loss_partial, pl.n_loss_partial - pl.es_blocks, pl.es_blocks,
+                                            reinterpret_cast<const Scalars *>(ws + pl.scalars), pl.cfg.lambda_lv, loss);
+    return hipGetLastError();
+}
+
+hipError_t launch_window_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st)
+{
+    const long long n = (long long)pl.T * pl.Bp;
+    window_backward_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+        ws + pl.gX, ws + pl.gO, ws + pl.u, lengths, reinterpret_cast<const Scalars *>(ws + pl.scalars), pl.cfg.lambda_lv,
+        ws + pl.gu, ws + pl.gv, pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, 4 * pl.IT, pl.OP);
+    return hipGetLastError();
+}
+
+hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *lengths, const float *es, float *ws,
+                              float *grad_es, hipStream_t st)
+{
+    const esrnn_config &c = pl.cfg;
+    EsBwdArgs a{y, lengths, es, ws + pl.lvl, ws + pl.S1, ws + pl.S2, ws + pl.gu, ws + pl.gv, grad_es,
+                pl.B, pl.Bp, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
+                c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
+    const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(es_backward_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    es_backward_kernel<<<(pl.B + 63) / 64, 64, lds, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_weights, hipStream_t st)
+{
+    for (int l = 0; l < pl.L; ++l) {
+        const LayerPlan &lp = pl.layer[l];
+        ReduceLstmArgs a{ws + lp.dw_partial, ws + lp.db_partial, grad_weights + lp.w_off, grad_weights + lp.b_off,
+                         pl.NB, pl.h, lp.in_dim, pl.HT, lp.KXT};
+        const int total = 4 * pl.h * (lp.in_dim + pl.h) + 4 * pl.h;
+        reduce_lstm_kernel<<<(total + 255) / 256, 256, 0, st>>>(a);
+    }
+    ReduceHeadArgs a{ws + pl.head_dw_partial, grad_weights + pl.Wa_off, grad_weights + pl.ba_off,
+                     grad_weights + pl.Wo_off, grad_weights + pl.bo_off,
+                     pl.n_head_waves, pl.head_dw_stride, pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
+    const int total = pl.h * pl.h + pl.h + pl.H * pl.h + pl.H;
+    reduce_head_kernel<<<(total + 255) / 256, 256, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace esrnn

@@ -1,0 +1,165 @@
+// C ABI of the ES-RNN library (include/esrnn.h): handle management, argument
+// checks and the order in which the kernels of one training step are enqueued.
+#include <new>
+
+#include "esrnn_internal.h"
+
+using namespace esrnn;
+
+struct esrnn_handle {
+    Plan plan;
+    bool forward_done;
+};
+
+#define ESRNN_TRY(expr)                              \
+    do {                                             \
+        hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) return ESRNN_ERR_HIP;  \
+    } while (0)
+
+extern "C" {
+
+esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
+{
+    if (!cfg || !out) return ESRNN_ERR_NULL;
+    *out = nullptr;
+    esrnn_handle *h = new (std::nothrow) esrnn_handle;
+    if (!h) return ESRNN_ERR_HIP;
+    esrnn_status st = build_plan(*cfg, h->plan);
+    if (st != ESRNN_OK) {
+        delete h;
+        return st;
+    }
+    h->forward_done = false;
+    *out = h;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_destroy(esrnn_handle *h)
+{
+    if (!h) return ESRNN_ERR_NULL;
+    delete h;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_workspace_bytes(const esrnn_handle *h, size_t *bytes)
+{
+    if (!h || !bytes) return ESRNN_ERR_NULL;
+    *bytes = h->plan.total_floats * sizeof(float);
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_es_param_rows(const esrnn_handle *h, int32_t *K)
+{
+    if (!h || !K) return ESRNN_ERR_NULL;
+    *K = h->plan.K;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_weight_count(const esrnn_handle *h, size_t *n)
+{
+    if (!h || !n) return ESRNN_ERR_NULL;
+    *n = h->plan.n_weights;
+    return ESRNN_OK;
+}
+
+const char *esrnn_status_string(esrnn_status s)
+{
+    switch (s) {
+    case ESRNN_OK: return "ok";
+    case ESRNN_ERR_NULL: return "null pointer argument";
+    case ESRNN_ERR_CONFIG: return "unsupported configuration";
+    case ESRNN_ERR_WORKSPACE: return "workspace pointer not 256-byte aligned";
+    case ESRNN_ERR_ORDER: return "backward called without a preceding forward";
+    case ESRNN_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengths,
+                           const float *es_params, const float *weights, void *workspace,
+                           float *loss, float *forecasts, void *stream)
+{
+    if (!h || !y || !lengths || !es_params || !weights || !workspace || !loss) return ESRNN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
+    const Plan &pl = h->plan;
+    float *ws = static_cast<float *>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    h->forward_done = false;
+    ESRNN_TRY(launch_prep(pl, lengths, ws, st));
+    ESRNN_TRY(launch_pack_weights(pl, weights, ws, st));
+    ESRNN_TRY(launch_es_forward(pl, y, lengths, es_params, ws, st));
+    ESRNN_TRY(launch_window_forward(pl, ws, st));
+    for (int l = 0; l < pl.L; ++l) ESRNN_TRY(launch_lstm_forward(pl, l, ws, st));
+    ESRNN_TRY(launch_head_forward(pl, lengths, ws, forecasts, st));
+    ESRNN_TRY(launch_loss_finalize(pl, ws, loss, st));
+    h->forward_done = true;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *lengths,
+                            const float *es_params, const float *weights, void *workspace,
+                            float *grad_es_params, float *grad_weights, void *stream)
+{
+    if (!h || !y || !lengths || !es_params || !weights || !workspace || !grad_es_params || !grad_weights)
+        return ESRNN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
+    if (!h->forward_done) return ESRNN_ERR_ORDER;
+    const Plan &pl = h->plan;
+    float *ws = static_cast<float *>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ESRNN_TRY(launch_head_backward(pl, lengths, ws, st));
+    for (int l = pl.L - 1; l >= 0; --l) ESRNN_TRY(launch_lstm_backward(pl, l, ws, st));
+    ESRNN_TRY(launch_window_backward(pl, lengths, ws, st));
+    ESRNN_TRY(launch_es_backward(pl, y, lengths, es_params, ws, grad_es_params, st));
+    ESRNN_TRY(launch_reduce_weight_grads(pl, ws, grad_weights, st));
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_workspace_buffer(const esrnn_handle *h, int32_t which, int32_t index, esrnn_buffer_view *out)
+{
+    if (!h || !out) return ESRNN_ERR_NULL;
+    const Plan &pl = h->plan;
+    size_t off = 0;
+    int layout = ESRNN_LAYOUT_TILE, rows = 0, logical = 0, lead = pl.P;
+    auto layer_ok = [&](int i) { return i >= 0 && i < pl.L; };
+    switch (which) {
+    case ESRNN_BUF_LEVEL: off = pl.lvl; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
+    case ESRNN_BUF_S1: off = pl.S1; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
+    case ESRNN_BUF_S2: off = pl.S2; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
+    case ESRNN_BUF_U: off = pl.u; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
+    case ESRNN_BUF_V: off = pl.v; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
+    case ESRNN_BUF_GRAD_U: off = pl.gu; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
+    case ESRNN_BUF_GRAD_V: off = pl.gv; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
+    case ESRNN_BUF_X: off = pl.X; rows = 4 * pl.IT; logical = pl.I; break;
+    case ESRNN_BUF_GRAD_X: off = pl.gX; rows = 4 * pl.IT; logical = pl.I; break;
+    case ESRNN_BUF_Z: off = pl.Z; rows = pl.OP; logical = pl.H; break;
+    case ESRNN_BUF_O: off = pl.O; rows = pl.OP; logical = pl.H; break;
+    case ESRNN_BUF_GRAD_O: off = pl.gO; rows = pl.OP; logical = pl.H; break;
+    case ESRNN_BUF_A: off = pl.A; rows = pl.HP; logical = pl.h; break;
+    case ESRNN_BUF_GRAD_TOP: off = pl.gTop; rows = pl.HP; logical = pl.h; break;
+    case ESRNN_BUF_GATES:
+        if (!layer_ok(index)) return ESRNN_ERR_CONFIG;
+        off = pl.layer[index].gates; layout = ESRNN_LAYOUT_GATE_TILE; rows = pl.HP; logical = pl.h; break;
+    case ESRNN_BUF_C:
+        if (!layer_ok(index)) return ESRNN_ERR_CONFIG;
+        off = pl.layer[index].c; rows = pl.HP; logical = pl.h; break;
+    case ESRNN_BUF_HID:
+        if (!layer_ok(index)) return ESRNN_ERR_CONFIG;
+        off = pl.layer[index].hid; rows = pl.HP; logical = pl.h; break;
+    case ESRNN_BUF_BLOCK_OUT:
+        if (index < 0 || index >= pl.cfg.n_blocks) return ESRNN_ERR_CONFIG;
+        off = pl.blk_out[index]; rows = pl.HP; logical = pl.h; break;
+    default: return ESRNN_ERR_CONFIG;
+    }
+    if (layout == ESRNN_LAYOUT_TIME_MAJOR) { lead = pl.T; rows = 1; logical = 1; }
+    out->offset_bytes = off * sizeof(float);
+    out->layout = layout;
+    out->dims[0] = lead;
+    out->dims[1] = pl.Bp;
+    out->dims[2] = rows;
+    out->dims[3] = logical;
+    return ESRNN_OK;
+}
+
+}  // extern "C"

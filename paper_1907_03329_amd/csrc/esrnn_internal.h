@@ -1,0 +1,110 @@
+// Internal declarations of the ES-RNN HIP library: launch plan, workspace map
+// and kernel launchers.  Not part of the public ABI (see include/esrnn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "esrnn.h"
+
+namespace esrnn {
+
+constexpr int kTileN = 16;       // series per tile (N of the 16x16x4 fp32 MFMA)
+constexpr int kMaxLayers = ESRNN_MAX_BLOCKS * ESRNN_MAX_LAYERS_PER_BLOCK;
+constexpr int kLstmWaves = 4;    // waves per workgroup in the LSTM kernels
+constexpr int kLdsPad = 17;      // row stride of LDS arrays that are read transposed
+
+// Tile layout TL(R): [P][NB][R][16]; element (p, b, r) at ((p*NB + b/16)*R + r)*16 + b%16.
+// A "unit tile" is 4 consecutive rows (64 floats = one float per lane).
+
+struct LayerPlan {
+    int dil, block, first_in_block, last_in_block;
+    int in_dim;          // logical width of the layer input
+    int KXT;             // unit tiles of the layer input (x part of the contraction)
+    size_t w_off, b_off; // offsets into the caller's flat weight vector
+    // forward operands (offsets in floats into the workspace)
+    size_t wpack_fwd;    // [HT][KXT+HT][64]  A operands of the gate contraction
+    size_t bias_pack;    // [HT][4][4]        bias of (unit tile, unit, gate)
+    size_t xsrc;         // TL(4*KXT) input
+    size_t gates, c, hid;
+    size_t resid, out;   // out = resid + hid for the last layer of a block >= 1 (0 = none)
+    // backward operands
+    size_t wpack_bwd;    // [MB][4*HT][64]    A operands of the transposed contraction
+    size_t gsrc;         // TL(HP) gradient arriving at this layer's hidden output
+    size_t gdst;         // TL(4*KXT) gradient with respect to the layer input
+    size_t gadd;         // TL(HP) added to gdst (residual path), 0 = none
+    size_t dhr, dcr;     // TL(HP) recurrent gradients for dilation >= 2
+    size_t dw_partial;   // [NB][HT*MB][4][64] per-workgroup weight-gradient tiles
+    size_t db_partial;   // [NB][HT][4][4]
+};
+
+struct Plan {
+    esrnn_config cfg;
+    int B, T, I, H, h, P;
+    int NB, Bp;          // series tiles, padded batch
+    int HT, HP;          // hidden unit tiles, padded hidden (4*HT)
+    int IT;              // unit tiles of the input window as used by layer 0
+    int OT, MO, OP;      // horizon: unit tiles, 16-row tiles, padded rows (16*MO)
+    int MA;              // 16-row tiles of the hidden dimension in "unit-tile" order: ceil(HT/4)
+    int L;
+    int K;               // rows of es_params
+    int row_gamma1, row_gamma2, row_s1, row_s2;
+    LayerPlan layer[kMaxLayers];
+    size_t Wa_off, ba_off, Wo_off, bo_off, n_weights;
+    // workspace map (offsets in floats)
+    size_t scalars;      // float[16]: see Scalars
+    size_t lvl, S1, S2, u, v, gu, gv;   // [T][Bp]
+    size_t X, Z;         // TL(4*IT), TL(OP)
+    size_t blk_out[ESRNN_MAX_BLOCKS];
+    size_t A, O, gO, gTop, gX;
+    size_t gblk[ESRNN_MAX_BLOCKS];      // gradient with respect to each block output
+    size_t dx[kMaxLayers];
+    size_t head_fwd_pack, head_bwd_pack; // packed head operands
+    size_t loss_partial; int n_loss_partial;   // double-aligned: [n][2] floats (pinball, level)
+    size_t head_dw_partial; int n_head_waves;  // [n_head_waves][head_dw_stride]
+    int head_dw_stride;
+    int es_blocks;
+    size_t total_floats;
+};
+
+// device-side scalars computed from lengths
+struct Scalars {
+    float inv_n_pin;   // 1 / number of unmasked head outputs
+    float inv_n_lv;    // 1 / number of second differences of the log level (0 if none)
+};
+
+// offsets inside the packed head operand blocks (floats), filled by plan.cpp
+struct HeadPack {
+    // forward: Wa as A operand in unit-tile order [MA][HT][64], ba [MA][4][4],
+    //          Wo as A operand, rows in natural order [MO][HT][64], bo [MO][4][4]
+    size_t WaF, baF, WoF, boF, fwd_total;
+    // backward: Wo^T [MA][OT][64], Wa^T [MA][HT][64]
+    size_t WoT, WaT, bwd_total;
+};
+HeadPack head_pack_layout(const Plan &pl);
+
+esrnn_status build_plan(const esrnn_config &cfg, Plan &pl);
+
+// ---- kernel launchers (each returns hipGetLastError()) -----------------------------------
+hipError_t launch_prep(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
+hipError_t launch_pack_weights(const Plan &pl, const float *weights, float *ws, hipStream_t st);
+hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,
+                             float *ws, hipStream_t st);
+hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st);
+hipError_t launch_lstm_forward(const Plan &pl, int layer, float *ws, hipStream_t st);
+hipError_t launch_head_forward(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts,
+                               hipStream_t st);
+hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStream_t st);
+
+hipError_t launch_head_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
+hipError_t launch_lstm_backward(const Plan &pl, int layer, float *ws, hipStream_t st);
+hipError_t launch_window_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
+hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,
+                              float *ws, float *grad_es, hipStream_t st);
+hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_weights, hipStream_t st);
+
+// Supported (HT, KXT) instantiations of the LSTM kernels.
+bool lstm_shape_supported(int HT, int KXT);
+
+}  // namespace esrnn

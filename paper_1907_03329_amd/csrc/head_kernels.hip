@@ -1,0 +1,331 @@
+// Output stage of the network (Section 3.4: tanh layer, then linear layer), the
+// pinball loss over unmasked outputs (Section 3.5), the forecasts of Eq. (5),
+// and the reverse pass of all three.  Every (window position, 16-series) tile is
+// independent: one wave processes one tile at a time with both weight matrices
+// as register-resident A operands of the 16x16x4 fp32 MFMA.
+//
+// Row orders.  "Unit-tile order" of a 16-row output tile ma: row 4g+r is hidden
+// unit 4(4ma+r)+g, so that component r of lane (g, n) is unit tile 4ma+r in the
+// one-float-per-lane layout and can be fed back as the B operand of k-step
+// 4ma+r.  The linear layer's output rows are in natural order.
+#include "device_utils.h"
+#include "esrnn_internal.h"
+
+namespace esrnn {
+
+namespace {
+
+struct HeadFwdArgs {
+    const float *WaF, *baF, *WoF, *boF;
+    const float *R;         // TL(HP) top block output
+    const float *Z;         // TL(OP)
+    const float *u, *S1, *S2;   // [T][Bp]
+    const int32_t *lengths;
+    float *A, *O;           // TL(HP), TL(OP)
+    float *forecasts;       // [P][B][H] or null
+    float *loss_partial;    // [gridDim.x]
+    int P, NB, B, Bp, T, I, H, n_seas;
+    float tau;
+};
+
+template <int HT, int MO>
+__global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
+{
+    constexpr int MA = (HT + 3) / 4;
+    constexpr int OP = 16 * MO;
+    __shared__ float s_part[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int g = lane >> 4, n = lane & 15;
+
+    float wa[MA][HT], wo[MO][HT];
+    f32x4 ba[MA], bo[MO];
+#pragma unroll
+    for (int ma = 0; ma < MA; ++ma) {
+#pragma unroll
+        for (int q = 0; q < HT; ++q) wa[ma][q] = a.WaF[(ma * HT + q) * 64 + lane];
+        const float4 v = *reinterpret_cast<const float4 *>(a.baF + (ma * 4 + g) * 4);
+        ba[ma] = f32x4{v.x, v.y, v.z, v.w};
+    }
+#pragma unroll
+    for (int mo = 0; mo < MO; ++mo) {
+#pragma unroll
+        for (int q = 0; q < HT; ++q) wo[mo][q] = a.WoF[(mo * HT + q) * 64 + lane];
+        const float4 v = *reinterpret_cast<const float4 *>(a.boF + (mo * 4 + g) * 4);
+        bo[mo] = f32x4{v.x, v.y, v.z, v.w};
+    }
+
+    float loss = 0.0f;
+    const long long n_tiles = (long long)a.P * a.NB;
+    for (long long tile = (long long)blockIdx.x * 4 + wv; tile < n_tiles; tile += (long long)gridDim.x * 4) {
+        const int p = (int)(tile / a.NB), bt = (int)(tile % a.NB);
+        const int b = bt * 16 + n;
+        int len = 0;
+        if (b < a.B) { len = a.lengths[b]; len = len < 0 ? 0 : (len > a.T ? a.T : len); }
+        const bool valid = p < len - a.I - a.H + 1;
+
+        float br[HT];
+#pragma unroll
+        for (int q = 0; q < HT; ++q) br[q] = a.R[(size_t)tile * HT * 64 + q * 64 + lane];
+        f32x4 acc[MA];
+#pragma unroll
+        for (int ma = 0; ma < MA; ++ma) acc[ma] = ba[ma];
+#pragma unroll
+        for (int q = 0; q < HT; ++q)
+#pragma unroll
+            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(wa[ma][q], br[q], acc[ma]);
+        float av[4 * MA];
+#pragma unroll
+        for (int ma = 0; ma < MA; ++ma)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int q = 4 * ma + r;
+                av[q] = tanh_f(acc[ma][r]);
+                if (q < HT) a.A[(size_t)tile * HT * 64 + q * 64 + lane] = av[q];
+            }
+        f32x4 oc[MO];
+#pragma unroll
+        for (int mo = 0; mo < MO; ++mo) oc[mo] = bo[mo];
+#pragma unroll
+        for (int q = 0; q < HT; ++q)
+#pragma unroll
+            for (int mo = 0; mo < MO; ++mo) oc[mo] = mfma16(wo[mo][q], av[q], oc[mo]);
+
+        const int t = p + a.I - 1;
+        const float ut = a.u[(size_t)t * a.Bp + b];
+#pragma unroll
+        for (int mo = 0; mo < MO; ++mo)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = 16 * mo + 4 * g + r;      // 0-based step of the horizon
+                const size_t e = ((size_t)tile * OP + j) * 16 + n;
+                const float o = oc[mo][r];
+                a.O[e] = o;
+                if (j < a.H) {
+                    if (valid) {
+                        const float d = a.Z[e] - o;
+                        loss += d >= 0.0f ? a.tau * d : (a.tau - 1.0f) * d;
+                    }
+                    if (a.forecasts && b < a.B) {
+                        float f = 0.0f;
+                        if (valid) {
+                            // Eq. (5): exp(output) * level * seasonal factors of the target time
+                            const size_t ts = (size_t)(t + 1 + j) * a.Bp + b;
+                            float seas = 1.0f;
+                            if (a.n_seas >= 1) seas = a.S1[ts];
+                            if (a.n_seas >= 2) seas *= a.S2[ts];
+                            f = expf(o + ut) * seas;
+                        }
+                        a.forecasts[((size_t)p * a.B + b) * a.H + j] = f;
+                    }
+                }
+            }
+    }
+    const float tot = wave_sum(loss);
+    if (lane == 0) s_part[wv] = tot;
+    __syncthreads();
+    if (threadIdx.x == 0) a.loss_partial[blockIdx.x] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+}
+
+struct HeadBwdArgs {
+    const float *WoT, *WaT;
+    const float *R, *A, *O, *Z;
+    const int32_t *lengths;
+    const Scalars *sc;
+    float *gO;              // TL(OP): dL/d(output); the target's gradient is its negative
+    float *gTop;            // TL(HP): dL/d(top block output)
+    float *partial;         // [n_waves][stride]
+    int P, NB, B, T, I, H, stride;
+    float tau;
+};
+
+template <int HT, int MO>
+__global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
+{
+    constexpr int MA = (HT + 3) / 4;
+    constexpr int OP = 16 * MO;
+    constexpr int OTMAX = 4 * MO;                 // k-steps that cover OP rows
+    constexpr int HP16 = 16 * MA;                 // hidden rows padded to whole 16-row tiles
+    // per-wave staging for the transposed operand reads of the weight-gradient tiles
+    __shared__ float s_go[4][OP * kLdsPad];
+    __shared__ float s_a[4][HP16 * kLdsPad];
+    __shared__ float s_dp[4][HP16 * kLdsPad];
+    __shared__ float s_r[4][HP16 * kLdsPad];
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int g = lane >> 4, n = lane & 15;
+    const int OT = (a.H + 3) / 4;
+    float *go_l = s_go[wv], *a_l = s_a[wv], *dp_l = s_dp[wv], *r_l = s_r[wv];
+    for (int i = lane; i < OP * kLdsPad; i += 64) go_l[i] = 0.0f;
+    for (int i = lane; i < HP16 * kLdsPad; i += 64) { a_l[i] = 0.0f; dp_l[i] = 0.0f; r_l[i] = 0.0f; }
+
+    float woT[MA][OTMAX], waT[MA][HT];
+#pragma unroll
+    for (int ma = 0; ma < MA; ++ma) {
+#pragma unroll
+        for (int ks = 0; ks < OTMAX; ++ks) woT[ma][ks] = ks < OT ? a.WoT[(ma * OT + ks) * 64 + lane] : 0.0f;
+#pragma unroll
+        for (int q = 0; q < HT; ++q) waT[ma][q] = a.WaT[(ma * HT + q) * 64 + lane];
+    }
+    f32x4 dWo[MO * MA], dWa[MA * MA];
+#pragma unroll
+    for (int i = 0; i < MO * MA; ++i) dWo[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < MA * MA; ++i) dWa[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float dbo[OTMAX], dba[4 * MA];
+#pragma unroll
+    for (int i = 0; i < OTMAX; ++i) dbo[i] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4 * MA; ++i) dba[i] = 0.0f;
+
+    const float inv_n = a.sc->inv_n_pin;
+    const long long n_tiles = (long long)a.P * a.NB;
+    for (long long tile = (long long)blockIdx.x * 4 + wv; tile < n_tiles; tile += (long long)gridDim.x * 4) {
+        const int p = (int)(tile / a.NB), bt = (int)(tile % a.NB);
+        const int b = bt * 16 + n;
+        int len = 0;
+        if (b < a.B) { len = a.lengths[b]; len = len < 0 ? 0 : (len > a.T ? a.T : len); }
+        const bool valid = p < len - a.I - a.H + 1;
+
+        // gradient of the pinball loss, one row (horizon step) per k-step lane group
+        float go[OTMAX];
+#pragma unroll
+        for (int ks = 0; ks < OTMAX; ++ks) {
+            const int j = 4 * ks + g;
+            const size_t e = ((size_t)tile * OP + j) * 16 + n;
+            float val = 0.0f;
+            if (valid && j < a.H) {
+                const float d = a.Z[e] - a.O[e];
+                val = (d >= 0.0f ? -a.tau : 1.0f - a.tau) * inv_n;
+            }
+            go[ks] = val;
+            a.gO[e] = val;
+            go_l[j * kLdsPad + n] = val;
+            dbo[ks] += val;
+        }
+        // dA = Wo^T gO (unit-tile order), through the tanh
+        f32x4 acc[MA];
+#pragma unroll
+        for (int ma = 0; ma < MA; ++ma) acc[ma] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < OTMAX; ++ks)
+#pragma unroll
+            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(woT[ma][ks], go[ks], acc[ma]);
+        float dp[4 * MA];
+#pragma unroll
+        for (int ma = 0; ma < MA; ++ma)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int q = 4 * ma + r;
+                float av = 0.0f, rv = 0.0f;
+                if (q < HT) {
+                    av = a.A[(size_t)tile * HT * 64 + q * 64 + lane];
+                    rv = a.R[(size_t)tile * HT * 64 + q * 64 + lane];
+                }
+                dp[q] = acc[ma][r] * (1.0f - av * av);
+                dba[q] += dp[q];
+                const int row = 4 * q + g;
+                a_l[row * kLdsPad + n] = av;
+                dp_l[row * kLdsPad + n] = dp[q];
+                r_l[row * kLdsPad + n] = rv;
+            }
+        // dR = Wa^T dpre
+#pragma unroll
+        for (int ma = 0; ma < MA; ++ma) acc[ma] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < HT; ++q)
+#pragma unroll
+            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(waT[ma][q], dp[q], acc[ma]);
+#pragma unroll
+        for (int ma = 0; ma < MA; ++ma)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int q = 4 * ma + r;
+                if (q < HT) a.gTop[(size_t)tile * HT * 64 + q * 64 + lane] = acc[ma][r];
+            }
+        // weight gradients: contraction over the 16 series of the tile
+#pragma unroll
+        for (int mo = 0; mo < MO; ++mo)
+#pragma unroll
+            for (int na = 0; na < MA; ++na)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    dWo[mo * MA + na] = mfma16(go_l[(16 * mo + n) * kLdsPad + 4 * ks + g],
+                                               a_l[(16 * na + n) * kLdsPad + 4 * ks + g], dWo[mo * MA + na]);
+#pragma unroll
+        for (int ma = 0; ma < MA; ++ma)
+#pragma unroll
+            for (int na = 0; na < MA; ++na)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    dWa[ma * MA + na] = mfma16(dp_l[(16 * ma + n) * kLdsPad + 4 * ks + g],
+                                               r_l[(16 * na + n) * kLdsPad + 4 * ks + g], dWa[ma * MA + na]);
+    }
+
+    // per-wave partial block: dWo tiles, dWa tiles, dbo, dba
+    float *dst = a.partial + (size_t)(blockIdx.x * 4 + wv) * a.stride;
+#pragma unroll
+    for (int i = 0; i < MO * MA; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dst[(i * 4 + r) * 64 + lane] = dWo[i][r];
+    dst += MO * MA * 256;
+#pragma unroll
+    for (int i = 0; i < MA * MA; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dst[(i * 4 + r) * 64 + lane] = dWa[i][r];
+    dst += MA * MA * 256;
+#pragma unroll
+    for (int ks = 0; ks < OTMAX; ++ks) {
+        const float tot = group16_sum(dbo[ks]);
+        if (n == 0 && ks < OT) dst[4 * ks + g] = tot;
+    }
+    dst += 4 * OT;
+#pragma unroll
+    for (int q = 0; q < 4 * MA; ++q) {
+        const float tot = group16_sum(dba[q]);
+        if (n == 0 && q < HT) dst[4 * q + g] = tot;
+    }
+}
+
+#define ESRNN_HEAD_SHAPES(X) \
+    X(2, 1) X(2, 2) X(2, 3) X(2, 4) X(8, 1) X(8, 2) X(8, 3) X(8, 4) X(10, 1) X(10, 2) X(10, 3) X(10, 4) \
+    X(13, 1) X(13, 2) X(13, 3) X(13, 4) X(16, 1) X(16, 2) X(16, 3) X(16, 4)
+
+}  // namespace
+
+hipError_t launch_head_forward(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st)
+{
+    const HeadPack hp = head_pack_layout(pl);
+    const float *f = ws + pl.head_fwd_pack;
+    const int blocks = pl.n_head_waves / 4;
+    HeadFwdArgs a{f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z,
+                  ws + pl.u, ws + pl.S1, ws + pl.S2, lengths, ws + pl.A, ws + pl.O, forecasts, ws + pl.loss_partial,
+                  pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.cfg.tau};
+#define X(HT_, MO_)                                                      \
+    if (pl.HT == HT_ && pl.MO == MO_) {                                  \
+        head_forward_kernel<HT_, MO_><<<blocks, 256, 0, st>>>(a);        \
+        return hipGetLastError();                                        \
+    }
+    ESRNN_HEAD_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_head_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st)
+{
+    const HeadPack hp = head_pack_layout(pl);
+    const float *bk = ws + pl.head_bwd_pack;
+    const int blocks = pl.n_head_waves / 4;
+    HeadBwdArgs a{bk + hp.WoT, bk + hp.WaT, ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.A, ws + pl.O, ws + pl.Z,
+                  lengths, reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.gO, ws + pl.gTop,
+                  ws + pl.head_dw_partial, pl.P, pl.NB, pl.B, pl.T, pl.I, pl.H, pl.head_dw_stride, pl.cfg.tau};
+#define X(HT_, MO_)                                                      \
+    if (pl.HT == HT_ && pl.MO == MO_) {                                  \
+        head_backward_kernel<HT_, MO_><<<blocks, 256, 0, st>>>(a);       \
+        return hipGetLastError();                                        \
+    }
+    ESRNN_HEAD_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+}  // namespace esrnn

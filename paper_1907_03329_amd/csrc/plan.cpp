@@ -1,0 +1,199 @@
+// Host-side launch plan: validates a configuration, lays out the workspace and
+// the packed operand blocks.  No device work happens here.
+#include <algorithm>
+#include <cstring>
+
+#include "esrnn_internal.h"
+
+namespace esrnn {
+
+namespace {
+
+struct Bump {
+    size_t at = 0;
+    size_t take(size_t n_floats)
+    {
+        size_t r = at;
+        at += (n_floats + 63) & ~size_t(63);   // keep every block 256-byte aligned
+        return r;
+    }
+};
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// hidden sizes are padded to one of the instantiated unit-tile counts
+int pick_ht(int hidden)
+{
+    const int need = ceil_div(hidden, 4);
+    const int avail[] = {2, 8, 10, 13, 16};
+    for (int v : avail)
+        if (need <= v) return v;
+    return -1;
+}
+
+}  // namespace
+
+bool lstm_shape_supported(int HT, int KXT)
+{
+    static const int pairs[][2] = {{2, 1}, {2, 2}, {8, 2}, {8, 8}, {10, 1}, {10, 6}, {10, 10},
+                                   {13, 3}, {13, 13}, {16, 16}};
+    for (auto &p : pairs)
+        if (p[0] == HT && p[1] == KXT) return true;
+    return false;
+}
+
+HeadPack head_pack_layout(const Plan &pl)
+{
+    HeadPack hp{};
+    Bump b;
+    hp.WaF = b.take((size_t)pl.MA * pl.HT * 64);
+    hp.baF = b.take((size_t)pl.MA * 16);
+    hp.WoF = b.take((size_t)pl.MO * pl.HT * 64);
+    hp.boF = b.take((size_t)pl.MO * 16);
+    hp.fwd_total = b.at;
+    Bump c;
+    hp.WoT = c.take((size_t)pl.MA * pl.OT * 64);
+    hp.WaT = c.take((size_t)pl.MA * pl.HT * 64);
+    hp.bwd_total = c.at;
+    return hp;
+}
+
+esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
+{
+    std::memset(&pl, 0, sizeof(pl));
+    pl.cfg = cfg;
+    if (cfg.B < 1 || cfg.T < 1 || cfg.I < 1 || cfg.H < 1 || cfg.hidden < 1) return ESRNN_ERR_CONFIG;
+    if (cfg.hidden > ESRNN_MAX_HIDDEN || cfg.I > ESRNN_MAX_WINDOW || cfg.H > ESRNN_MAX_WINDOW) return ESRNN_ERR_CONFIG;
+    if (cfg.n_seas < 0 || cfg.n_seas > 2) return ESRNN_ERR_CONFIG;
+    if (cfg.n_seas >= 1 && (cfg.m1 < 1 || cfg.m1 > cfg.T)) return ESRNN_ERR_CONFIG;
+    if (cfg.n_seas >= 2 && (cfg.m2 < 1 || cfg.m2 > cfg.T)) return ESRNN_ERR_CONFIG;
+    if ((long long)cfg.I + cfg.H > cfg.T) return ESRNN_ERR_CONFIG;
+    if (cfg.n_blocks < 1 || cfg.n_blocks > ESRNN_MAX_BLOCKS) return ESRNN_ERR_CONFIG;
+    if (!(cfg.tau > 0.0f && cfg.tau < 1.0f)) return ESRNN_ERR_CONFIG;
+    if (!(cfg.lambda_lv >= 0.0f)) return ESRNN_ERR_CONFIG;
+    if (cfg.param_space != ESRNN_PARAMS_DIRECT && cfg.param_space != ESRNN_PARAMS_LOGIT) return ESRNN_ERR_CONFIG;
+    if ((long long)cfg.B * cfg.T > (1LL << 30)) return ESRNN_ERR_CONFIG;
+
+    pl.B = cfg.B; pl.T = cfg.T; pl.I = cfg.I; pl.H = cfg.H; pl.h = cfg.hidden;
+    pl.P = cfg.T - cfg.I - cfg.H + 1;
+    pl.NB = ceil_div(cfg.B, kTileN);
+    pl.Bp = pl.NB * kTileN;
+    pl.HT = pick_ht(cfg.hidden);
+    if (pl.HT < 0) return ESRNN_ERR_CONFIG;
+    pl.HP = 4 * pl.HT;
+    pl.OT = ceil_div(cfg.H, 4);
+    pl.MO = ceil_div(cfg.H, 16);
+    pl.OP = 16 * pl.MO;
+    pl.MA = ceil_div(pl.HT, 4);
+    // layer 0 input tiles: exact if that kernel shape is instantiated, else padded to HT
+    pl.IT = ceil_div(cfg.I, 4);
+    if (!lstm_shape_supported(pl.HT, pl.IT)) {
+        if (cfg.I > pl.HP) return ESRNN_ERR_CONFIG;
+        pl.IT = pl.HT;
+    }
+
+    int r = 1;
+    pl.row_gamma1 = pl.row_gamma2 = pl.row_s1 = pl.row_s2 = -1;
+    if (cfg.n_seas >= 1) pl.row_gamma1 = r++;
+    if (cfg.n_seas >= 2) pl.row_gamma2 = r++;
+    if (cfg.n_seas >= 1) { pl.row_s1 = r; r += cfg.m1; }
+    if (cfg.n_seas >= 2) { pl.row_s2 = r; r += cfg.m2; }
+    pl.K = r;
+
+    // user weight offsets
+    size_t off = 0;
+    int L = 0;
+    const int h = cfg.hidden;
+    for (int k = 0; k < cfg.n_blocks; ++k) {
+        const int nl = cfg.layers_in_block[k];
+        if (nl < 1 || nl > ESRNN_MAX_LAYERS_PER_BLOCK) return ESRNN_ERR_CONFIG;
+        for (int j = 0; j < nl; ++j) {
+            LayerPlan &lp = pl.layer[L];
+            lp.dil = cfg.dilation[k][j];
+            if (lp.dil < 1) return ESRNN_ERR_CONFIG;
+            lp.block = k;
+            lp.first_in_block = (j == 0);
+            lp.last_in_block = (j == nl - 1);
+            lp.in_dim = (L == 0) ? cfg.I : h;
+            lp.KXT = (L == 0) ? pl.IT : pl.HT;
+            lp.w_off = off; off += (size_t)4 * h * (lp.in_dim + h);
+            lp.b_off = off; off += (size_t)4 * h;
+            ++L;
+        }
+    }
+    pl.L = L;
+    pl.Wa_off = off; off += (size_t)h * h;
+    pl.ba_off = off; off += h;
+    pl.Wo_off = off; off += (size_t)cfg.H * h;
+    pl.bo_off = off; off += cfg.H;
+    pl.n_weights = off;
+
+    // workspace
+    Bump ws;
+    const size_t TB = (size_t)pl.T * pl.Bp;
+    const size_t PN = (size_t)pl.P * pl.NB;
+    const size_t tileH = (size_t)pl.HT * 64;         // floats of one (p, series-tile) block with HP rows
+    pl.scalars = ws.take(64);
+    pl.lvl = ws.take(TB); pl.S1 = ws.take(TB); pl.S2 = ws.take(TB);
+    pl.u = ws.take(TB); pl.v = ws.take(TB); pl.gu = ws.take(TB); pl.gv = ws.take(TB);
+    pl.X = ws.take(PN * (size_t)pl.IT * 64);
+    pl.Z = ws.take(PN * (size_t)pl.OP * 16);
+    pl.gX = ws.take(PN * (size_t)pl.IT * 64);
+    pl.A = ws.take(PN * tileH);
+    pl.O = ws.take(PN * (size_t)pl.OP * 16);
+    pl.gO = ws.take(PN * (size_t)pl.OP * 16);
+    for (int k = 0; k < cfg.n_blocks; ++k) pl.gblk[k] = ws.take(PN * tileH);
+    pl.gTop = pl.gblk[cfg.n_blocks - 1];
+    for (int l = 0; l < L; ++l) {
+        LayerPlan &lp = pl.layer[l];
+        const int KT = lp.KXT + pl.HT;
+        const int MB = ceil_div(KT, 4);
+        lp.wpack_fwd = ws.take((size_t)pl.HT * KT * 64);
+        lp.bias_pack = ws.take((size_t)pl.HT * 16);
+        lp.wpack_bwd = ws.take((size_t)MB * 4 * pl.HT * 64);
+        lp.gates = ws.take(PN * tileH * 4);
+        lp.c = ws.take(PN * tileH);
+        lp.hid = ws.take(PN * tileH);
+        if (lp.dil >= 2) { lp.dhr = ws.take(PN * tileH); lp.dcr = ws.take(PN * tileH); }
+        lp.dw_partial = ws.take((size_t)pl.NB * pl.HT * MB * 256);
+        lp.db_partial = ws.take((size_t)pl.NB * pl.HT * 16);
+        pl.dx[l] = (l > 0 && !lp.first_in_block) ? ws.take(PN * tileH) : 0;
+    }
+    // block outputs: block 0's is the hidden state of its last layer
+    for (int l = 0; l < L; ++l) {
+        LayerPlan &lp = pl.layer[l];
+        if (lp.last_in_block) {
+            if (lp.block == 0) pl.blk_out[0] = lp.hid;
+            else pl.blk_out[lp.block] = ws.take(PN * tileH);
+        }
+    }
+    for (int l = 0; l < L; ++l) {
+        LayerPlan &lp = pl.layer[l];
+        // forward wiring
+        if (l == 0) lp.xsrc = pl.X;
+        else if (lp.first_in_block) lp.xsrc = pl.blk_out[lp.block - 1];
+        else lp.xsrc = pl.layer[l - 1].hid;
+        if (lp.last_in_block && lp.block >= 1) { lp.resid = pl.blk_out[lp.block - 1]; lp.out = pl.blk_out[lp.block]; }
+        // backward wiring
+        lp.gsrc = lp.last_in_block ? pl.gblk[lp.block] : pl.dx[l + 1];
+        if (l == 0) { lp.gdst = pl.gX; lp.gadd = 0; }
+        else if (lp.first_in_block) { lp.gdst = pl.gblk[lp.block - 1]; lp.gadd = pl.gblk[lp.block]; }
+        else { lp.gdst = pl.dx[l]; lp.gadd = 0; }
+    }
+    const HeadPack hp = head_pack_layout(pl);
+    pl.head_fwd_pack = ws.take(hp.fwd_total);
+    pl.head_bwd_pack = ws.take(hp.bwd_total);
+    const size_t n_tiles = PN;
+    const int head_blocks = (int)std::min<size_t>((n_tiles + 3) / 4, 512);
+    pl.n_head_waves = head_blocks * 4;
+    pl.head_dw_stride = (pl.MO * pl.MA + pl.MA * pl.MA) * 256 + 4 * pl.OT + 4 * pl.HT;
+    pl.head_dw_stride = (pl.head_dw_stride + 63) & ~63;
+    pl.head_dw_partial = ws.take((size_t)pl.n_head_waves * pl.head_dw_stride);
+    pl.es_blocks = ceil_div(pl.Bp, 64);
+    pl.n_loss_partial = head_blocks + pl.es_blocks;
+    pl.loss_partial = ws.take((size_t)pl.n_loss_partial);
+    pl.total_floats = ws.at;
+    return ESRNN_OK;
+}
+
+}  // namespace esrnn

@@ -1,0 +1,127 @@
+"""GPU parity: the HIP training step against the float64 CPU oracle, tensor by
+tensor, through the C ABI.  Sizes span several 16-series tiles with a ragged
+last tile; lengths are ragged where stated."""
+import numpy as np
+import pytest
+
+from paper_1907_03329_amd import synth
+from paper_1907_03329_amd.synth import CONFIGS, Config
+
+pytestmark = pytest.mark.gpu
+
+from tests import gpu_common as gc  # noqa: E402
+
+
+def small(name, **kw):
+    base = dict(name=name, B=37, T=40, n_seas=1, m1=4, m2=0, I=4, H=8, hidden=8, blocks=((1, 2), (4, 8)),
+                tau=0.48, lambda_lv=50.0)
+    base.update(kw)
+    return Config(**base)
+
+
+def report(errs):
+    worst = sorted(errs.items(), key=lambda kv: -kv[1])[:4]
+    print("  worst:", ", ".join(f"{k}={v:.2e}" for k, v in worst), flush=True)
+
+
+@pytest.mark.parametrize("ragged", [False, True])
+def test_tiny_quarterly_config(ragged):
+    errs = gc.run_and_check(CONFIGS["tiny_quarterly"], seed=0, ragged=ragged)
+    report(errs)
+
+
+@pytest.mark.parametrize("space", [synth.PARAMS_DIRECT, synth.PARAMS_LOGIT])
+def test_single_seasonality_small_hidden(space):
+    errs = gc.run_and_check(small("single_h8", param_space=space), seed=1, ragged=True)
+    report(errs)
+
+
+def test_level_only():
+    cfg = small("none_h8", n_seas=0, m1=0, I=6, H=6, blocks=((1, 2), (2, 6)), step_mu=0.01, step_sd=0.05, noise_sd=0.03)
+    report(gc.run_and_check(cfg, seed=2, ragged=True))
+
+
+@pytest.mark.parametrize("space", [synth.PARAMS_DIRECT, synth.PARAMS_LOGIT])
+def test_double_seasonality(space):
+    cfg = small("double_h8", T=60, n_seas=2, m1=3, m2=7, seas_sd2=0.1, I=5, H=6, param_space=space,
+                blocks=((1, 3), (5,)))
+    report(gc.run_and_check(cfg, seed=3, ragged=True))
+
+
+def test_hidden_30_shape_of_yearly():
+    cfg = CONFIGS["yearly"].with_(B=50)
+    report(gc.run_and_check(cfg, seed=4, ragged=True))
+
+
+def test_hidden_40_shape_of_quarterly_several_tiles():
+    cfg = CONFIGS["quarterly"].with_(B=70)
+    report(gc.run_and_check(cfg, seed=5, ragged=True))
+
+
+def test_hidden_50_shape_of_monthly():
+    cfg = CONFIGS["monthly"].with_(B=21, T=90)
+    report(gc.run_and_check(cfg, seed=6, ragged=True))
+
+
+def test_shape_of_hourly_short():
+    cfg = CONFIGS["hourly"].with_(B=19, T=300)
+    report(gc.run_and_check(cfg, seed=7, ragged=False))
+
+
+def test_three_blocks_and_single_layer_blocks():
+    cfg = small("three_blocks", blocks=((1,), (2,), (3, 1)), hidden=5, I=3, H=5)
+    report(gc.run_and_check(cfg, seed=8, ragged=True))
+
+
+def test_input_window_padded_to_hidden_tiles():
+    # I = 13 has no dedicated kernel shape with hidden 30: the input is padded to the hidden tile count
+    cfg = small("padded_input", hidden=30, I=13, H=3, T=48)
+    report(gc.run_and_check(cfg, seed=9, ragged=True))
+
+
+def test_no_penalty_and_other_quantile():
+    cfg = small("tau_0.3", lambda_lv=0.0, tau=0.3)
+    report(gc.run_and_check(cfg, seed=10, ragged=False))
+
+
+def test_batch_of_one_and_exact_tile():
+    report(gc.run_and_check(small("one", B=1), seed=11))
+    report(gc.run_and_check(small("sixteen", B=16), seed=12))
+
+
+def test_minimum_length_series():
+    """Series whose length equals I + H have exactly one window."""
+    cfg = small("minlen", B=20)
+
+    def mutate(inp):
+        inp["lengths"][:] = cfg.I + cfg.H
+        inp["lengths"][0] = cfg.T
+        inp["y"][np.arange(cfg.T)[:, None] >= inp["lengths"][None, :]] = 1.0
+
+    report(gc.run_and_check(cfg, seed=13, mutate=mutate))
+
+
+def test_padding_values_are_ignored():
+    import torch
+    from paper_1907_03329_amd import binding
+    cfg = small("pad", B=20)
+    inp = synth.make_inputs(cfg, seed=14, ragged=True)
+    s1 = gc.run_gpu(cfg, inp)
+    inp2 = {k: v.copy() for k, v in inp.items()}
+    pad = np.arange(cfg.T)[:, None] >= inp["lengths"][None, :]
+    inp2["y"][pad] = -5.0      # would be NaN under a logarithm
+    s2 = gc.run_gpu(cfg, inp2)
+    assert torch.equal(s1.loss, s2.loss)
+    assert torch.equal(s1.forecasts, s2.forecasts)
+    assert torch.equal(s1.grad_es_params, s2.grad_es_params)
+    assert torch.equal(s1.grad_weights, s2.grad_weights)
+
+
+def test_results_are_deterministic():
+    import torch
+    cfg = small("det", B=40)
+    inp = synth.make_inputs(cfg, seed=15, ragged=True)
+    s1, s2 = gc.run_gpu(cfg, inp), gc.run_gpu(cfg, inp)
+    assert torch.equal(s1.loss, s2.loss)
+    assert torch.equal(s1.grad_weights, s2.grad_weights)
+    assert torch.equal(s1.grad_es_params, s2.grad_es_params)
