@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the ES-RNN training step on one MI355X.
+
+One step = esrnn_forward + esrnn_backward (every stage of the hot path) over one
+batch of synthetic series that is already resident in HBM.  Prints ONE JSON
+line: throughput in series-steps/s (one series-step = one time step of one
+series; a step processes B*T of them), the roofline position of the dominant
+kernel measured with HIP events on the launch stream, and the float64 CPU
+oracle timed on the host cores of the same box as a reported baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload quarterly]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
+
+
+def stage_model(cfg, name):
+    """Algorithmic work of one launch of a stage: (bound, amount, unit).
+
+    Contractions are priced in flops (2 per multiply-add, logical sizes, no
+    padding); streaming stages in the bytes the method has to move (fp32)."""
+    B, T, I, H, h = cfg.B, cfg.T, cfg.I, cfg.H, cfg.hidden
+    P = T - I - H + 1
+    n_seas = cfg.n_seas
+    if name.startswith("lstm_forward_l") or name.startswith("lstm_backward_l"):
+        layer = int(name.rsplit("l", 1)[1])
+        k = (I if layer == 0 else h) + h
+        per = 2 * k * 4 * h
+        if name.startswith("lstm_backward"):
+            per *= 2                      # transposed contraction + weight gradient
+        return "mfma", float(per) * B * P, "flop"
+    if name == "head_forward":
+        return "mfma", 2.0 * (h * h + H * h) * B * P, "flop"
+    if name == "head_backward":
+        return "mfma", 4.0 * (h * h + H * h) * B * P, "flop"
+    if name == "es_forward":
+        return "hbm", 4.0 * B * T * (1 + 3 + n_seas) + 4.0 * B * cfg.K, "byte"       # read y; write level, u, v, factors
+    if name == "es_backward":
+        return "hbm", 4.0 * B * T * (4 + n_seas) + 4.0 * B * cfg.K, "byte"           # read y, level, gu, gv, factors
+    if name == "window_forward":
+        return "hbm", 4.0 * B * P * (I + H) + 8.0 * B * T, "byte"                     # write X, Z; read u, v
+    if name == "window_backward":
+        return "hbm", 4.0 * B * P * (I + H) + 8.0 * B * T, "byte"                     # read gX, gO; write gu, gv
+    return None, 0.0, ""
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="quarterly")
+    ap.add_argument("--batch", type=int, default=0, help="override the number of series")
+    ap.add_argument("--profile-steps", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (series shard trivially across GPUs, "
+              "but no multi-GPU path is built); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1907_03329_amd import binding, synth
+
+    cfg = synth.CONFIGS[args.workload]
+    if args.batch:
+        cfg = cfg.with_(B=args.batch)
+    inp = synth.make_inputs(cfg, seed=0)
+    torch.cuda.set_device(0)
+    dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
+    step = binding.TrainingStep(cfg, want_forecasts=True)
+
+    def one_step():
+        step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+        step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    series_steps = cfg.B * cfg.T
+    value = series_steps / (elapsed / args.steps)
+    loss = float(step.loss.item())
+
+    # per-stage durations: HIP events recorded by the library on the launch stream
+    binding.esrnn_profile_enable(step.handle, True)
+    for _ in range(max(1, args.profile_steps)):
+        one_step()
+        binding.esrnn_profile_collect(step.handle)
+    stages = binding.esrnn_profile_read(step.handle)
+    binding.esrnn_profile_enable(step.handle, False)
+    stage_ms = {name: tot / max(cnt, 1) for name, tot, cnt in stages}
+    total_stage_ms = sum(stage_ms.values())
+    dominant = max(stage_ms, key=stage_ms.get)
+    bound, amount, _ = stage_model(cfg, dominant)
+    dur_s = stage_ms[dominant] * 1e-3
+    if bound == "mfma":
+        achieved, peak, unit = amount / dur_s / 1e12, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"
+    elif bound == "hbm":
+        achieved, peak, unit = amount / dur_s / 1e9, PEAK_HBM_GBS, "GB/s"
+    else:
+        achieved, peak, unit = 0.0, 1.0, ""
+    roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": None,
+                "avg_launch_ms": round(stage_ms[dominant], 4)}
+    stage_report = {}
+    for name, ms in stage_ms.items():
+        b, amt, _ = stage_model(cfg, name)
+        entry = {"ms": round(ms, 4)}
+        if b == "mfma":
+            entry["tflops"] = round(amt / (ms * 1e-3) / 1e12, 2)
+            entry["frac_mfma_peak"] = round(entry["tflops"] / PEAK_FP32_MFMA_TFLOPS, 4)
+        elif b == "hbm":
+            entry["gbs"] = round(amt / (ms * 1e-3) / 1e9, 1)
+            entry["frac_hbm_peak"] = round(entry["gbs"] / PEAK_HBM_GBS, 4)
+        stage_report[name] = entry
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        # the full workload if it is small enough, else a prefix of the series
+        flops = 3.0 * sum(stage_model(cfg, f"lstm_forward_l{l}")[1] for l in range(cfg.n_layers))
+        nb = cfg.B
+        while nb > 64 and flops * nb / cfg.B > 1.2e11:
+            nb //= 2
+        sub = synth.take_series(inp, range(nb))
+        scfg = cfg.with_(B=nb)
+        reps = 2
+
+        def oracle_step():
+            f = oracle.forward(scfg, sub["y"], sub["lengths"], sub["es_params"], sub["weights"], want_forecasts=True)
+            oracle.backward(scfg, f, want_adjoints=False)
+            return f
+
+        f = oracle_step()                                  # warm-up, also checks the GPU loss when nb == B
+        t1 = time.perf_counter()
+        for _ in range(reps):
+            oracle_step()
+        cpu_s = (time.perf_counter() - t1) / reps
+        cpu = {"value": round(nb * cfg.T / cpu_s, 1), "unit": "series-steps/s", "cores": oracle.max_threads(),
+               "kind": "oracle",
+               "sample": f"{nb} of {cfg.B} series of the same batch, forward+backward, float64, {reps} reps",
+               "ms_per_step_sample": round(1e3 * cpu_s, 1)}
+        if nb == cfg.B:
+            cpu["loss_rel_diff_vs_gpu"] = abs(loss - f.loss) / abs(f.loss)
+
+    out = {
+        "metric": "training-step series-steps/sec (fwd+bwd)",
+        "value": round(value, 1),
+        "unit": "series-steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "seasons": [m for m in (cfg.m1, cfg.m2) if m],
+                   "I": cfg.I, "H": cfg.H, "hidden": cfg.hidden, "dilations": [list(b) for b in cfg.blocks],
+                   "tau": cfg.tau, "lambda_lv": cfg.lambda_lv, "window_steps": cfg.B * cfg.P},
+        "loss": loss,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "stages": stage_report,
+        "sum_stage_ms": round(total_stage_ms, 4),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

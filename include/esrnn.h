@@ -156,6 +156,23 @@ typedef struct {
 
 esrnn_status esrnn_workspace_buffer(const esrnn_handle *h, int32_t which, int32_t index, esrnn_buffer_view *out);
 
+/*
+ * Per-stage timing for benchmarks.  While enabled, esrnn_forward and
+ * esrnn_backward bracket every stage (one kernel launch, except the packing
+ * and gradient-reduction stages, which launch one small kernel per layer) with
+ * HIP events on the caller's stream.  esrnn_profile_collect waits for the
+ * events of the last forward/backward pair (the only call here that blocks the
+ * host) and adds their elapsed times to per-stage totals; call it once after
+ * each pair.  esrnn_profile_read copies the totals in milliseconds and the
+ * number of collected launches into host arrays of esrnn_profile_stage_count
+ * entries.  Enabling resets the totals.
+ */
+esrnn_status esrnn_profile_enable(esrnn_handle *h, int32_t on);
+esrnn_status esrnn_profile_stage_count(const esrnn_handle *h, int32_t *n);
+esrnn_status esrnn_profile_stage_name(const esrnn_handle *h, int32_t i, const char **name);
+esrnn_status esrnn_profile_collect(esrnn_handle *h);
+esrnn_status esrnn_profile_read(const esrnn_handle *h, double *total_ms, int32_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -70,6 +70,14 @@ def load_library():
     lib.esrnn_forward.argtypes = [vp, fp, i32p, fp, fp, vp, fp, fp, vp]
     lib.esrnn_backward.argtypes = [vp, fp, i32p, fp, fp, vp, fp, fp, vp]
     lib.esrnn_workspace_buffer.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(BufferView)]
+    lib.esrnn_profile_enable.argtypes = [vp, C.c_int32]
+    lib.esrnn_profile_stage_count.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.esrnn_profile_stage_name.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p)]
+    lib.esrnn_profile_collect.argtypes = [vp]
+    lib.esrnn_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    for fn in ("esrnn_profile_enable", "esrnn_profile_stage_count", "esrnn_profile_stage_name",
+               "esrnn_profile_collect", "esrnn_profile_read"):
+        getattr(lib, fn).restype = C.c_int
     for fn in ("esrnn_create", "esrnn_destroy", "esrnn_workspace_bytes", "esrnn_es_param_rows",
                "esrnn_weight_count", "esrnn_forward", "esrnn_backward", "esrnn_workspace_buffer"):
         getattr(lib, fn).restype = C.c_int
@@ -147,6 +155,40 @@ def esrnn_workspace_buffer(handle, which, index: int = 0) -> BufferView:
     if st != ESRNN_OK:
         raise EsrnnError(st, "esrnn_workspace_buffer")
     return v
+
+
+def esrnn_profile_enable(handle, on: bool) -> None:
+    st = load_library().esrnn_profile_enable(handle, 1 if on else 0)
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_profile_enable")
+
+
+def esrnn_profile_collect(handle) -> None:
+    st = load_library().esrnn_profile_collect(handle)
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_profile_collect")
+
+
+def esrnn_profile_read(handle):
+    """Returns [(stage name, total milliseconds, collected launches)]."""
+    lib = load_library()
+    n = C.c_int32()
+    st = lib.esrnn_profile_stage_count(handle, C.byref(n))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_profile_stage_count")
+    ms = (C.c_double * n.value)()
+    cnt = (C.c_int32 * n.value)()
+    st = lib.esrnn_profile_read(handle, ms, cnt)
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_profile_read")
+    out = []
+    for i in range(n.value):
+        name = C.c_char_p()
+        st = lib.esrnn_profile_stage_name(handle, i, C.byref(name))
+        if st != ESRNN_OK:
+            raise EsrnnError(st, "esrnn_profile_stage_name")
+        out.append((name.value.decode(), float(ms[i]), int(cnt[i])))
+    return out
 
 
 def _ptr(t, dtype=None, allow_none=False):

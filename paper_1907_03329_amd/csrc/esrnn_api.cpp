@@ -1,15 +1,61 @@
 // C ABI of the ES-RNN library (include/esrnn.h): handle management, argument
 // checks and the order in which the kernels of one training step are enqueued.
+#include <cstdio>
 #include <new>
 
 #include "esrnn_internal.h"
 
 using namespace esrnn;
 
+namespace {
+constexpr int kMaxStages = 16 + 2 * kMaxLayers;
+struct Stage {
+    char name[32];
+    hipEvent_t start, stop;
+    bool recorded;
+    double total_ms;
+    int launches;
+};
+}  // namespace
+
 struct esrnn_handle {
     Plan plan;
     bool forward_done;
+    bool profiling;
+    int n_stages;
+    Stage stage[kMaxStages];
+    // stage indices
+    int st_prep, st_pack, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head_fwd, st_loss;
+    int st_head_bwd, st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce;
 };
+
+namespace {
+int add_stage(esrnn_handle *h, const char *fmt, int arg)
+{
+    Stage &s = h->stage[h->n_stages];
+    snprintf(s.name, sizeof(s.name), fmt, arg);
+    s.start = s.stop = nullptr;
+    s.recorded = false;
+    s.total_ms = 0.0;
+    s.launches = 0;
+    return h->n_stages++;
+}
+
+// Runs one stage; with profiling on, brackets it with events on the same stream.
+template <class F>
+hipError_t run_stage(esrnn_handle *h, int idx, hipStream_t st, F &&launch)
+{
+    if (!h->profiling) return launch();
+    Stage &s = h->stage[idx];
+    hipError_t e = hipEventRecord(s.start, st);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(s.stop, st);
+    s.recorded = true;
+    return e;
+}
+}  // namespace
 
 #define ESRNN_TRY(expr)                              \
     do {                                             \
@@ -31,6 +77,21 @@ esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
         return st;
     }
     h->forward_done = false;
+    h->profiling = false;
+    h->n_stages = 0;
+    const Plan &pl = h->plan;
+    h->st_prep = add_stage(h, "prep", 0);
+    h->st_pack = add_stage(h, "pack_weights", 0);
+    h->st_es_fwd = add_stage(h, "es_forward", 0);
+    h->st_win_fwd = add_stage(h, "window_forward", 0);
+    for (int l = 0; l < pl.L; ++l) h->st_lstm_fwd[l] = add_stage(h, "lstm_forward_l%d", l);
+    h->st_head_fwd = add_stage(h, "head_forward", 0);
+    h->st_loss = add_stage(h, "loss_finalize", 0);
+    h->st_head_bwd = add_stage(h, "head_backward", 0);
+    for (int l = pl.L - 1; l >= 0; --l) h->st_lstm_bwd[l] = add_stage(h, "lstm_backward_l%d", l);
+    h->st_win_bwd = add_stage(h, "window_backward", 0);
+    h->st_es_bwd = add_stage(h, "es_backward", 0);
+    h->st_reduce = add_stage(h, "reduce_weight_grads", 0);
     *out = h;
     return ESRNN_OK;
 }
@@ -38,6 +99,10 @@ esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
 esrnn_status esrnn_destroy(esrnn_handle *h)
 {
     if (!h) return ESRNN_ERR_NULL;
+    for (int i = 0; i < h->n_stages; ++i) {
+        if (h->stage[i].start) (void)hipEventDestroy(h->stage[i].start);
+        if (h->stage[i].stop) (void)hipEventDestroy(h->stage[i].stop);
+    }
     delete h;
     return ESRNN_OK;
 }
@@ -86,13 +151,14 @@ esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengt
     float *ws = static_cast<float *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     h->forward_done = false;
-    ESRNN_TRY(launch_prep(pl, lengths, ws, st));
-    ESRNN_TRY(launch_pack_weights(pl, weights, ws, st));
-    ESRNN_TRY(launch_es_forward(pl, y, lengths, es_params, ws, st));
-    ESRNN_TRY(launch_window_forward(pl, ws, st));
-    for (int l = 0; l < pl.L; ++l) ESRNN_TRY(launch_lstm_forward(pl, l, ws, st));
-    ESRNN_TRY(launch_head_forward(pl, lengths, ws, forecasts, st));
-    ESRNN_TRY(launch_loss_finalize(pl, ws, loss, st));
+    ESRNN_TRY(run_stage(h, h->st_prep, st, [&] { return launch_prep(pl, lengths, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_pack, st, [&] { return launch_pack_weights(pl, weights, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, lengths, es_params, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, ws, st); }));
+    for (int l = 0; l < pl.L; ++l)
+        ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_head_fwd, st, [&] { return launch_head_forward(pl, lengths, ws, forecasts, st); }));
+    ESRNN_TRY(run_stage(h, h->st_loss, st, [&] { return launch_loss_finalize(pl, ws, loss, st); }));
     h->forward_done = true;
     return ESRNN_OK;
 }
@@ -108,11 +174,71 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
     const Plan &pl = h->plan;
     float *ws = static_cast<float *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    ESRNN_TRY(launch_head_backward(pl, lengths, ws, st));
-    for (int l = pl.L - 1; l >= 0; --l) ESRNN_TRY(launch_lstm_backward(pl, l, ws, st));
-    ESRNN_TRY(launch_window_backward(pl, lengths, ws, st));
-    ESRNN_TRY(launch_es_backward(pl, y, lengths, es_params, ws, grad_es_params, st));
-    ESRNN_TRY(launch_reduce_weight_grads(pl, ws, grad_weights, st));
+    ESRNN_TRY(run_stage(h, h->st_head_bwd, st, [&] { return launch_head_backward(pl, lengths, ws, st); }));
+    for (int l = pl.L - 1; l >= 0; --l)
+        ESRNN_TRY(run_stage(h, h->st_lstm_bwd[l], st, [&] { return launch_lstm_backward(pl, l, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_win_bwd, st, [&] { return launch_window_backward(pl, lengths, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_es_bwd, st,
+                        [&] { return launch_es_backward(pl, y, lengths, es_params, ws, grad_es_params, st); }));
+    ESRNN_TRY(run_stage(h, h->st_reduce, st, [&] { return launch_reduce_weight_grads(pl, ws, grad_weights, st); }));
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_profile_enable(esrnn_handle *h, int32_t on)
+{
+    if (!h) return ESRNN_ERR_NULL;
+    if (on) {
+        for (int i = 0; i < h->n_stages; ++i) {
+            Stage &s = h->stage[i];
+            if (!s.start) ESRNN_TRY(hipEventCreate(&s.start));
+            if (!s.stop) ESRNN_TRY(hipEventCreate(&s.stop));
+            s.recorded = false;
+            s.total_ms = 0.0;
+            s.launches = 0;
+        }
+    }
+    h->profiling = on != 0;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_profile_stage_count(const esrnn_handle *h, int32_t *n)
+{
+    if (!h || !n) return ESRNN_ERR_NULL;
+    *n = h->n_stages;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_profile_stage_name(const esrnn_handle *h, int32_t i, const char **name)
+{
+    if (!h || !name) return ESRNN_ERR_NULL;
+    if (i < 0 || i >= h->n_stages) return ESRNN_ERR_CONFIG;
+    *name = h->stage[i].name;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_profile_collect(esrnn_handle *h)
+{
+    if (!h) return ESRNN_ERR_NULL;
+    for (int i = 0; i < h->n_stages; ++i) {
+        Stage &s = h->stage[i];
+        if (!s.recorded) continue;
+        ESRNN_TRY(hipEventSynchronize(s.stop));
+        float ms = 0.0f;
+        ESRNN_TRY(hipEventElapsedTime(&ms, s.start, s.stop));
+        s.total_ms += ms;
+        s.launches += 1;
+        s.recorded = false;
+    }
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_profile_read(const esrnn_handle *h, double *total_ms, int32_t *launches)
+{
+    if (!h || !total_ms || !launches) return ESRNN_ERR_NULL;
+    for (int i = 0; i < h->n_stages; ++i) {
+        total_ms[i] = h->stage[i].total_ms;
+        launches[i] = h->stage[i].launches;
+    }
     return ESRNN_OK;
 }
 
