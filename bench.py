@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the number of series")
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one device-to-device copy of this many MiB (reference for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (series shard trivially across GPUs, "
@@ -80,6 +83,13 @@ def main():
     torch.cuda.set_device(0)
     dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
     step = binding.TrainingStep(cfg, want_forecasts=True)
+
+    if args.copy_probe_mib:
+        src = torch.ones(args.copy_probe_mib * 262144, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def one_step():
         step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])

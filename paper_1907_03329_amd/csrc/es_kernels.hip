@@ -462,72 +462,92 @@ struct ReduceLstmArgs {
     int NB, h, in_dim, HT, KXT;
 };
 
+// Sums `n_part` partial blocks for 64 consecutive elements per workgroup: the
+// four waves take interleaved quarters of the partials (each load instruction
+// reads 256 contiguous bytes of one partial), then combine in a fixed order.
+__device__ __forceinline__ float reduce_partials(const float *__restrict__ base, size_t stride, int n_part, int elem,
+                                                 bool active, float (*s_red)[64])
+{
+    const int e = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    float acc = 0.0f;
+    if (active) {
+        const float *src = base + elem;
+        int w = sl;
+        for (; w + 12 < n_part; w += 16) {
+            const float a0 = src[(size_t)w * stride], a1 = src[(size_t)(w + 4) * stride];
+            const float a2 = src[(size_t)(w + 8) * stride], a3 = src[(size_t)(w + 12) * stride];
+            acc += (a0 + a1) + (a2 + a3);
+        }
+        for (; w < n_part; w += 4) acc += src[(size_t)w * stride];
+    }
+    s_red[sl][e] = acc;
+    __syncthreads();
+    return (s_red[0][e] + s_red[1][e]) + (s_red[2][e] + s_red[3][e]);
+}
+
 __global__ void __launch_bounds__(256) reduce_lstm_kernel(ReduceLstmArgs a)
 {
+    __shared__ float s_red[4][64];
     const int KT = a.KXT + a.HT, MB = (KT + 3) / 4, ld = a.in_dim + a.h;
-    const int nW = 4 * a.h * ld, nb = 4 * a.h;
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx < nW) {
-        const int row = idx / ld, col = idx % ld;
-        const int gate = row / a.h, unit = row % a.h;
-        const int mt = unit >> 2, g = unit & 3;
-        const int xr = col < a.in_dim ? col : 4 * a.KXT + (col - a.in_dim);
-        const int nbk = xr >> 4, c = xr & 15;
-        // tile (mt, nbk): row 4*gate + g  ->  lane group = gate, component = g; column c
-        const size_t stride = (size_t)a.HT * MB * 256;
-        const float *src = a.dw_partial + ((size_t)(mt * MB + nbk) * 4 + g) * 64 + gate * 16 + c;
-        double s = 0.0;
-        for (int w = 0; w < a.NB; ++w) s += (double)src[w * stride];
-        a.gW[idx] = (float)s;
-    } else if (idx < nW + nb) {
-        const int j = idx - nW;
-        const int gate = j / a.h, unit = j % a.h;
-        const size_t stride = (size_t)a.HT * 16;
-        const float *src = a.db_partial + unit * 4 + gate;
-        double s = 0.0;
-        for (int w = 0; w < a.NB; ++w) s += (double)src[w * stride];
-        a.gb[j] = (float)s;
+    const int n_dw = a.HT * MB * 256, n_db = a.HT * 16;
+    const int n_dw_blocks = (n_dw + 63) / 64;
+    const int e = threadIdx.x & 63;
+    if ((int)blockIdx.x < n_dw_blocks) {
+        const int idx = blockIdx.x * 64 + e;                  // element of the tile block: [tile][component][lane]
+        const float tot = reduce_partials(a.dw_partial, (size_t)n_dw, a.NB, idx, idx < n_dw, s_red);
+        if (threadIdx.x < 64 && idx < n_dw) {
+            const int lane = idx & 63, comp = (idx >> 6) & 3, tix = idx >> 8;
+            const int mt = tix / MB, nbk = tix % MB;
+            // tile row 4*gate + unit-in-tile sits in lane group `gate`, component `unit-in-tile`
+            const int gate = lane >> 4, unit = 4 * mt + comp;
+            const int xr = 16 * nbk + (lane & 15);
+            int col = -1;
+            if (xr < 4 * a.KXT) { if (xr < a.in_dim) col = xr; }
+            else if (xr - 4 * a.KXT < a.h) col = a.in_dim + xr - 4 * a.KXT;
+            if (unit < a.h && col >= 0) a.gW[(size_t)(gate * a.h + unit) * ld + col] = tot;
+        }
+    } else {
+        const int idx = (blockIdx.x - n_dw_blocks) * 64 + e;   // [unit tile][unit][gate]
+        const float tot = reduce_partials(a.db_partial, (size_t)n_db, a.NB, idx, idx < n_db, s_red);
+        if (threadIdx.x < 64 && idx < n_db) {
+            const int gate = idx & 3, unit = idx >> 2;
+            if (unit < a.h) a.gb[gate * a.h + unit] = tot;
+        }
     }
 }
 
 struct ReduceHeadArgs {
     const float *partial;
     float *gWa, *gba, *gWo, *gbo;
-    int n_waves, stride, h, H, HT, MA, MO, OT;
+    int n_part, stride, h, H, HT, MA, MO, OT;
 };
 
 __global__ void __launch_bounds__(256) reduce_head_kernel(ReduceHeadArgs a)
 {
-    const int nWa = a.h * a.h, nba = a.h, nWo = a.H * a.h, nbo = a.H;
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= nWa + nba + nWo + nbo) return;
-    // partial block of one wave: dWo tiles [MO*MA][4][64], dWa tiles [MA*MA][4][64], dbo [4*OT], dba [4*HT]
+    __shared__ float s_red[4][64];
+    // partial block: dWo tiles [MO*MA][4][64], dWa tiles [MA*MA][4][64], dbo [4*OT], dba [4*HT]
     const int offWa = a.MO * a.MA * 256, offbo = offWa + a.MA * a.MA * 256, offba = offbo + 4 * a.OT;
-    int src_off;
-    float *dst;
-    if (idx < nWa) {
-        const int row = idx / a.h, col = idx % a.h;       // dWa[row][col] = sum dpre[row] * r[col]
-        const int mt = row >> 4, i = row & 15, nt = col >> 4, c = col & 15;
-        src_off = offWa + ((mt * a.MA + nt) * 4 + (i & 3)) * 64 + (i >> 2) * 16 + c;
-        dst = a.gWa + idx;
-    } else if (idx < nWa + nba) {
-        const int j = idx - nWa;
-        src_off = offba + j;
-        dst = a.gba + j;
-    } else if (idx < nWa + nba + nWo) {
-        const int j = idx - nWa - nba;
-        const int row = j / a.h, col = j % a.h;           // dWo[row][col] = sum gO[row] * a[col]
-        const int mt = row >> 4, i = row & 15, nt = col >> 4, c = col & 15;
-        src_off = ((mt * a.MA + nt) * 4 + (i & 3)) * 64 + (i >> 2) * 16 + c;
-        dst = a.gWo + j;
+    const int n = offba + 4 * a.HT;
+    const int idx = blockIdx.x * 64 + (threadIdx.x & 63);
+    const float tot = reduce_partials(a.partial, (size_t)a.stride, a.n_part, idx, idx < n, s_red);
+    if (threadIdx.x >= 64 || idx >= n) return;
+    if (idx < offbo) {
+        const bool isWa = idx >= offWa;
+        const int j = isWa ? idx - offWa : idx;
+        const int lane = j & 63, comp = (j >> 6) & 3, tix = j >> 8;
+        const int mt = tix / a.MA, nt = tix % a.MA;
+        const int row = 16 * mt + 4 * (lane >> 4) + comp, col = 16 * nt + (lane & 15);
+        if (col < a.h) {
+            if (isWa) { if (row < a.h) a.gWa[row * a.h + col] = tot; }
+            else if (row < a.H) a.gWo[row * a.h + col] = tot;
+        }
+    } else if (idx < offba) {
+        const int j = idx - offbo;
+        if (j < a.H) a.gbo[j] = tot;
     } else {
-        const int j = idx - nWa - nba - nWo;
-        src_off = offbo + j;
-        dst = a.gbo + j;
+        const int j = idx - offba;
+        if (j < a.h) a.gba[j] = tot;
     }
-    double s = 0.0;
-    for (int w = 0; w < a.n_waves; ++w) s += (double)a.partial[(size_t)w * a.stride + src_off];
-    *dst = (float)s;
 }
 
 }  // namespace
@@ -626,14 +646,15 @@ hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_wei
         const LayerPlan &lp = pl.layer[l];
         ReduceLstmArgs a{ws + lp.dw_partial, ws + lp.db_partial, grad_weights + lp.w_off, grad_weights + lp.b_off,
                          pl.NB, pl.h, lp.in_dim, pl.HT, lp.KXT};
-        const int total = 4 * pl.h * (lp.in_dim + pl.h) + 4 * pl.h;
-        reduce_lstm_kernel<<<(total + 255) / 256, 256, 0, st>>>(a);
+        const int MB = (lp.KXT + pl.HT + 3) / 4;
+        const int blocks = (pl.HT * MB * 256 + 63) / 64 + (pl.HT * 16 + 63) / 64;
+        reduce_lstm_kernel<<<blocks, 256, 0, st>>>(a);
     }
     ReduceHeadArgs a{ws + pl.head_dw_partial, grad_weights + pl.Wa_off, grad_weights + pl.ba_off,
                      grad_weights + pl.Wo_off, grad_weights + pl.bo_off,
                      pl.n_head_waves, pl.head_dw_stride, pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
-    const int total = pl.h * pl.h + pl.h + pl.H * pl.h + pl.H;
-    reduce_head_kernel<<<(total + 255) / 256, 256, 0, st>>>(a);
+    const int total = (pl.MO * pl.MA + pl.MA * pl.MA) * 256 + 4 * pl.OT + 4 * pl.HT;
+    reduce_head_kernel<<<(total + 63) / 64, 256, 0, st>>>(a);
     return hipGetLastError();
 }
 
