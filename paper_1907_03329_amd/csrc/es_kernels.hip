@@ -645,7 +645,7 @@ hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_wei
     for (int l = 0; l < pl.L; ++l) {
         const LayerPlan &lp = pl.layer[l];
         ReduceLstmArgs a{ws + lp.dw_partial, ws + lp.db_partial, grad_weights + lp.w_off, grad_weights + lp.b_off,
-                         pl.NB, pl.h, lp.in_dim, pl.HT, lp.KXT};
+                         pl.NB * lp.chains, pl.h, lp.in_dim, pl.HT, lp.KXT};
         const int MB = (lp.KXT + pl.HT + 3) / 4;
         const int blocks = (pl.HT * MB * 256 + 63) / 64 + (pl.HT * 16 + 63) / 64;
         reduce_lstm_kernel<<<blocks, 256, 0, st>>>(a);

@@ -34,9 +34,9 @@ struct LayerPlan {
     size_t gsrc;         // TL(HP) gradient arriving at this layer's hidden output
     size_t gdst;         // TL(4*KXT) gradient with respect to the layer input
     size_t gadd;         // TL(HP) added to gdst (residual path), 0 = none
-    size_t dhr, dcr;     // TL(HP) recurrent gradients for dilation >= 2
-    size_t dw_partial;   // [NB][HT*MB][4][64] per-workgroup weight-gradient tiles
-    size_t db_partial;   // [NB][HT][4][4]
+    int chains;          // workgroups per series tile; each walks the residue classes r, r+chains, ... (mod dil)
+    size_t dw_partial;   // [NB*chains][HT*MB][4][64] per-workgroup weight-gradient tiles
+    size_t db_partial;   // [NB*chains][HT][4][4]
 };
 
 struct Plan {

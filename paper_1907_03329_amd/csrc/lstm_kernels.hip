@@ -1,15 +1,20 @@
 // Dilated LSTM layer, forward and reverse (Section 3.2, Table 1), one launch per
-// layer.  A workgroup of four waves owns 16 series and walks the window
-// positions in order; series never interact, so there is no grid-level
-// synchronisation.  The gate contraction runs on the 16x16x4 fp32 MFMA with the
-// weights as the A operand, held in registers for the whole launch, and the
-// activations [x_p ; h_{p-d}] of 16 series as the B operand.
+// layer.
 //
-// Row order of the A operand: row 4g+r of unit tile mt is gate r of hidden unit
-// 4mt+g.  With that order a lane ends up holding the four gate pre-activations
-// of one unit for one series (cell update without any cross-lane traffic), and
-// the hidden state it produces for unit tile mt is, as it stands, the B operand
-// of k-step mt of a later position.
+// Parallel structure.  Series never interact, and a layer with dilation d is d
+// independent recurrences over the interleaved position classes p = r (mod d).
+// A workgroup of four waves therefore owns 16 series and one or more residue
+// classes r (grid = series tiles x chains) and walks each class in order with
+// the recurrent state on chip: h through LDS, c in registers.  There is no
+// grid-level synchronisation and no recurrent traffic through global memory.
+//
+// Arithmetic.  The gate contraction runs on the 16x16x4 fp32 MFMA with the
+// weights as the A operand, held in registers for the whole launch, and the
+// activations [x_p ; h_{p-d}] of 16 series as the B operand.  Row order of the
+// A operand: row 4g+r of unit tile mt is gate r of hidden unit 4mt+g.  A lane
+// then holds the four gate pre-activations of one unit for one series (cell
+// update without cross-lane traffic), and the hidden state it produces for unit
+// tile mt is, as it stands, the B operand of k-step mt of the next position.
 #include "device_utils.h"
 #include "esrnn_internal.h"
 
@@ -29,18 +34,16 @@ struct LstmFwdArgs {
 };
 
 template <int HT, int KXT>
-__global__ void __launch_bounds__(64 * kLstmWaves) lstm_forward_kernel(LstmFwdArgs a)
+__global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFwdArgs a)
 {
     constexpr int KT = KXT + HT;
     constexpr int MTW = (HT + kLstmWaves - 1) / kLstmWaves;   // unit tiles per wave
     __shared__ float hbuf[2][HT * 64];
 
     const int lane = threadIdx.x & 63, s = threadIdx.x >> 6, bt = blockIdx.x;
-    const bool d1 = (a.d == 1);
 
     float wreg[MTW][KT];
     f32x4 bias[MTW];
-    float creg[MTW];
 #pragma unroll
     for (int j = 0; j < MTW; ++j) {
         const int mt = s + kLstmWaves * j;
@@ -50,26 +53,20 @@ __global__ void __launch_bounds__(64 * kLstmWaves) lstm_forward_kernel(LstmFwdAr
         const float4 bv = valid ? *reinterpret_cast<const float4 *>(a.bpack + (mt * 4 + (lane >> 4)) * 4)
                                 : make_float4(0.f, 0.f, 0.f, 0.f);
         bias[j] = f32x4{bv.x, bv.y, bv.z, bv.w};
-        creg[j] = 0.0f;
     }
-    for (int i = threadIdx.x; i < HT * 64; i += 64 * kLstmWaves) hbuf[0][i] = 0.0f;
-    __syncthreads();
+    const size_t xtile = (size_t)KXT * 64;
 
-    const size_t xtile = (size_t)KXT * 64, htile = (size_t)HT * 64;
-    float bx[KXT], bh[HT], cpv[MTW];
+    for (int r = blockIdx.y; r < a.d && r < a.P; r += gridDim.y) {
+        // start of a chain: zero state
+        float creg[MTW];
 #pragma unroll
-    for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[(size_t)bt * xtile + ks * 64 + lane];
-#pragma unroll
-    for (int ks = 0; ks < HT; ++ks) bh[ks] = 0.0f;
-#pragma unroll
-    for (int j = 0; j < MTW; ++j) cpv[j] = 0.0f;
+        for (int j = 0; j < MTW; ++j) creg[j] = 0.0f;
+        for (int i = threadIdx.x; i < HT * 64; i += 64 * kLstmWaves) hbuf[0][i] = 0.0f;
 
-    for (int p = 0; p < a.P; ++p) {
-        const size_t pb = (size_t)p * a.NB + bt;
-        if (d1) {
+        // input part of the first position
+        float bx[KXT];
 #pragma unroll
-            for (int ks = 0; ks < HT; ++ks) bh[ks] = hbuf[p & 1][ks * 64 + lane];
-        }
+        for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[((size_t)r * a.NB + bt) * xtile + ks * 64 + lane];
         f32x4 acc[MTW];
 #pragma unroll
         for (int j = 0; j < MTW; ++j) acc[j] = bias[j];
@@ -77,70 +74,86 @@ __global__ void __launch_bounds__(64 * kLstmWaves) lstm_forward_kernel(LstmFwdAr
         for (int ks = 0; ks < KXT; ++ks)
 #pragma unroll
             for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
+        if (r + a.d < a.P) {
 #pragma unroll
-        for (int ks = 0; ks < HT; ++ks)
-#pragma unroll
-            for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][KXT + ks], bh[ks], acc[j]);
-
-        // operands of the next position (the input never depends on this layer)
-        if (p + 1 < a.P) {
-            const size_t nb = ((size_t)(p + 1) * a.NB + bt) * xtile;
-#pragma unroll
-            for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
+            for (int ks = 0; ks < KXT; ++ks)
+                bx[ks] = a.xsrc[((size_t)(r + a.d) * a.NB + bt) * xtile + ks * 64 + lane];
         }
+        lds_barrier();
 
+        int it = 0;
+        for (int p = r; p < a.P; p += a.d, ++it) {
+            const size_t pb = (size_t)p * a.NB + bt;
+            // recurrent part
+            const float *hb = hbuf[it & 1];
+            float bh[HT];
 #pragma unroll
-        for (int j = 0; j < MTW; ++j) {
-            const int mt = s + kLstmWaves * j;
-            if (mt < HT) {
-                const float gi = sigmoid_f(acc[j][0]);
-                const float gf = sigmoid_f(acc[j][1]);
-                const float gg = tanh_f(acc[j][2]);
-                const float go = sigmoid_f(acc[j][3]);
-                const float cprev = d1 ? creg[j] : cpv[j];
-                const float cn = gf * cprev + gi * gg;
-                const float hn = go * tanh_f(cn);
-                const size_t e = (pb * HT + mt) * 64 + lane;
-                reinterpret_cast<float4 *>(a.gates)[e] = make_float4(gi, gf, gg, go);
-                a.c[e] = cn;
-                a.hid[e] = hn;
-                if (a.out) a.out[e] = a.resid[e] + hn;
-                creg[j] = cn;
-                if (d1) hbuf[(p + 1) & 1][mt * 64 + lane] = hn;
-            }
-        }
-        if (d1) {
-            lds_barrier();
-        } else {
-            // the state of position p+1-d was written by all four waves: make
-            // those stores visible before anyone reads them back
-            __syncthreads();
-            if (p + 1 < a.P) {
-                if (p + 1 >= a.d) {
-                    const size_t rb = ((size_t)(p + 1 - a.d) * a.NB + bt) * htile;
+            for (int ks = 0; ks < HT; ++ks) bh[ks] = hb[ks * 64 + lane];
+            float *hn_buf = hbuf[(it + 1) & 1];
+            // tile by tile: the activations of one tile overlap the MFMAs of the next
 #pragma unroll
-                    for (int ks = 0; ks < HT; ++ks) bh[ks] = a.hid[rb + ks * 64 + lane];
+            for (int j = 0; j < MTW; ++j) {
+                const int mt = s + kLstmWaves * j;
+                if (j < MTW - 1 || mt < HT) {
 #pragma unroll
-                    for (int j = 0; j < MTW; ++j) {
-                        const int mt = s + kLstmWaves * j;
-                        cpv[j] = mt < HT ? a.c[rb + mt * 64 + lane] : 0.0f;
-                    }
+                    for (int ks = 0; ks < HT; ++ks) acc[j] = mfma16(wreg[j][KXT + ks], bh[ks], acc[j]);
+                    const float gi = sigmoid_f(acc[j][0]);
+                    const float gf = sigmoid_f(acc[j][1]);
+                    const float gg = tanh_f(acc[j][2]);
+                    const float go = sigmoid_f(acc[j][3]);
+                    const float cn = gf * creg[j] + gi * gg;
+                    const float hn = go * tanh_f(cn);
+                    creg[j] = cn;
+                    hn_buf[mt * 64 + lane] = hn;
+                    const size_t e = (pb * HT + mt) * 64 + lane;
+                    reinterpret_cast<float4 *>(a.gates)[e] = make_float4(gi, gf, gg, go);
+                    a.c[e] = cn;
+                    a.hid[e] = hn;
+                    if (a.out) a.out[e] = a.resid[e] + hn;
                 }
             }
+            // input part of the next position of the chain: independent of the
+            // recurrence, so it runs on the matrix pipe while the waves meet at
+            // the barrier
+            if (p + a.d < a.P) {
+#pragma unroll
+                for (int j = 0; j < MTW; ++j) acc[j] = bias[j];
+#pragma unroll
+                for (int ks = 0; ks < KXT; ++ks)
+#pragma unroll
+                    for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
+                if (p + 2 * a.d < a.P) {
+                    const size_t nb = ((size_t)(p + 2 * a.d) * a.NB + bt) * xtile;
+#pragma unroll
+                    for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
+                }
+            }
+            lds_barrier();
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// Reverse pass of one layer.  Per position p (descending):
+// Reverse pass of one layer.  Per position p of a chain (descending):
 //   A. every lane turns (dh, dc) of its hidden unit into the four gate
-//      pre-activation gradients da and leaves them in LDS;
-//   B. transposed contraction d[x_p ; h_{p-d}] = W^T da on the MFMA, with W^T
-//      register-resident; the row order of its output tiles is chosen so that
-//      the result is again laid out one unit tile per 64 lanes;
+//      pre-activation gradients da (registers), and leaves them in LDS next to
+//      [x_p ; h_{p-d}] for step C;
+//   B. transposed contraction d[x_p ; h_{p-d}] = W^T da on the MFMA, split over
+//      the waves along the contraction: a wave multiplies the k-steps of the
+//      units it owns, whose da it has just computed, so no operand crosses
+//      waves; the four partial results meet in LDS and every wave sums the
+//      output tiles it needs next (the recurrent dh of its own units) in a
+//      fixed order.  The row order of the output tiles (row 4g+r of tile mb is
+//      row g of input unit tile 4mb+r) keeps the result one unit tile per 64
+//      lanes;
 //   C. weight gradient dW += da (x) [x_p ; h_{p-d}]: contraction over the 16
-//      series on the MFMA, both operands read transposed from LDS; the tiles
-//      stay in accumulators for the whole launch.
+//      series on the MFMA, both operands read transposed from LDS; whole rows
+//      of tiles per wave, in accumulators for the whole launch.  Rows go to the
+//      waves in reverse order of unit ownership, which evens out the MFMA
+//      count of B plus C.
+// The loop is software-pipelined: the MFMAs of C(p) are issued together with
+// the elementwise work of A(p-d), whose global operands were requested one
+// position earlier.
 // ---------------------------------------------------------------------------
 struct LstmBwdArgs {
     const float *wpack;   // [MB][4*HT][64]
@@ -149,191 +162,261 @@ struct LstmBwdArgs {
     const float *gsrc;    // TL(HP) gradient arriving at the hidden output
     float *gdst;          // TL(4*KXT)
     const float *gadd;    // TL(HP) or null
-    float *dhr, *dcr;     // TL(HP) recurrent gradients, dilation >= 2
-    float *dw_partial;    // [NB][HT*MB][4][64]
-    float *db_partial;    // [NB][HT][4][4]
+    float *dw_partial;    // [NB*chains][HT*MB][4][64]
+    float *db_partial;    // [NB*chains][HT][4][4]
     int P, NB, d;
 };
 
 template <int HT, int KXT>
-__global__ void __launch_bounds__(64 * kLstmWaves) lstm_backward_kernel(LstmBwdArgs a)
+__global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_backward_kernel(LstmBwdArgs a)
 {
+    constexpr int W = kLstmWaves;
     constexpr int KT = KXT + HT;
-    constexpr int MB = (KT + 3) / 4;                                    // 16-row tiles of [x ; h]
-    constexpr int MTW = (HT + kLstmWaves - 1) / kLstmWaves;             // unit tiles per wave (step A)
-    constexpr int MBW = (MB + kLstmWaves - 1) / kLstmWaves;             // output tiles per wave (step B)
-    constexpr int NDW = HT * MB;                                        // weight-gradient tiles
-    constexpr int DWW = (NDW + kLstmWaves - 1) / kLstmWaves;            // ... per wave (step C)
+    constexpr int MB = (KT + 3) / 4;                 // 16-row tiles of [x ; h]
+    constexpr int MTW = (HT + W - 1) / W;            // unit tiles per wave
+    constexpr int QXW = (KXT + W - 1) / W;           // input unit tiles finalised per wave
+    constexpr int NT = 64 * W;
+    constexpr int DA_ROWS = 16 * W * MTW;            // includes dummy rows for tiles past HT
     constexpr int XH_ROWS = 16 * MB;
-    constexpr int NT = 64 * kLstmWaves;
+    constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
 
-    __shared__ float da_lds[HT * 16 * kLdsPad];        // [mt][4*gate + unit][series]
-    __shared__ float xh_lds[XH_ROWS * kLdsPad];        // [row of x ; h][series]
-    __shared__ float dh_lds[HT * 64];                  // recurrent dh for the next position (dilation 1)
+    __shared__ float da_lds[DA_ROWS * kLdsPad];      // [mt][4*gate + unit][series]
+    __shared__ float xh_lds[XH_ROWS * kLdsPad];      // [row of x ; h][series]
+    __shared__ float part_lds[W][MB * 4][64];        // partial d[x ; h] of every wave
 
     const int lane = threadIdx.x & 63, s = threadIdx.x >> 6, bt = blockIdx.x;
     const int g = lane >> 4, n = lane & 15;
-    const bool d1 = (a.d == 1);
+    const bool last_own_valid = s + W * (MTW - 1) < HT;           // unit tile s + 4(MTW-1)
+    const bool last_row_valid = (W - 1 - s) + W * (MTW - 1) < HT; // dW row (3-s) + 4(MTW-1)
+    const bool last_qx_valid = s + W * (QXW - 1) < KXT;
 
-    float wreg[MBW][4 * HT];
+    // W^T operands of the k-steps this wave owns: k-step 4*mt + gate, mt = s + 4j
+    float wreg[MB][4 * MTW];
 #pragma unroll
-    for (int j = 0; j < MBW; ++j) {
-        const int mb = s + kLstmWaves * j;
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int ks = 0; ks < 4 * HT; ++ks)
-            wreg[j][ks] = mb < MB ? a.wpack[((size_t)mb * 4 * HT + ks) * 64 + lane] : 0.0f;
-    }
-    f32x4 dw[DWW];
+        for (int j = 0; j < MTW; ++j) {
+            const int mt = s + W * j;
 #pragma unroll
-    for (int j = 0; j < DWW; ++j) dw[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int r = 0; r < 4; ++r)
+                wreg[mb][4 * j + r] = mt < HT ? a.wpack[((size_t)mb * 4 * HT + 4 * mt + r) * 64 + lane] : 0.0f;
+        }
+    f32x4 dw[MTW][MB];
     f32x4 dbacc[MTW];
-    float dcreg[MTW];
 #pragma unroll
-    for (int j = 0; j < MTW; ++j) { dbacc[j] = f32x4{0.f, 0.f, 0.f, 0.f}; dcreg[j] = 0.0f; }
-    for (int i = threadIdx.x; i < HT * 64; i += NT) dh_lds[i] = 0.0f;
+    for (int j = 0; j < MTW; ++j) {
+        dbacc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     for (int i = threadIdx.x; i < XH_ROWS * kLdsPad; i += NT) xh_lds[i] = 0.0f;
-    __syncthreads();
+    for (int i = threadIdx.x; i < DA_ROWS * kLdsPad; i += NT) da_lds[i] = 0.0f;
 
     const size_t xtile = (size_t)KXT * 64, htile = (size_t)HT * 64;
-    constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
 
-    for (int p = a.P - 1; p >= 0; --p) {
+    // ---- operands of one position, requested one position ahead; branch-free:
+    // tiles past HT alias the last tile, a missing predecessor aliases p itself
+    float4 pf_gt[MTW];
+    float pf_c[MTW], pf_cp[MTW], pf_g[MTW], pf_xh[XH_PER_THREAD], pf_ga[QXW];
+    auto fetch = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
         const bool has_prev = p >= a.d;
-        const size_t pbd = has_prev ? (size_t)(p - a.d) * a.NB + bt : 0;
+        const size_t pbd = (size_t)(has_prev ? p - a.d : p) * a.NB + bt;
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) {
+            const int mt = min(s + W * j, HT - 1);
+            const size_t e = (pb * HT + mt) * 64 + lane;
+            pf_gt[j] = reinterpret_cast<const float4 *>(a.gates)[e];
+            pf_c[j] = a.c[e];
+            pf_cp[j] = a.c[(pbd * HT + mt) * 64 + lane];
+            pf_g[j] = a.gsrc[e];
+        }
+#pragma unroll
+        for (int i = 0; i < XH_PER_THREAD; ++i) {
+            const int e = min((int)threadIdx.x + i * NT, KT * 64 - 1);
+            const float *src = e < KXT * 64 ? a.xsrc + pb * xtile + e : a.hid + pbd * htile + (e - KXT * 64);
+            pf_xh[i] = *src;
+        }
+    };
+    // residual-path addend of the input gradient of position p (needed when p is finalised)
+    auto fetch_ga = [&](int p) {
+        const size_t pb = (size_t)p * a.NB + bt;
+#pragma unroll
+        for (int j = 0; j < QXW; ++j) {
+            const int q = min(s + W * j, KXT - 1);
+            pf_ga[j] = a.gadd ? a.gadd[pb * xtile + q * 64 + lane] : 0.0f;
+        }
+    };
 
-        // [x_p ; h_{p-d}] into LDS, row-major with padded rows
+    float dcreg[MTW], dhreg[MTW];
+    float da[MTW][4];
+    // ---- step A for the fetched position p: gate gradients (registers and LDS) and [x ; h] (LDS)
+    auto step_a = [&](int p) {
+        const bool has_prev = p >= a.d;
 #pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
             const int e = threadIdx.x + i * NT;
-            if (e < KT * 64) {
-                float val;
-                if (e < KXT * 64) val = a.xsrc[pb * xtile + e];
-                else val = has_prev ? a.hid[pbd * htile + (e - KXT * 64)] : 0.0f;
-                xh_lds[(e >> 4) * kLdsPad + (e & 15)] = val;
-            }
+            if (e < KT * 64) xh_lds[(e >> 4) * kLdsPad + (e & 15)] = (e < KXT * 64 || has_prev) ? pf_xh[i] : 0.0f;
         }
-
-        // A: gate gradients of this wave's units
 #pragma unroll
         for (int j = 0; j < MTW; ++j) {
-            const int mt = s + kLstmWaves * j;
-            if (mt < HT) {
-                const size_t e = (pb * HT + mt) * 64 + lane;
-                const float4 gt = reinterpret_cast<const float4 *>(a.gates)[e];
-                const float cn = a.c[e];
-                const float cp = has_prev ? a.c[(pbd * HT + mt) * 64 + lane] : 0.0f;
-                float dh = a.gsrc[e];
-                float dc;
-                if (d1) {
-                    dh += dh_lds[mt * 64 + lane];
-                    dc = dcreg[j];
-                } else {
-                    const bool has_next = p + a.d < a.P;
-                    dh += has_next ? a.dhr[e] : 0.0f;
-                    dc = has_next ? a.dcr[e] : 0.0f;
-                }
-                const float tc = tanh_f(cn);
-                dc += dh * gt.w * (1.0f - tc * tc);
-                const float dai = dc * gt.z * gt.x * (1.0f - gt.x);
-                const float daf = dc * cp * gt.y * (1.0f - gt.y);
-                const float dag = dc * gt.x * (1.0f - gt.z * gt.z);
-                const float dao = dh * tc * gt.w * (1.0f - gt.w);
-                const float dcp = dc * gt.y;
-                if (d1) dcreg[j] = dcp;
-                else if (has_prev) a.dcr[(pbd * HT + mt) * 64 + lane] = dcp;
-                float *dst = da_lds + (mt * 16 + g) * kLdsPad + n;
-                dst[0 * 4 * kLdsPad] = dai;
-                dst[1 * 4 * kLdsPad] = daf;
-                dst[2 * 4 * kLdsPad] = dag;
-                dst[3 * 4 * kLdsPad] = dao;
-                dbacc[j][0] += dai; dbacc[j][1] += daf; dbacc[j][2] += dag; dbacc[j][3] += dao;
+            const float4 gt = pf_gt[j];
+            const float dh = pf_g[j] + dhreg[j];
+            const float tc = tanh_f(pf_c[j]);
+            const float dc = dcreg[j] + dh * gt.w * (1.0f - tc * tc);
+            const float cp = has_prev ? pf_cp[j] : 0.0f;
+            da[j][0] = dc * gt.z * gt.x * (1.0f - gt.x);
+            da[j][1] = dc * cp * gt.y * (1.0f - gt.y);
+            da[j][2] = dc * gt.x * (1.0f - gt.z * gt.z);
+            da[j][3] = dh * tc * gt.w * (1.0f - gt.w);
+            dcreg[j] = dc * gt.y;
+            float *dst = da_lds + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                dst[r * 4 * kLdsPad] = da[j][r];
+                dbacc[j][r] += da[j][r];
             }
         }
-        lds_barrier();
+    };
+    // ---- step B: partial W^T da over this wave's k-steps, into LDS
+    auto step_b = [&]() {
+        f32x4 acc[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < MTW - 1; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) acc[mb] = mfma16(wreg[mb][4 * j + r], da[j][r], acc[mb]);
+        if (last_own_valid) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    acc[mb] = mfma16(wreg[mb][4 * (MTW - 1) + r], da[MTW - 1][r], acc[mb]);
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part_lds[s][mb * 4 + r][lane] = acc[mb][r];
+    };
 
-        // B: d[x ; h] = W^T da
-        f32x4 acc[MBW];
+    for (int r0 = blockIdx.y; r0 < a.d && r0 < a.P; r0 += gridDim.y) {
+        const int p_last = r0 + ((a.P - 1 - r0) / a.d) * a.d;
+        // start of a chain: no gradient arrives from later positions
 #pragma unroll
-        for (int j = 0; j < MBW; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4 * HT; ++ks) {
-            // k-step 4mt+gate, contraction index = unit within the tile
-            const float bv = da_lds[((ks >> 2) * 16 + (ks & 3) * 4 + g) * kLdsPad + n];
-#pragma unroll
-            for (int j = 0; j < MBW; ++j) acc[j] = mfma16(wreg[j][ks], bv, acc[j]);
-        }
-#pragma unroll
-        for (int j = 0; j < MBW; ++j) {
-            const int mb = s + kLstmWaves * j;
-            if (mb < MB) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int q = 4 * mb + r;           // unit tile of [x ; h]
-                    if (q < KXT) {
-                        const size_t e = pb * xtile + q * 64 + lane;
-                        float val = acc[j][r];
-                        if (a.gadd) val += a.gadd[e];
-                        a.gdst[e] = val;
-                    } else if (q < KT) {
-                        const int mt = q - KXT;
-                        if (d1) dh_lds[mt * 64 + lane] = acc[j][r];   // read after the closing barrier
-                        else if (has_prev) a.dhr[(pbd * HT + mt) * 64 + lane] = acc[j][r];
-                    }
-                }
-            }
-        }
+        for (int j = 0; j < MTW; ++j) { dcreg[j] = 0.0f; dhreg[j] = 0.0f; }
+        __syncthreads();            // LDS free (previous chain / initial clearing)
+        fetch(p_last);
+        fetch_ga(p_last);
+        step_a(p_last);
+        if (p_last >= a.d) fetch(p_last - a.d);
+        step_b();
 
-        // C: dW tiles of this wave
+        for (int p = p_last; p >= 0; p -= a.d) {
+            const size_t pb = (size_t)p * a.NB + bt;
+            const bool has_prev = p >= a.d;
+            // the input-gradient addend of position p was requested one iteration ago
+            float ga[QXW];
 #pragma unroll
-        for (int j = 0; j < DWW; ++j) {
-            const int tix = s + kLstmWaves * j;
-            if (tix < NDW) {
-                const int mt = tix / MB, nbk = tix % MB;
-                const float *ap = da_lds + (mt * 16 + n) * kLdsPad + g;
-                const float *bp = xh_lds + (nbk * 16 + n) * kLdsPad + g;
+            for (int j = 0; j < QXW; ++j) ga[j] = pf_ga[j];
+            if (has_prev) fetch_ga(p - a.d);
+            lds_barrier();          // partials, da, [x ; h] of position p complete
+
+            // finalise the output tiles this wave needs or stores: sum of the four partials
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) dw[j] = mfma16(ap[4 * ks], bp[4 * ks], dw[j]);
+            for (int j = 0; j < MTW; ++j) {
+                const int q = min(KXT + s + W * j, KT - 1);
+                const int row = q;  // (q / 4) * 4 + q % 4
+                dhreg[j] = (part_lds[0][row][lane] + part_lds[1][row][lane]) +
+                           (part_lds[2][row][lane] + part_lds[3][row][lane]);
+            }
+            float dxv[QXW];
+#pragma unroll
+            for (int j = 0; j < QXW; ++j) {
+                const int q = min(s + W * j, KXT - 1);
+                dxv[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
+            }
+            // operands of C
+            float xb[MB][4], ar[MTW][4];
+#pragma unroll
+            for (int nbk = 0; nbk < MB; ++nbk)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) xb[nbk][ks] = xh_lds[(nbk * 16 + n) * kLdsPad + 4 * ks + g];
+#pragma unroll
+            for (int j = 0; j < MTW; ++j)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    ar[j][ks] = da_lds[(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
+            lds_barrier();          // everything of position p has been read
+
+#pragma unroll
+            for (int j = 0; j < QXW; ++j) {
+                if (j < QXW - 1 || last_qx_valid)
+                    a.gdst[pb * xtile + (s + W * j) * 64 + lane] = dxv[j] + ga[j];
+            }
+            // gate gradients of the next position, interleaved with the dW MFMAs of this one
+            if (has_prev) {
+                // (fetch(p - d) was issued one iteration ago)
+                step_a(p - a.d);
+            }
+#pragma unroll
+            for (int j = 0; j < MTW - 1; ++j)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = mfma16(ar[j][ks], xb[nbk][ks], dw[j][nbk]);
+            if (last_row_valid) {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int nbk = 0; nbk < MB; ++nbk)
+                        dw[MTW - 1][nbk] = mfma16(ar[MTW - 1][ks], xb[nbk][ks], dw[MTW - 1][nbk]);
+            }
+            if (has_prev) {
+                if (p >= 2 * a.d) fetch(p - 2 * a.d);
+                step_b();
             }
         }
-        if (d1) lds_barrier();
-        else __syncthreads();   // recurrent gradients go through global memory
     }
 
     // per-workgroup partial results
+    const size_t part = (size_t)bt * gridDim.y + blockIdx.y;
 #pragma unroll
-    for (int j = 0; j < DWW; ++j) {
-        const int tix = s + kLstmWaves * j;
-        if (tix < NDW) {
-            float *dst = a.dw_partial + ((size_t)bt * NDW + tix) * 256 + lane;
+    for (int j = 0; j < MTW; ++j) {
+        const int row = (W - 1 - s) + W * j;
+        if (row < HT) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) dst[r * 64] = dw[j][r];
+            for (int nbk = 0; nbk < MB; ++nbk) {
+                float *dst = a.dw_partial + (part * (HT * MB) + row * MB + nbk) * 256 + lane;
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) dst[rr * 64] = dw[j][nbk][rr];
+            }
         }
     }
 #pragma unroll
     for (int j = 0; j < MTW; ++j) {
-        const int mt = s + kLstmWaves * j;
-        if (mt < HT) {
+        const int mt = s + W * j;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float tot = group16_sum(dbacc[j][r]);
-                if (n == 0) a.db_partial[((size_t)bt * HT + mt) * 16 + g * 4 + r] = tot;
-            }
+        for (int rr = 0; rr < 4; ++rr) {
+            const float tot = group16_sum(dbacc[j][rr]);
+            if (n == 0 && mt < HT) a.db_partial[(part * HT + mt) * 16 + g * 4 + rr] = tot;
         }
     }
 }
 
 template <int HT, int KXT>
-hipError_t run_fwd(const LstmFwdArgs &a, hipStream_t st)
+hipError_t run_fwd(const LstmFwdArgs &a, int chains, hipStream_t st)
 {
-    lstm_forward_kernel<HT, KXT><<<a.NB, 64 * kLstmWaves, 0, st>>>(a);
+    lstm_forward_kernel<HT, KXT><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
     return hipGetLastError();
 }
 
 template <int HT, int KXT>
-hipError_t run_bwd(const LstmBwdArgs &a, hipStream_t st)
+hipError_t run_bwd(const LstmBwdArgs &a, int chains, hipStream_t st)
 {
-    lstm_backward_kernel<HT, KXT><<<a.NB, 64 * kLstmWaves, 0, st>>>(a);
+    lstm_backward_kernel<HT, KXT><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -346,7 +429,7 @@ hipError_t launch_lstm_forward(const Plan &pl, int layer, float *ws, hipStream_t
     const LayerPlan &lp = pl.layer[layer];
     LstmFwdArgs a{ws + lp.wpack_fwd, ws + lp.bias_pack, ws + lp.xsrc, ws + lp.gates, ws + lp.c, ws + lp.hid,
                   lp.out ? ws + lp.resid : nullptr, lp.out ? ws + lp.out : nullptr, pl.P, pl.NB, lp.dil};
-#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_fwd<HT_, KXT_>(a, st);
+#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_fwd<HT_, KXT_>(a, lp.chains, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;
@@ -356,9 +439,8 @@ hipError_t launch_lstm_backward(const Plan &pl, int layer, float *ws, hipStream_
 {
     const LayerPlan &lp = pl.layer[layer];
     LstmBwdArgs a{ws + lp.wpack_bwd, ws + lp.xsrc, ws + lp.gates, ws + lp.c, ws + lp.hid, ws + lp.gsrc, ws + lp.gdst,
-                  lp.gadd ? ws + lp.gadd : nullptr, lp.dil >= 2 ? ws + lp.dhr : nullptr,
-                  lp.dil >= 2 ? ws + lp.dcr : nullptr, ws + lp.dw_partial, ws + lp.db_partial, pl.P, pl.NB, lp.dil};
-#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, st);
+                  lp.gadd ? ws + lp.gadd : nullptr, ws + lp.dw_partial, ws + lp.db_partial, pl.P, pl.NB, lp.dil};
+#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

@@ -1,6 +1,7 @@
 // Host-side launch plan: validates a configuration, lays out the workspace and
 // the packed operand blocks.  No device work happens here.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 #include "esrnn_internal.h"
@@ -154,9 +155,13 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         lp.gates = ws.take(PN * tileH * 4);
         lp.c = ws.take(PN * tileH);
         lp.hid = ws.take(PN * tileH);
-        if (lp.dil >= 2) { lp.dhr = ws.take(PN * tileH); lp.dcr = ws.take(PN * tileH); }
-        lp.dw_partial = ws.take((size_t)pl.NB * pl.HT * MB * 256);
-        lp.db_partial = ws.take((size_t)pl.NB * pl.HT * 16);
+        // enough workgroups to put several on every compute unit, without more
+        // weight-gradient partials than the reduction can read cheaply
+        int max_chains = std::max(1, ceil_div(1024, pl.NB));
+        if (const char *e = std::getenv("ESRNN_MAX_CHAINS")) max_chains = std::max(1, std::atoi(e));
+        lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
+        lp.dw_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * MB * 256);
+        lp.db_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * 16);
         pl.dx[l] = (l > 0 && !lp.first_in_block) ? ws.take(PN * tileH) : 0;
     }
     // block outputs: block 0's is the hidden state of its last layer
