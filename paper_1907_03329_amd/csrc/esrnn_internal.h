@@ -31,9 +31,9 @@ struct LayerPlan {
     size_t resid, out;   // out = resid + hid for the last layer of a block >= 1 (0 = none)
     // backward operands
     size_t wpack_bwd;    // [MB][4*HT][64]    A operands of the transposed contraction
-    size_t gsrc;         // TL(HP) gradient arriving at this layer's hidden output
+    size_t gsrc[4];      // TL(HP): the gradient arriving at this layer's hidden output is the sum of these
+    int n_gsrc;
     size_t gdst;         // TL(4*KXT) gradient with respect to the layer input
-    size_t gadd;         // TL(HP) added to gdst (residual path), 0 = none
     int chains;          // workgroups per series tile; each walks the residue classes r, r+chains, ... (mod dil)
     size_t dw_partial;   // [NB*chains][HT*MB][4][64] per-workgroup weight-gradient tiles
     size_t db_partial;   // [NB*chains][HT][4][4]
@@ -58,8 +58,7 @@ struct Plan {
     size_t X, Z;         // TL(4*IT), TL(OP)
     size_t blk_out[ESRNN_MAX_BLOCKS];
     size_t A, O, gO, gTop, gX;
-    size_t gblk[ESRNN_MAX_BLOCKS];      // gradient with respect to each block output
-    size_t dx[kMaxLayers];
+    size_t dx[kMaxLayers];              // gradient with respect to the input of layer l (layer 0: gX)
     size_t head_fwd_pack, head_bwd_pack; // packed head operands
     size_t loss_partial; int n_loss_partial;   // double-aligned: [n][2] floats (pinball, level)
     size_t head_dw_partial; int n_head_waves;  // [n_head_waves][head_dw_stride]

@@ -74,10 +74,10 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         for (int ks = 0; ks < KXT; ++ks)
 #pragma unroll
             for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
-        if (r + a.d < a.P) {
+        {
+            const size_t nb = ((size_t)min(r + a.d, a.P - 1) * a.NB + bt) * xtile;
 #pragma unroll
-            for (int ks = 0; ks < KXT; ++ks)
-                bx[ks] = a.xsrc[((size_t)(r + a.d) * a.NB + bt) * xtile + ks * 64 + lane];
+            for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
         }
         lds_barrier();
 
@@ -122,11 +122,9 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                 for (int ks = 0; ks < KXT; ++ks)
 #pragma unroll
                     for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
-                if (p + 2 * a.d < a.P) {
-                    const size_t nb = ((size_t)(p + 2 * a.d) * a.NB + bt) * xtile;
+                const size_t nb = ((size_t)min(p + 2 * a.d, a.P - 1) * a.NB + bt) * xtile;
 #pragma unroll
-                    for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
-                }
+                for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
             }
             lds_barrier();
         }
@@ -159,9 +157,9 @@ struct LstmBwdArgs {
     const float *wpack;   // [MB][4*HT][64]
     const float *xsrc;    // TL(4*KXT)
     const float *gates, *c, *hid;
-    const float *gsrc;    // TL(HP) gradient arriving at the hidden output
+    const float *gsrc[4]; // TL(HP): the gradient arriving at the hidden output is the sum of these
+    int n_gsrc;
     float *gdst;          // TL(4*KXT)
-    const float *gadd;    // TL(HP) or null
     float *dw_partial;    // [NB*chains][HT*MB][4][64]
     float *db_partial;    // [NB*chains][HT][4][4]
     int P, NB, d;
@@ -177,11 +175,11 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     constexpr int QXW = (KXT + W - 1) / W;           // input unit tiles finalised per wave
     constexpr int NT = 64 * W;
     constexpr int DA_ROWS = 16 * W * MTW;            // includes dummy rows for tiles past HT
-    constexpr int XH_ROWS = 16 * MB;
     constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
+    constexpr int XH_ROWS = (16 * MB > 16 * XH_PER_THREAD) ? 16 * MB : 16 * XH_PER_THREAD;
 
     __shared__ float da_lds[DA_ROWS * kLdsPad];      // [mt][4*gate + unit][series]
-    __shared__ float xh_lds[XH_ROWS * kLdsPad];      // [row of x ; h][series]
+    __shared__ float xh_lds[XH_ROWS * kLdsPad];      // [row of x ; h][series]; rows past 4*KT are scratch
     __shared__ float part_lds[W][MB * 4][64];        // partial d[x ; h] of every wave
 
     const int lane = threadIdx.x & 63, s = threadIdx.x >> 6, bt = blockIdx.x;
@@ -198,8 +196,10 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
         for (int j = 0; j < MTW; ++j) {
             const int mt = s + W * j;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                wreg[mb][4 * j + r] = mt < HT ? a.wpack[((size_t)mb * 4 * HT + 4 * mt + r) * 64 + lane] : 0.0f;
+            for (int r = 0; r < 4; ++r) {
+                const float w = a.wpack[((size_t)mb * 4 * HT + 4 * min(mt, HT - 1) + r) * 64 + lane];
+                wreg[mb][4 * j + r] = mt < HT ? w : 0.0f;
+            }
         }
     f32x4 dw[MTW][MB];
     f32x4 dbacc[MTW];
@@ -214,14 +214,14 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 
     const size_t xtile = (size_t)KXT * 64, htile = (size_t)HT * 64;
 
-    // ---- operands of one position, requested one position ahead; branch-free:
-    // tiles past HT alias the last tile, a missing predecessor aliases p itself
+    // ---- operands of one position, requested one position ahead.  Branch-free:
+    // tiles past HT alias the last tile, a missing predecessor aliases p itself,
+    // elements past the end of [x ; h] alias its last element.
     float4 pf_gt[MTW];
-    float pf_c[MTW], pf_cp[MTW], pf_g[MTW], pf_xh[XH_PER_THREAD], pf_ga[QXW];
+    float pf_c[MTW], pf_cp[MTW], pf_g[MTW], pf_g2[MTW], pf_xh[XH_PER_THREAD];
     auto fetch = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
-        const bool has_prev = p >= a.d;
-        const size_t pbd = (size_t)(has_prev ? p - a.d : p) * a.NB + bt;
+        const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
 #pragma unroll
         for (int j = 0; j < MTW; ++j) {
             const int mt = min(s + W * j, HT - 1);
@@ -229,7 +229,8 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             pf_gt[j] = reinterpret_cast<const float4 *>(a.gates)[e];
             pf_c[j] = a.c[e];
             pf_cp[j] = a.c[(pbd * HT + mt) * 64 + lane];
-            pf_g[j] = a.gsrc[e];
+            pf_g[j] = a.gsrc[0][e];
+            pf_g2[j] = a.gsrc[1][e];    // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
         }
 #pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
@@ -237,45 +238,42 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             const float *src = e < KXT * 64 ? a.xsrc + pb * xtile + e : a.hid + pbd * htile + (e - KXT * 64);
             pf_xh[i] = *src;
         }
-    };
-    // residual-path addend of the input gradient of position p (needed when p is finalised)
-    auto fetch_ga = [&](int p) {
-        const size_t pb = (size_t)p * a.NB + bt;
+        if (a.n_gsrc > 2) {             // more than two residual blocks: rare, summed eagerly
 #pragma unroll
-        for (int j = 0; j < QXW; ++j) {
-            const int q = min(s + W * j, KXT - 1);
-            pf_ga[j] = a.gadd ? a.gadd[pb * xtile + q * 64 + lane] : 0.0f;
+            for (int j = 0; j < MTW; ++j) {
+                const size_t e = (pb * HT + min(s + W * j, HT - 1)) * 64 + lane;
+                for (int k = 2; k < a.n_gsrc; ++k) pf_g2[j] += a.gsrc[k][e];
+            }
         }
     };
 
+    const float g2_scale = a.n_gsrc >= 2 ? 1.0f : 0.0f;
     float dcreg[MTW], dhreg[MTW];
     float da[MTW][4];
-    // ---- step A for the fetched position p: gate gradients (registers and LDS) and [x ; h] (LDS)
-    auto step_a = [&](int p) {
-        const bool has_prev = p >= a.d;
+    // ---- step A, tile j of the fetched position: gate gradients to registers and LDS
+    auto step_a_tile = [&](int j, bool has_prev) {
+        const float4 gt = pf_gt[j];
+        const float dh = pf_g[j] + g2_scale * pf_g2[j] + dhreg[j];
+        const float tc = tanh_f(pf_c[j]);
+        const float dc = dcreg[j] + dh * gt.w * (1.0f - tc * tc);
+        const float cp = has_prev ? pf_cp[j] : 0.0f;
+        da[j][0] = dc * gt.z * gt.x * (1.0f - gt.x);
+        da[j][1] = dc * cp * gt.y * (1.0f - gt.y);
+        da[j][2] = dc * gt.x * (1.0f - gt.z * gt.z);
+        da[j][3] = dh * tc * gt.w * (1.0f - gt.w);
+        dcreg[j] = dc * gt.y;
+        float *dst = da_lds + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            dst[r * 4 * kLdsPad] = da[j][r];
+            dbacc[j][r] += da[j][r];
+        }
+    };
+    auto store_xh = [&](bool has_prev) {
 #pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
             const int e = threadIdx.x + i * NT;
-            if (e < KT * 64) xh_lds[(e >> 4) * kLdsPad + (e & 15)] = (e < KXT * 64 || has_prev) ? pf_xh[i] : 0.0f;
-        }
-#pragma unroll
-        for (int j = 0; j < MTW; ++j) {
-            const float4 gt = pf_gt[j];
-            const float dh = pf_g[j] + dhreg[j];
-            const float tc = tanh_f(pf_c[j]);
-            const float dc = dcreg[j] + dh * gt.w * (1.0f - tc * tc);
-            const float cp = has_prev ? pf_cp[j] : 0.0f;
-            da[j][0] = dc * gt.z * gt.x * (1.0f - gt.x);
-            da[j][1] = dc * cp * gt.y * (1.0f - gt.y);
-            da[j][2] = dc * gt.x * (1.0f - gt.z * gt.z);
-            da[j][3] = dh * tc * gt.w * (1.0f - gt.w);
-            dcreg[j] = dc * gt.y;
-            float *dst = da_lds + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                dst[r * 4 * kLdsPad] = da[j][r];
-                dbacc[j][r] += da[j][r];
-            }
+            xh_lds[(e >> 4) * kLdsPad + (e & 15)] = (e < KXT * 64 || has_prev) ? pf_xh[i] : 0.0f;
         }
     };
     // ---- step B: partial W^T da over this wave's k-steps, into LDS
@@ -301,6 +299,43 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 #pragma unroll
             for (int r = 0; r < 4; ++r) part_lds[s][mb * 4 + r][lane] = acc[mb][r];
     };
+    // ---- end of position p: sum the partials this wave needs (recurrent dh of its
+    // units) or stores (input gradient), and pull the operands of step C into registers
+    float xb[MB][4], ar[MTW][4];
+    auto finish = [&](int p) {
+        const size_t pb = (size_t)p * a.NB + bt;
+        lds_barrier();              // partials, da, [x ; h] of position p complete
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) {
+            const int q = min(KXT + s + W * j, KT - 1);   // row of part_lds = unit tile of [x ; h]
+            dhreg[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
+        }
+        float dxv[QXW];
+#pragma unroll
+        for (int j = 0; j < QXW; ++j) {
+            const int q = min(s + W * j, KXT - 1);
+            dxv[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
+        }
+#pragma unroll
+        for (int nbk = 0; nbk < MB; ++nbk)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) xb[nbk][ks] = xh_lds[(nbk * 16 + n) * kLdsPad + 4 * ks + g];
+#pragma unroll
+        for (int j = 0; j < MTW; ++j)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                ar[j][ks] = da_lds[(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
+        lds_barrier();              // everything of position p has been read
+#pragma unroll
+        for (int j = 0; j < QXW; ++j)
+            if (j < QXW - 1 || last_qx_valid) a.gdst[pb * xtile + (s + W * j) * 64 + lane] = dxv[j];
+    };
+    auto dw_row = [&](int j) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = mfma16(ar[j][ks], xb[nbk][ks], dw[j][nbk]);
+    };
 
     for (int r0 = blockIdx.y; r0 < a.d && r0 < a.P; r0 += gridDim.y) {
         const int p_last = r0 + ((a.P - 1 - r0) / a.d) * a.d;
@@ -309,76 +344,31 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
         for (int j = 0; j < MTW; ++j) { dcreg[j] = 0.0f; dhreg[j] = 0.0f; }
         __syncthreads();            // LDS free (previous chain / initial clearing)
         fetch(p_last);
-        fetch_ga(p_last);
-        step_a(p_last);
-        if (p_last >= a.d) fetch(p_last - a.d);
+        store_xh(p_last >= a.d);
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d);
+        fetch(max(p_last - a.d, r0));
         step_b();
 
-        for (int p = p_last; p >= 0; p -= a.d) {
-            const size_t pb = (size_t)p * a.NB + bt;
-            const bool has_prev = p >= a.d;
-            // the input-gradient addend of position p was requested one iteration ago
-            float ga[QXW];
+        for (int p = p_last; p >= a.d; p -= a.d) {
+            finish(p);
+            // gate gradients of position p - d (elementwise) interleaved with the dW MFMAs of p
+            const bool has_prev = p >= 2 * a.d;
+            store_xh(has_prev);
 #pragma unroll
-            for (int j = 0; j < QXW; ++j) ga[j] = pf_ga[j];
-            if (has_prev) fetch_ga(p - a.d);
-            lds_barrier();          // partials, da, [x ; h] of position p complete
-
-            // finalise the output tiles this wave needs or stores: sum of the four partials
-#pragma unroll
-            for (int j = 0; j < MTW; ++j) {
-                const int q = min(KXT + s + W * j, KT - 1);
-                const int row = q;  // (q / 4) * 4 + q % 4
-                dhreg[j] = (part_lds[0][row][lane] + part_lds[1][row][lane]) +
-                           (part_lds[2][row][lane] + part_lds[3][row][lane]);
+            for (int j = 0; j < MTW - 1; ++j) {
+                step_a_tile(j, has_prev);
+                dw_row(j);
             }
-            float dxv[QXW];
-#pragma unroll
-            for (int j = 0; j < QXW; ++j) {
-                const int q = min(s + W * j, KXT - 1);
-                dxv[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
-            }
-            // operands of C
-            float xb[MB][4], ar[MTW][4];
-#pragma unroll
-            for (int nbk = 0; nbk < MB; ++nbk)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) xb[nbk][ks] = xh_lds[(nbk * 16 + n) * kLdsPad + 4 * ks + g];
-#pragma unroll
-            for (int j = 0; j < MTW; ++j)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    ar[j][ks] = da_lds[(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
-            lds_barrier();          // everything of position p has been read
-
-#pragma unroll
-            for (int j = 0; j < QXW; ++j) {
-                if (j < QXW - 1 || last_qx_valid)
-                    a.gdst[pb * xtile + (s + W * j) * 64 + lane] = dxv[j] + ga[j];
-            }
-            // gate gradients of the next position, interleaved with the dW MFMAs of this one
-            if (has_prev) {
-                // (fetch(p - d) was issued one iteration ago)
-                step_a(p - a.d);
-            }
-#pragma unroll
-            for (int j = 0; j < MTW - 1; ++j)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                    for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = mfma16(ar[j][ks], xb[nbk][ks], dw[j][nbk]);
-            if (last_row_valid) {
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                    for (int nbk = 0; nbk < MB; ++nbk)
-                        dw[MTW - 1][nbk] = mfma16(ar[MTW - 1][ks], xb[nbk][ks], dw[MTW - 1][nbk]);
-            }
-            if (has_prev) {
-                if (p >= 2 * a.d) fetch(p - 2 * a.d);
-                step_b();
-            }
+            step_a_tile(MTW - 1, has_prev);
+            fetch(max(p - 2 * a.d, r0));
+            if (last_row_valid) dw_row(MTW - 1);
+            step_b();
         }
+        finish(r0);
+#pragma unroll
+        for (int j = 0; j < MTW - 1; ++j) dw_row(j);
+        if (last_row_valid) dw_row(MTW - 1);
     }
 
     // per-workgroup partial results
@@ -438,8 +428,12 @@ hipError_t launch_lstm_forward(const Plan &pl, int layer, float *ws, hipStream_t
 hipError_t launch_lstm_backward(const Plan &pl, int layer, float *ws, hipStream_t st)
 {
     const LayerPlan &lp = pl.layer[layer];
-    LstmBwdArgs a{ws + lp.wpack_bwd, ws + lp.xsrc, ws + lp.gates, ws + lp.c, ws + lp.hid, ws + lp.gsrc, ws + lp.gdst,
-                  lp.gadd ? ws + lp.gadd : nullptr, ws + lp.dw_partial, ws + lp.db_partial, pl.P, pl.NB, lp.dil};
+    LstmBwdArgs a{};
+    a.wpack = ws + lp.wpack_bwd; a.xsrc = ws + lp.xsrc; a.gates = ws + lp.gates; a.c = ws + lp.c; a.hid = ws + lp.hid;
+    a.n_gsrc = lp.n_gsrc;
+    for (int k = 0; k < 4; ++k) a.gsrc[k] = ws + lp.gsrc[k < lp.n_gsrc ? k : 0];
+    a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
+    a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
 #define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X

@@ -143,8 +143,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.A = ws.take(PN * tileH);
     pl.O = ws.take(PN * (size_t)pl.OP * 16);
     pl.gO = ws.take(PN * (size_t)pl.OP * 16);
-    for (int k = 0; k < cfg.n_blocks; ++k) pl.gblk[k] = ws.take(PN * tileH);
-    pl.gTop = pl.gblk[cfg.n_blocks - 1];
+    pl.gTop = ws.take(PN * tileH);
     for (int l = 0; l < L; ++l) {
         LayerPlan &lp = pl.layer[l];
         const int KT = lp.KXT + pl.HT;
@@ -162,7 +161,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
         lp.dw_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * MB * 256);
         lp.db_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * 16);
-        pl.dx[l] = (l > 0 && !lp.first_in_block) ? ws.take(PN * tileH) : 0;
+        pl.dx[l] = l > 0 ? ws.take(PN * tileH) : pl.gX;
     }
     // block outputs: block 0's is the hidden state of its last layer
     for (int l = 0; l < L; ++l) {
@@ -179,11 +178,18 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         else if (lp.first_in_block) lp.xsrc = pl.blk_out[lp.block - 1];
         else lp.xsrc = pl.layer[l - 1].hid;
         if (lp.last_in_block && lp.block >= 1) { lp.resid = pl.blk_out[lp.block - 1]; lp.out = pl.blk_out[lp.block]; }
-        // backward wiring
-        lp.gsrc = lp.last_in_block ? pl.gblk[lp.block] : pl.dx[l + 1];
-        if (l == 0) { lp.gdst = pl.gX; lp.gadd = 0; }
-        else if (lp.first_in_block) { lp.gdst = pl.gblk[lp.block - 1]; lp.gadd = pl.gblk[lp.block]; }
-        else { lp.gdst = pl.dx[l]; lp.gadd = 0; }
+        // backward wiring.  The output of block k feeds the first layer of every
+        // later block through the residual sums, and the head: the gradient
+        // arriving at its last layer is the sum of those input gradients.
+        lp.gdst = pl.dx[l];
+        lp.n_gsrc = 0;
+        if (lp.last_in_block) {
+            lp.gsrc[lp.n_gsrc++] = pl.gTop;
+            for (int m = l + 1; m < L; ++m)
+                if (pl.layer[m].first_in_block) lp.gsrc[lp.n_gsrc++] = pl.dx[m];
+        } else {
+            lp.gsrc[lp.n_gsrc++] = pl.dx[l + 1];
+        }
     }
     const HeadPack hp = head_pack_layout(pl);
     pl.head_fwd_pack = ws.take(hp.fwd_total);
