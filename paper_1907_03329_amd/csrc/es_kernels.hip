@@ -162,6 +162,7 @@ struct EsArgs {
     int row_gamma1, row_gamma2, row_s1, row_s2;
 };
 
+template <int NS>
 __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
 {
     extern __shared__ float ring[];   // [m1 + m2][64]
@@ -174,20 +175,20 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
     float alpha = 0.5f, g1 = 0.0f, g2 = 0.0f;
     if (in_batch) {
         alpha = a.es[b];
-        if (a.n_seas >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
-        if (a.n_seas >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
+        if (NS >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
+        if (NS >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
         if (a.logit) {
             alpha = 1.0f / (1.0f + expf(-alpha));
             g1 = 1.0f / (1.0f + expf(-g1));
             g2 = 1.0f / (1.0f + expf(-g2));
         }
     }
-    if (a.n_seas >= 1)
+    if (NS >= 1)
         for (int k = 0; k < a.m1; ++k) {
             float s = in_batch ? a.es[(size_t)(a.row_s1 + k) * a.B + b] : 1.0f;
             ring1[k * 64 + lane] = (a.logit && in_batch) ? expf(s) : s;
         }
-    if (a.n_seas >= 2)
+    if (NS >= 2)
         for (int k = 0; k < a.m2; ++k) {
             float s = in_batch ? a.es[(size_t)(a.row_s2 + k) * a.B + b] : 1.0f;
             ring2[k * 64 + lane] = (a.logit && in_batch) ? expf(s) : s;
@@ -196,41 +197,61 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
     float l_prev = 1.0f, u1 = 0.0f, u2 = 0.0f, lv_sum = 0.0f;
     int i1 = 0, i2 = 0;
     const float one_m_alpha = 1.0f - alpha;
-    float y_next = (0 < len) ? a.y[b] : 1.0f;
-    for (int t = 0; t < a.T; ++t) {
-        const bool live = t < len;
-        const float yt = y_next;
-        if (t + 1 < a.T) y_next = (t + 1 < len) ? a.y[(size_t)(t + 1) * a.B + b] : 1.0f;
-        float s1 = 1.0f, s2 = 1.0f;
-        if (a.n_seas >= 1) s1 = ring1[i1 * 64 + lane];
-        if (a.n_seas >= 2) s2 = ring2[i2 * 64 + lane];
-        const float q = yt / (s1 * s2);
-        // reading for the state before the first observation: l_{-1} = y_0 / S[0]
-        const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
-        if (t >= 1) {
-            // Eq. (3): divide by the previous level (and the other factor)
-            if (a.n_seas >= 1) ring1[i1 * 64 + lane] = g1 * (yt / (l_prev * s2)) + (1.0f - g1) * s1;
-            if (a.n_seas >= 2) ring2[i2 * 64 + lane] = g2 * (yt / (l_prev * s1)) + (1.0f - g2) * s2;
+    // observations are requested a chunk ahead so that no step waits for memory
+    constexpr int CH = 8;
+    float ybuf[CH], ynext[CH];
+    auto load_chunk = [&](int t0, float *dst) {
+#pragma unroll
+        for (int k = 0; k < CH; ++k) {
+            const int t = t0 + k;
+            const float val = a.y[(size_t)(t < len ? t : 0) * a.B + (in_batch ? b : 0)];
+            dst[k] = t < len ? val : 1.0f;
         }
-        const float ut = live ? logf(lt) : 0.0f;
-        const float vt = live ? logf(yt) - logf(s1 * s2) : 0.0f;
-        if (store) {
-            const size_t o = (size_t)t * a.Bp + b;
-            a.lvl[o] = live ? lt : 1.0f;
-            a.u[o] = ut;
-            a.v[o] = vt;
-            if (a.n_seas >= 1) a.S1[o] = live ? s1 : 1.0f;
-            if (a.n_seas >= 2) a.S2[o] = live ? s2 : 1.0f;
+    };
+    load_chunk(0, ybuf);
+    for (int t0 = 0; t0 < a.T; t0 += CH) {
+        load_chunk(t0 + CH, ynext);
+#pragma unroll
+        for (int k = 0; k < CH; ++k) {
+            const int t = t0 + k;
+            if (t < a.T) {
+                const bool live = t < len;
+                const float yt = ybuf[k];
+                float s1 = 1.0f, s2 = 1.0f;
+                if (NS >= 1) s1 = ring1[i1 * 64 + lane];
+                if (NS >= 2) s2 = ring2[i2 * 64 + lane];
+                const float q = (yt) * fast_rcp(s1 * s2);
+                // reading for the state before the first observation: l_{-1} = y_0 / S[0]
+                const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
+                if (t >= 1) {
+                    // Eq. (3): divide by the previous level (and the other factor)
+                    const float ry = (yt) * fast_rcp(l_prev);
+                    if (NS >= 1) ring1[i1 * 64 + lane] = g1 * (ry) * fast_rcp(s2) + (1.0f - g1) * s1;
+                    if (NS >= 2) ring2[i2 * 64 + lane] = g2 * (ry) * fast_rcp(s1) + (1.0f - g2) * s2;
+                }
+                const float ut = live ? __logf(lt) : 0.0f;
+                const float vt = live ? __logf(q) : 0.0f;      // ln y - ln(S1 S2)
+                if (store) {
+                    const size_t o = (size_t)t * a.Bp + b;
+                    a.lvl[o] = live ? lt : 1.0f;
+                    a.u[o] = ut;
+                    a.v[o] = vt;
+                    if (NS >= 1) a.S1[o] = live ? s1 : 1.0f;
+                    if (NS >= 2) a.S2[o] = live ? s2 : 1.0f;
+                }
+                // Section 8.4: squared second difference of the log level
+                if (live && t >= 2) {
+                    const float e = ut - 2.0f * u1 + u2;
+                    lv_sum += e * e;
+                }
+                u2 = u1; u1 = ut;
+                if (live) l_prev = lt;
+                if (NS >= 1 && ++i1 == a.m1) i1 = 0;
+                if (NS >= 2 && ++i2 == a.m2) i2 = 0;
+            }
         }
-        // Section 8.4: squared second difference of the log level
-        if (live && t >= 2) {
-            const float e = ut - 2.0f * u1 + u2;
-            lv_sum += e * e;
-        }
-        u2 = u1; u1 = ut;
-        if (live) l_prev = lt;
-        if (a.n_seas >= 1 && ++i1 == a.m1) i1 = 0;
-        if (a.n_seas >= 2 && ++i2 == a.m2) i2 = 0;
+#pragma unroll
+        for (int k = 0; k < CH; ++k) ybuf[k] = ynext[k];
     }
     const float tot = wave_sum(lv_sum);
     if (lane == 0) a.lv_partial[blockIdx.x] = tot;
@@ -355,6 +376,7 @@ struct EsBwdArgs {
     int row_gamma1, row_gamma2, row_s1, row_s2;
 };
 
+template <int NS>
 __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
 {
     extern __shared__ float ring[];
@@ -364,8 +386,8 @@ __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
     const int len = clamp_len(a.lengths[b], a.T);
     float *ring1 = ring, *ring2 = ring + (size_t)a.m1 * 64;
     float alpha = a.es[b], g1 = 0.0f, g2 = 0.0f;
-    if (a.n_seas >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
-    if (a.n_seas >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
+    if (NS >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
+    if (NS >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
     if (a.logit) {
         alpha = 1.0f / (1.0f + expf(-alpha));
         g1 = 1.0f / (1.0f + expf(-g1));
@@ -377,44 +399,69 @@ __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
     float Lb_carry = 0.0f;      // contributions to the adjoint of l[t] from later steps
     int i1 = 0, i2 = 0;
     if (len > 0) {
-        if (a.n_seas >= 1) i1 = (len - 1) % a.m1;
-        if (a.n_seas >= 2) i2 = (len - 1) % a.m2;
+        if (NS >= 1) i1 = (len - 1) % a.m1;
+        if (NS >= 2) i2 = (len - 1) % a.m2;
     }
-    for (int t = len - 1; t >= 1; --t) {
-        const size_t o = (size_t)t * a.Bp + b;
-        const float yt = a.y[(size_t)t * a.B + b];
-        const float lt = a.lvl[o], lp = a.lvl[o - a.Bp];
-        const float s1 = a.n_seas >= 1 ? a.S1[o] : 1.0f;
-        const float s2 = a.n_seas >= 2 ? a.S2[o] : 1.0f;
-        const float gvt = a.gv[o];
-        const float Lb = a.gu[o] / lt + Lb_carry;
-        float S1b = a.n_seas >= 1 ? -gvt / s1 : 0.0f;
-        float S2b = a.n_seas >= 2 ? -gvt / s2 : 0.0f;
-        float Lb_prev = 0.0f;
-        if (a.n_seas >= 1) {
-            const float A = (t + a.m1 <= len - 1) ? ring1[i1 * 64 + lane] : 0.0f;
-            const float r = yt / (lp * s2);
-            g1b += A * (r - s1);
-            Lb_prev -= A * g1 * r / lp;
-            S2b -= A * g1 * r / s2;
-            S1b += A * (1.0f - g1);
+    // operands are requested a chunk of steps ahead (descending in time)
+    constexpr int CH = 4;
+    struct Chunk { float gu[CH], gv[CH], y[CH], lp[CH], s1[CH], s2[CH]; };
+    Chunk cur, nxt;
+    auto load_chunk = [&](int t_hi, Chunk &c) {
+#pragma unroll
+        for (int k = 0; k < CH; ++k) {
+            const int t = t_hi - k;
+            const int tc = t >= 1 ? t : 1;                 // steps below 1 are not executed
+            const size_t o = (size_t)tc * a.Bp + b;
+            c.gu[k] = a.gu[o];
+            c.gv[k] = a.gv[o];
+            c.y[k] = a.y[(size_t)tc * a.B + b];
+            c.lp[k] = a.lvl[o - a.Bp];
+            c.s1[k] = NS >= 1 ? a.S1[o] : 1.0f;
+            c.s2[k] = NS >= 2 ? a.S2[o] : 1.0f;
         }
-        if (a.n_seas >= 2) {
-            const float A = (t + a.m2 <= len - 1) ? ring2[i2 * 64 + lane] : 0.0f;
-            const float r = yt / (lp * s1);
-            g2b += A * (r - s2);
-            Lb_prev -= A * g2 * r / lp;
-            S1b -= A * g2 * r / s1;
-            S2b += A * (1.0f - g2);
+    };
+    float lt = len >= 1 ? a.lvl[(size_t)(len - 1) * a.Bp + b] : 1.0f;
+    if (len >= 2) load_chunk(len - 1, cur);
+    for (int t_hi = len - 1; t_hi >= 1; t_hi -= CH) {
+        if (t_hi - CH >= 1) load_chunk(t_hi - CH, nxt);
+#pragma unroll
+        for (int k = 0; k < CH; ++k) {
+            const int t = t_hi - k;
+            if (t >= 1) {
+                const float yt = cur.y[k], lp = cur.lp[k], s1 = cur.s1[k], s2 = cur.s2[k], gvt = cur.gv[k];
+                const float Lb = (cur.gu[k]) * fast_rcp(lt) + Lb_carry;
+                float S1b = NS >= 1 ? -(gvt) * fast_rcp(s1) : 0.0f;
+                float S2b = NS >= 2 ? -(gvt) * fast_rcp(s2) : 0.0f;
+                float Lb_prev = 0.0f;
+                const float ry = (yt) * fast_rcp(lp);
+                if (NS >= 1) {
+                    const float A = (t + a.m1 <= len - 1) ? ring1[i1 * 64 + lane] : 0.0f;
+                    const float r = (ry) * fast_rcp(s2);
+                    g1b += A * (r - s1);
+                    Lb_prev -= (A * g1 * r) * fast_rcp(lp);
+                    S2b -= (A * g1 * r) * fast_rcp(s2);
+                    S1b += A * (1.0f - g1);
+                }
+                if (NS >= 2) {
+                    const float A = (t + a.m2 <= len - 1) ? ring2[i2 * 64 + lane] : 0.0f;
+                    const float r = (ry) * fast_rcp(s1);
+                    g2b += A * (r - s2);
+                    Lb_prev -= (A * g2 * r) * fast_rcp(lp);
+                    S1b -= (A * g2 * r) * fast_rcp(s1);
+                    S2b += A * (1.0f - g2);
+                }
+                const float q = (yt) * fast_rcp(s1 * s2);
+                ab += Lb * (q - lp);
+                S1b -= (Lb * alpha * q) * fast_rcp(s1);
+                S2b -= (Lb * alpha * q) * fast_rcp(s2);
+                Lb_prev += Lb * (1.0f - alpha);
+                if (NS >= 1) { ring1[i1 * 64 + lane] = S1b; if (--i1 < 0) i1 = a.m1 - 1; }
+                if (NS >= 2) { ring2[i2 * 64 + lane] = S2b; if (--i2 < 0) i2 = a.m2 - 1; }
+                Lb_carry = Lb_prev;
+                lt = lp;
+            }
         }
-        const float q = yt / (s1 * s2);
-        ab += Lb * (q - lp);
-        S1b -= Lb * alpha * q / s1;
-        S2b -= Lb * alpha * q / s2;
-        Lb_prev += Lb * (1.0f - alpha);
-        if (a.n_seas >= 1) { ring1[i1 * 64 + lane] = S1b; if (--i1 < 0) i1 = a.m1 - 1; }
-        if (a.n_seas >= 2) { ring2[i2 * 64 + lane] = S2b; if (--i2 < 0) i2 = a.m2 - 1; }
-        Lb_carry = Lb_prev;
+        cur = nxt;
     }
     if (len >= 1) {
         // t = 0: l[0] = y0 / (S1[0] S2[0]); the first produced factors equal the initial ones
@@ -422,19 +469,19 @@ __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
         const float l0 = a.lvl[o];
         const float Lb = a.gu[o] / l0 + Lb_carry;
         const float gv0 = a.gv[o];
-        if (a.n_seas >= 1) {
+        if (NS >= 1) {
             const float s1 = a.S1[o];
             const float A = (a.m1 <= len - 1) ? ring1[lane] : 0.0f;
             ring1[lane] = -gv0 / s1 + A - Lb * l0 / s1;
         }
-        if (a.n_seas >= 2) {
+        if (NS >= 2) {
             const float s2 = a.S2[o];
             const float A = (a.m2 <= len - 1) ? ring2[lane] : 0.0f;
             ring2[lane] = -gv0 / s2 + A - Lb * l0 / s2;
         }
     }
     a.grad_es[b] = a.logit ? ab * alpha * (1.0f - alpha) : ab;
-    if (a.n_seas >= 1) {
+    if (NS >= 1) {
         a.grad_es[(size_t)a.row_gamma1 * a.B + b] = a.logit ? g1b * g1 * (1.0f - g1) : g1b;
         for (int k = 0; k < a.m1; ++k) {
             float gs = (k < len) ? ring1[k * 64 + lane] : 0.0f;
@@ -442,7 +489,7 @@ __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
             a.grad_es[(size_t)(a.row_s1 + k) * a.B + b] = gs;
         }
     }
-    if (a.n_seas >= 2) {
+    if (NS >= 2) {
         a.grad_es[(size_t)a.row_gamma2 * a.B + b] = a.logit ? g2b * g2 * (1.0f - g2) : g2b;
         for (int k = 0; k < a.m2; ++k) {
             float gs = (k < len) ? ring2[k * 64 + lane] : 0.0f;
@@ -456,6 +503,39 @@ __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
 // Weight-gradient reduction: sums the per-workgroup (LSTM) and per-wave (head)
 // partial tiles in a fixed order and writes the caller's packing.
 // ---------------------------------------------------------------------------
+// Stage 1: every job (one block of partial results per producer workgroup or
+// wave) is cut into `splits` interleaved subsets of the producers; a thread sums
+// one element over one subset.  Stage 2 (the kernels below) sums the subsets and
+// writes the caller's packing.  Both orders are fixed.
+struct ReduceJob {
+    const float *src;
+    float *dst;          // [splits][n_elems]
+    unsigned stride;     // floats between consecutive partial blocks
+    int n_part, n_elems, splits;
+};
+constexpr int kMaxReduceJobs = 2 * kMaxLayers + 1;
+struct ReduceJobs {
+    ReduceJob job[kMaxReduceJobs];
+};
+
+__global__ void __launch_bounds__(256) reduce_stage1_kernel(ReduceJobs jobs)
+{
+    const ReduceJob &j = jobs.job[blockIdx.z];
+    const int e = blockIdx.x * 256 + threadIdx.x, sp = blockIdx.y;
+    if (sp >= j.splits || e >= j.n_elems) return;
+    const float *src = j.src + e;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int w = sp;
+    for (; w + 3 * j.splits < j.n_part; w += 4 * j.splits) {
+        a0 += src[(size_t)w * j.stride];
+        a1 += src[(size_t)(w + j.splits) * j.stride];
+        a2 += src[(size_t)(w + 2 * j.splits) * j.stride];
+        a3 += src[(size_t)(w + 3 * j.splits) * j.stride];
+    }
+    for (; w < j.n_part; w += j.splits) a0 += src[(size_t)w * j.stride];
+    j.dst[(size_t)sp * j.n_elems + e] = (a0 + a1) + (a2 + a3);
+}
+
 struct ReduceLstmArgs {
     const float *dw_partial, *db_partial;
     float *gW, *gb;
@@ -590,13 +670,18 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
              pl.B, pl.Bp, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
              c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
     const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(es_forward_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    es_forward_kernel<<<pl.es_blocks, 64, lds, st>>>(a);
-    return hipGetLastError();
+    auto run = [&](auto kernel) {
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        kernel<<<pl.es_blocks, 64, lds, st>>>(a);
+        return hipGetLastError();
+    };
+    if (c.n_seas == 0) return run(es_forward_kernel<0>);
+    if (c.n_seas == 1) return run(es_forward_kernel<1>);
+    return run(es_forward_kernel<2>);
 }
 
 hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st)
@@ -631,30 +716,55 @@ hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *len
                 pl.B, pl.Bp, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
                 c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
     const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(es_backward_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    es_backward_kernel<<<(pl.B + 63) / 64, 64, lds, st>>>(a);
-    return hipGetLastError();
+    auto run = [&](auto kernel) {
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        kernel<<<(pl.B + 63) / 64, 64, lds, st>>>(a);
+        return hipGetLastError();
+    };
+    if (c.n_seas == 0) return run(es_backward_kernel<0>);
+    if (c.n_seas == 1) return run(es_backward_kernel<1>);
+    return run(es_backward_kernel<2>);
 }
 
 hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_weights, hipStream_t st)
 {
+    ReduceJobs jobs{};
+    int nj = 0, max_elems = 0, max_splits = 1;
+    auto add = [&](size_t src, size_t dst, size_t stride, int n_part, int n_elems) {
+        const int splits = n_part < kReduceSplits ? n_part : kReduceSplits;
+        jobs.job[nj++] = ReduceJob{ws + src, ws + dst, (unsigned)stride, n_part, n_elems, splits};
+        if (n_elems > max_elems) max_elems = n_elems;
+        if (splits > max_splits) max_splits = splits;
+        return splits;
+    };
+    int lstm_splits[kMaxLayers];
     for (int l = 0; l < pl.L; ++l) {
         const LayerPlan &lp = pl.layer[l];
-        ReduceLstmArgs a{ws + lp.dw_partial, ws + lp.db_partial, grad_weights + lp.w_off, grad_weights + lp.b_off,
-                         pl.NB * lp.chains, pl.h, lp.in_dim, pl.HT, lp.KXT};
+        const int MB = (lp.KXT + pl.HT + 3) / 4;
+        const int n_dw = pl.HT * MB * 256, n_db = pl.HT * 16;
+        lstm_splits[l] = add(lp.dw_partial, lp.dw_reduced, n_dw, pl.NB * lp.chains, n_dw);
+        add(lp.db_partial, lp.db_reduced, n_db, pl.NB * lp.chains, n_db);
+    }
+    const int n_head = (pl.MO * pl.MA + pl.MA * pl.MA) * 256 + 4 * pl.OT + 4 * pl.HT;
+    const int head_splits = add(pl.head_dw_partial, pl.head_dw_reduced, pl.head_dw_stride, pl.n_head_waves, n_head);
+    reduce_stage1_kernel<<<dim3((max_elems + 255) / 256, max_splits, nj), 256, 0, st>>>(jobs);
+
+    for (int l = 0; l < pl.L; ++l) {
+        const LayerPlan &lp = pl.layer[l];
+        ReduceLstmArgs a{ws + lp.dw_reduced, ws + lp.db_reduced, grad_weights + lp.w_off, grad_weights + lp.b_off,
+                         lstm_splits[l], pl.h, lp.in_dim, pl.HT, lp.KXT};
         const int MB = (lp.KXT + pl.HT + 3) / 4;
         const int blocks = (pl.HT * MB * 256 + 63) / 64 + (pl.HT * 16 + 63) / 64;
         reduce_lstm_kernel<<<blocks, 256, 0, st>>>(a);
     }
-    ReduceHeadArgs a{ws + pl.head_dw_partial, grad_weights + pl.Wa_off, grad_weights + pl.ba_off,
+    ReduceHeadArgs a{ws + pl.head_dw_reduced, grad_weights + pl.Wa_off, grad_weights + pl.ba_off,
                      grad_weights + pl.Wo_off, grad_weights + pl.bo_off,
-                     pl.n_head_waves, pl.head_dw_stride, pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
-    const int total = (pl.MO * pl.MA + pl.MA * pl.MA) * 256 + 4 * pl.OT + 4 * pl.HT;
-    reduce_head_kernel<<<(total + 63) / 64, 256, 0, st>>>(a);
+                     head_splits, n_head, pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
+    reduce_head_kernel<<<(n_head + 63) / 64, 256, 0, st>>>(a);
     return hipGetLastError();
 }
 

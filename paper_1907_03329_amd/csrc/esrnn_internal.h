@@ -13,6 +13,7 @@ namespace esrnn {
 constexpr int kTileN = 16;       // series per tile (N of the 16x16x4 fp32 MFMA)
 constexpr int kMaxLayers = ESRNN_MAX_BLOCKS * ESRNN_MAX_LAYERS_PER_BLOCK;
 constexpr int kLstmWaves = 4;    // waves per workgroup in the LSTM kernels
+constexpr int kReduceSplits = 16; // subsets of producers in the first stage of the weight-gradient reduction
 constexpr int kLdsPad = 17;      // row stride of LDS arrays that are read transposed
 
 // Tile layout TL(R): [P][NB][R][16]; element (p, b, r) at ((p*NB + b/16)*R + r)*16 + b%16.
@@ -37,6 +38,7 @@ struct LayerPlan {
     int chains;          // workgroups per series tile; each walks the residue classes r, r+chains, ... (mod dil)
     size_t dw_partial;   // [NB*chains][HT*MB][4][64] per-workgroup weight-gradient tiles
     size_t db_partial;   // [NB*chains][HT][4][4]
+    size_t dw_reduced, db_reduced;   // [kReduceSplits][...] first reduction stage
 };
 
 struct Plan {
@@ -63,6 +65,7 @@ struct Plan {
     size_t loss_partial; int n_loss_partial;   // double-aligned: [n][2] floats (pinball, level)
     size_t head_dw_partial; int n_head_waves;  // [n_head_waves][head_dw_stride]
     int head_dw_stride;
+    size_t head_dw_reduced;
     int es_blocks;
     size_t total_floats;
 };

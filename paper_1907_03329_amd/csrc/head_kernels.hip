@@ -56,23 +56,56 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
 
     float loss = 0.0f;
     const long long n_tiles = (long long)a.P * a.NB;
-    for (long long tile = (long long)blockIdx.x * 4 + wv; tile < n_tiles; tile += (long long)gridDim.x * 4) {
+    const long long stride = (long long)gridDim.x * 4;
+
+    // operands of one tile; those of the next tile are requested before this one is computed
+    struct Ops {
+        float br[HT];
+        float z[4 * MO], seas[4 * MO];
+        float ut;
+        int len;
+    };
+    auto load_ops = [&](long long tile_, Ops &o) {
+        const long long tile = tile_ < n_tiles ? tile_ : n_tiles - 1;
         const int p = (int)(tile / a.NB), bt = (int)(tile % a.NB);
         const int b = bt * 16 + n;
-        int len = 0;
-        if (b < a.B) { len = a.lengths[b]; len = len < 0 ? 0 : (len > a.T ? a.T : len); }
+        const int t = p + a.I - 1;
+#pragma unroll
+        for (int q = 0; q < HT; ++q) o.br[q] = a.R[(size_t)tile * HT * 64 + q * 64 + lane];
+        o.len = a.lengths[b < a.B ? b : a.B - 1];
+        o.ut = a.u[(size_t)t * a.Bp + b];
+#pragma unroll
+        for (int mo = 0; mo < MO; ++mo)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int j = 16 * mo + 4 * g + r;
+                o.z[4 * mo + r] = a.Z[((size_t)tile * OP + j) * 16 + n];
+                const int tj = t + 1 + j < a.T ? t + 1 + j : a.T - 1;
+                float sv = 1.0f;
+                if (a.n_seas >= 1) sv = a.S1[(size_t)tj * a.Bp + b];
+                if (a.n_seas >= 2) sv *= a.S2[(size_t)tj * a.Bp + b];
+                o.seas[4 * mo + r] = sv;
+            }
+    };
+
+    Ops cur, nxt;
+    long long tile = (long long)blockIdx.x * 4 + wv;
+    if (tile < n_tiles) load_ops(tile, cur);
+    for (; tile < n_tiles; tile += stride) {
+        load_ops(tile + stride, nxt);
+        const int p = (int)(tile / a.NB), bt = (int)(tile % a.NB);
+        const int b = bt * 16 + n;
+        int len = cur.len < 0 ? 0 : (cur.len > a.T ? a.T : cur.len);
+        if (b >= a.B) len = 0;
         const bool valid = p < len - a.I - a.H + 1;
 
-        float br[HT];
-#pragma unroll
-        for (int q = 0; q < HT; ++q) br[q] = a.R[(size_t)tile * HT * 64 + q * 64 + lane];
         f32x4 acc[MA];
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma) acc[ma] = ba[ma];
 #pragma unroll
         for (int q = 0; q < HT; ++q)
 #pragma unroll
-            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(wa[ma][q], br[q], acc[ma]);
+            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(wa[ma][q], cur.br[q], acc[ma]);
         float av[4 * MA];
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma)
@@ -90,8 +123,6 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
 #pragma unroll
             for (int mo = 0; mo < MO; ++mo) oc[mo] = mfma16(wo[mo][q], av[q], oc[mo]);
 
-        const int t = p + a.I - 1;
-        const float ut = a.u[(size_t)t * a.Bp + b];
 #pragma unroll
         for (int mo = 0; mo < MO; ++mo)
 #pragma unroll
@@ -102,23 +133,17 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
                 a.O[e] = o;
                 if (j < a.H) {
                     if (valid) {
-                        const float d = a.Z[e] - o;
+                        const float d = cur.z[4 * mo + r] - o;
                         loss += d >= 0.0f ? a.tau * d : (a.tau - 1.0f) * d;
                     }
                     if (a.forecasts && b < a.B) {
-                        float f = 0.0f;
-                        if (valid) {
-                            // Eq. (5): exp(output) * level * seasonal factors of the target time
-                            const size_t ts = (size_t)(t + 1 + j) * a.Bp + b;
-                            float seas = 1.0f;
-                            if (a.n_seas >= 1) seas = a.S1[ts];
-                            if (a.n_seas >= 2) seas *= a.S2[ts];
-                            f = expf(o + ut) * seas;
-                        }
+                        // Eq. (5): exp(output) * level * seasonal factors of the target time
+                        const float f = valid ? __expf(o + cur.ut) * cur.seas[4 * mo + r] : 0.0f;
                         a.forecasts[((size_t)p * a.B + b) * a.H + j] = f;
                     }
                 }
             }
+        cur = nxt;
     }
     const float tot = wave_sum(loss);
     if (lane == 0) s_part[wv] = tot;
@@ -179,11 +204,41 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
 
     const float inv_n = a.sc->inv_n_pin;
     const long long n_tiles = (long long)a.P * a.NB;
-    for (long long tile = (long long)blockIdx.x * 4 + wv; tile < n_tiles; tile += (long long)gridDim.x * 4) {
+    const long long stride = (long long)gridDim.x * 4;
+
+    // operands of one tile; those of the next tile are requested before this one is computed
+    struct Ops {
+        float d[OTMAX];          // target minus output, row 4*ks + g
+        float av[4 * MA], rv[4 * MA];
+        int len;
+    };
+    auto load_ops = [&](long long tile_, Ops &o) {
+        const long long tile = tile_ < n_tiles ? tile_ : n_tiles - 1;
+        const int bt = (int)(tile % a.NB);
+        const int b = bt * 16 + n;
+        o.len = a.lengths[b < a.B ? b : a.B - 1];
+#pragma unroll
+        for (int ks = 0; ks < OTMAX; ++ks) {
+            const size_t e = ((size_t)tile * OP + 4 * ks + g) * 16 + n;
+            o.d[ks] = a.Z[e] - a.O[e];
+        }
+#pragma unroll
+        for (int q = 0; q < 4 * MA; ++q) {
+            const int qc = q < HT ? q : HT - 1;
+            o.av[q] = a.A[(size_t)tile * HT * 64 + qc * 64 + lane];
+            o.rv[q] = a.R[(size_t)tile * HT * 64 + qc * 64 + lane];
+        }
+    };
+
+    Ops cur, nxt;
+    long long tile = (long long)blockIdx.x * 4 + wv;
+    if (tile < n_tiles) load_ops(tile, cur);
+    for (; tile < n_tiles; tile += stride) {
+        load_ops(tile + stride, nxt);
         const int p = (int)(tile / a.NB), bt = (int)(tile % a.NB);
         const int b = bt * 16 + n;
-        int len = 0;
-        if (b < a.B) { len = a.lengths[b]; len = len < 0 ? 0 : (len > a.T ? a.T : len); }
+        int len = cur.len < 0 ? 0 : (cur.len > a.T ? a.T : cur.len);
+        if (b >= a.B) len = 0;
         const bool valid = p < len - a.I - a.H + 1;
 
         // gradient of the pinball loss, one row (horizon step) per k-step lane group
@@ -192,11 +247,7 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
         for (int ks = 0; ks < OTMAX; ++ks) {
             const int j = 4 * ks + g;
             const size_t e = ((size_t)tile * OP + j) * 16 + n;
-            float val = 0.0f;
-            if (valid && j < a.H) {
-                const float d = a.Z[e] - a.O[e];
-                val = (d >= 0.0f ? -a.tau : 1.0f - a.tau) * inv_n;
-            }
+            const float val = (valid && j < a.H) ? (cur.d[ks] >= 0.0f ? -a.tau : 1.0f - a.tau) * inv_n : 0.0f;
             go[ks] = val;
             a.gO[e] = val;
             go_l[j * kLdsPad + n] = val;
@@ -216,11 +267,7 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int q = 4 * ma + r;
-                float av = 0.0f, rv = 0.0f;
-                if (q < HT) {
-                    av = a.A[(size_t)tile * HT * 64 + q * 64 + lane];
-                    rv = a.R[(size_t)tile * HT * 64 + q * 64 + lane];
-                }
+                const float av = q < HT ? cur.av[q] : 0.0f, rv = q < HT ? cur.rv[q] : 0.0f;
                 dp[q] = acc[ma][r] * (1.0f - av * av);
                 dba[q] += dp[q];
                 const int row = 4 * q + g;
@@ -259,6 +306,7 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
                 for (int ks = 0; ks < 4; ++ks)
                     dWa[ma * MA + na] = mfma16(dp_l[(16 * ma + n) * kLdsPad + 4 * ks + g],
                                                r_l[(16 * na + n) * kLdsPad + 4 * ks + g], dWa[ma * MA + na]);
+        cur = nxt;
     }
 
     // per-wave partial block: dWo tiles, dWa tiles, dbo, dba

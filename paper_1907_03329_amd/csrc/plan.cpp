@@ -161,6 +161,8 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
         lp.dw_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * MB * 256);
         lp.db_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * 16);
+        lp.dw_reduced = ws.take((size_t)kReduceSplits * pl.HT * MB * 256);
+        lp.db_reduced = ws.take((size_t)kReduceSplits * pl.HT * 16);
         pl.dx[l] = l > 0 ? ws.take(PN * tileH) : pl.gX;
     }
     // block outputs: block 0's is the hidden state of its last layer
@@ -200,6 +202,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.head_dw_stride = (pl.MO * pl.MA + pl.MA * pl.MA) * 256 + 4 * pl.OT + 4 * pl.HT;
     pl.head_dw_stride = (pl.head_dw_stride + 63) & ~63;
     pl.head_dw_partial = ws.take((size_t)pl.n_head_waves * pl.head_dw_stride);
+    pl.head_dw_reduced = ws.take((size_t)kReduceSplits * pl.head_dw_stride);
     pl.es_blocks = ceil_div(pl.Bp, 64);
     pl.n_loss_partial = head_blocks + pl.es_blocks;
     pl.loss_partial = ws.take((size_t)pl.n_loss_partial);
