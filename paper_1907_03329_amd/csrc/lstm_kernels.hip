@@ -79,11 +79,23 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
 #pragma unroll
             for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
         }
+        // residual input of the block (last layer of a block >= 1), one position ahead like the input
+        float res[MTW];
+#pragma unroll
+        for (int j = 0; j < MTW; ++j)
+            res[j] = a.out ? a.resid[(((size_t)r * a.NB + bt) * HT + min(s + kLstmWaves * j, HT - 1)) * 64 + lane] : 0.0f;
         lds_barrier();
 
         int it = 0;
         for (int p = r; p < a.P; p += a.d, ++it) {
             const size_t pb = (size_t)p * a.NB + bt;
+            float res_next[MTW];
+            if (a.out) {
+                const size_t nb = ((size_t)min(p + a.d, a.P - 1) * a.NB + bt) * HT;
+#pragma unroll
+                for (int j = 0; j < MTW; ++j)
+                    res_next[j] = a.resid[(nb + min(s + kLstmWaves * j, HT - 1)) * 64 + lane];
+            }
             // recurrent part
             const float *hb = hbuf[it & 1];
             float bh[HT];
@@ -109,7 +121,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                     reinterpret_cast<float4 *>(a.gates)[e] = make_float4(gi, gf, gg, go);
                     a.c[e] = cn;
                     a.hid[e] = hn;
-                    if (a.out) a.out[e] = a.resid[e] + hn;
+                    if (a.out) a.out[e] = res[j] + hn;
                 }
             }
             // input part of the next position of the chain: independent of the
@@ -125,6 +137,11 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                 const size_t nb = ((size_t)min(p + 2 * a.d, a.P - 1) * a.NB + bt) * xtile;
 #pragma unroll
                 for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
+
+            }
+            if (a.out) {
+#pragma unroll
+                for (int j = 0; j < MTW; ++j) res[j] = res_next[j];
             }
             lds_barrier();
         }
