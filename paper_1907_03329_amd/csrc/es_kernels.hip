@@ -1,6 +1,8 @@
 // Streaming kernels of the training step: loss normalisers, operand packing,
 // exponential-smoothing recursions (forward and adjoint), window extraction
 // (forward and adjoint), loss reduction and weight-gradient reduction.
+#include <algorithm>
+
 #include "device_utils.h"
 #include "esrnn_internal.h"
 
@@ -13,9 +15,17 @@ __device__ __forceinline__ int clamp_len(int len, int T) { return len < 0 ? 0 : 
 // ---------------------------------------------------------------------------
 // Loss normalisers (Section 3.5: padded outputs are masked out of the loss).
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) prep_kernel(const int32_t *__restrict__ lengths, int B, int T, int I, int H,
-                                                    Scalars *__restrict__ sc)
+struct PrepArgs {
+    const int32_t *lengths;
+    Scalars *sc;
+    int B, T, I, H;
+};
+
+__device__ void prep_body(const PrepArgs &pa)
 {
+    const int32_t *__restrict__ lengths = pa.lengths;
+    Scalars *__restrict__ sc = pa.sc;
+    const int B = pa.B, T = pa.T, I = pa.I, H = pa.H;
     __shared__ double s_pin[256], s_lv[256];
     double np_ = 0.0, nl = 0.0;
     for (int b = threadIdx.x; b < B; b += 256) {
@@ -51,7 +61,7 @@ struct PackLstmArgs {
     int h, in_dim, HT, KXT;
 };
 
-__global__ void __launch_bounds__(256) pack_lstm_kernel(PackLstmArgs a)
+__device__ void pack_lstm_body(const PackLstmArgs &a)
 {
     const int KT = a.KXT + a.HT, MB = (KT + 3) / 4, ld = a.in_dim + a.h;
     const int n_fwd = a.HT * KT * 64, n_bias = a.HT * 16, n_bwd = MB * 4 * a.HT * 64;
@@ -92,7 +102,7 @@ struct PackHeadArgs {
     int h, H, HT, MA, MO, OT;
 };
 
-__global__ void __launch_bounds__(256) pack_head_kernel(PackHeadArgs a)
+__device__ void pack_head_body(const PackHeadArgs &a)
 {
     const int nWaF = a.MA * a.HT * 64, nbaF = a.MA * 16, nWoF = a.MO * a.HT * 64, nboF = a.MO * 16;
     const int nWoT = a.MA * a.OT * 64, nWaT = a.MA * a.HT * 64;
@@ -142,6 +152,23 @@ __global__ void __launch_bounds__(256) pack_head_kernel(PackHeadArgs a)
             a.WaT[j] = (unit < a.h && row < a.h) ? a.Wa[row * a.h + unit] : 0.0f;
         }
     }
+}
+
+// One launch for everything that only depends on the weights and the lengths:
+// blockIdx.z selects an LSTM layer, the output stage, or the loss normalisers.
+struct SetupArgs {
+    PackLstmArgs lstm[kMaxLayers];
+    PackHeadArgs head;
+    PrepArgs prep;
+    int L;
+};
+
+__global__ void __launch_bounds__(256) setup_kernel(SetupArgs a)
+{
+    const int z = blockIdx.z;
+    if (z < a.L) pack_lstm_body(a.lstm[z]);
+    else if (z == a.L) pack_head_body(a.head);
+    else if (blockIdx.x == 0) prep_body(a.prep);
 }
 
 // ---------------------------------------------------------------------------
@@ -565,9 +592,8 @@ __device__ __forceinline__ float reduce_partials(const float *__restrict__ base,
     return (s_red[0][e] + s_red[1][e]) + (s_red[2][e] + s_red[3][e]);
 }
 
-__global__ void __launch_bounds__(256) reduce_lstm_kernel(ReduceLstmArgs a)
+__device__ void reduce_lstm_body(const ReduceLstmArgs &a, float (*s_red)[64])
 {
-    __shared__ float s_red[4][64];
     const int KT = a.KXT + a.HT, MB = (KT + 3) / 4, ld = a.in_dim + a.h;
     const int n_dw = a.HT * MB * 256, n_db = a.HT * 16;
     const int n_dw_blocks = (n_dw + 63) / 64;
@@ -602,9 +628,8 @@ struct ReduceHeadArgs {
     int n_part, stride, h, H, HT, MA, MO, OT;
 };
 
-__global__ void __launch_bounds__(256) reduce_head_kernel(ReduceHeadArgs a)
+__device__ void reduce_head_body(const ReduceHeadArgs &a, float (*s_red)[64])
 {
-    __shared__ float s_red[4][64];
     // partial block: dWo tiles [MO*MA][4][64], dWa tiles [MA*MA][4][64], dbo [4*OT], dba [4*HT]
     const int offWa = a.MO * a.MA * 256, offbo = offWa + a.MA * a.MA * 256, offba = offbo + 4 * a.OT;
     const int n = offba + 4 * a.HT;
@@ -630,34 +655,45 @@ __global__ void __launch_bounds__(256) reduce_head_kernel(ReduceHeadArgs a)
     }
 }
 
+struct ReduceStage2Args {
+    ReduceLstmArgs lstm[kMaxLayers];
+    ReduceHeadArgs head;
+    int L;
+};
+
+__global__ void __launch_bounds__(256) reduce_stage2_kernel(ReduceStage2Args a)
+{
+    __shared__ float s_red[4][64];
+    const int z = blockIdx.z;
+    if (z < a.L) reduce_lstm_body(a.lstm[z], s_red);
+    else reduce_head_body(a.head, s_red);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
-hipError_t launch_prep(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st)
+hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *weights, float *ws, hipStream_t st)
 {
-    prep_kernel<<<1, 256, 0, st>>>(lengths, pl.B, pl.T, pl.I, pl.H, reinterpret_cast<Scalars *>(ws + pl.scalars));
-    return hipGetLastError();
-}
-
-hipError_t launch_pack_weights(const Plan &pl, const float *weights, float *ws, hipStream_t st)
-{
+    SetupArgs a{};
+    a.L = pl.L;
+    int max_total = 256;
     for (int l = 0; l < pl.L; ++l) {
         const LayerPlan &lp = pl.layer[l];
-        PackLstmArgs a{weights + lp.w_off, weights + lp.b_off, ws + lp.wpack_fwd, ws + lp.bias_pack, ws + lp.wpack_bwd,
-                       pl.h, lp.in_dim, pl.HT, lp.KXT};
+        a.lstm[l] = PackLstmArgs{weights + lp.w_off, weights + lp.b_off, ws + lp.wpack_fwd, ws + lp.bias_pack,
+                                 ws + lp.wpack_bwd, pl.h, lp.in_dim, pl.HT, lp.KXT};
         const int KT = lp.KXT + pl.HT, MB = (KT + 3) / 4;
-        const int total = pl.HT * KT * 64 + pl.HT * 16 + MB * 4 * pl.HT * 64;
-        pack_lstm_kernel<<<(total + 255) / 256, 256, 0, st>>>(a);
+        max_total = std::max(max_total, pl.HT * KT * 64 + pl.HT * 16 + MB * 4 * pl.HT * 64);
     }
     const HeadPack hp = head_pack_layout(pl);
     float *f = ws + pl.head_fwd_pack, *b = ws + pl.head_bwd_pack;
-    PackHeadArgs a{weights + pl.Wa_off, weights + pl.ba_off, weights + pl.Wo_off, weights + pl.bo_off,
-                   f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, b + hp.WoT, b + hp.WaT,
-                   pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
-    const int total = pl.MA * pl.HT * 64 * 2 + pl.MA * 16 + pl.MO * pl.HT * 64 + pl.MO * 16 + pl.MA * pl.OT * 64;
-    pack_head_kernel<<<(total + 255) / 256, 256, 0, st>>>(a);
+    a.head = PackHeadArgs{weights + pl.Wa_off, weights + pl.ba_off, weights + pl.Wo_off, weights + pl.bo_off,
+                          f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, b + hp.WoT, b + hp.WaT,
+                          pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
+    a.prep = PrepArgs{lengths, reinterpret_cast<Scalars *>(ws + pl.scalars), pl.B, pl.T, pl.I, pl.H};
+    const int blocks = std::min((max_total + 255) / 256, 64);   // the bodies loop over their elements
+    setup_kernel<<<dim3(blocks, 1, pl.L + 2), 256, 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -753,18 +789,20 @@ hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_wei
     const int head_splits = add(pl.head_dw_partial, pl.head_dw_reduced, pl.head_dw_stride, pl.n_head_waves, n_head);
     reduce_stage1_kernel<<<dim3((max_elems + 255) / 256, max_splits, nj), 256, 0, st>>>(jobs);
 
+    ReduceStage2Args r{};
+    r.L = pl.L;
+    int max_blocks = (n_head + 63) / 64;
     for (int l = 0; l < pl.L; ++l) {
         const LayerPlan &lp = pl.layer[l];
-        ReduceLstmArgs a{ws + lp.dw_reduced, ws + lp.db_reduced, grad_weights + lp.w_off, grad_weights + lp.b_off,
-                         lstm_splits[l], pl.h, lp.in_dim, pl.HT, lp.KXT};
+        r.lstm[l] = ReduceLstmArgs{ws + lp.dw_reduced, ws + lp.db_reduced, grad_weights + lp.w_off,
+                                   grad_weights + lp.b_off, lstm_splits[l], pl.h, lp.in_dim, pl.HT, lp.KXT};
         const int MB = (lp.KXT + pl.HT + 3) / 4;
-        const int blocks = (pl.HT * MB * 256 + 63) / 64 + (pl.HT * 16 + 63) / 64;
-        reduce_lstm_kernel<<<blocks, 256, 0, st>>>(a);
+        max_blocks = std::max(max_blocks, (pl.HT * MB * 256 + 63) / 64 + (pl.HT * 16 + 63) / 64);
     }
-    ReduceHeadArgs a{ws + pl.head_dw_reduced, grad_weights + pl.Wa_off, grad_weights + pl.ba_off,
-                     grad_weights + pl.Wo_off, grad_weights + pl.bo_off,
-                     head_splits, n_head, pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
-    reduce_head_kernel<<<(n_head + 63) / 64, 256, 0, st>>>(a);
+    r.head = ReduceHeadArgs{ws + pl.head_dw_reduced, grad_weights + pl.Wa_off, grad_weights + pl.ba_off,
+                            grad_weights + pl.Wo_off, grad_weights + pl.bo_off,
+                            head_splits, n_head, pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
+    reduce_stage2_kernel<<<dim3(max_blocks, 1, pl.L + 1), 256, 0, st>>>(r);
     return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ struct esrnn_handle {
     int n_stages;
     Stage stage[kMaxStages];
     // stage indices
-    int st_prep, st_pack, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head_fwd, st_loss;
+    int st_setup, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head_fwd, st_loss;
     int st_head_bwd, st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce;
 };
 
@@ -80,8 +80,7 @@ esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
     h->profiling = false;
     h->n_stages = 0;
     const Plan &pl = h->plan;
-    h->st_prep = add_stage(h, "prep", 0);
-    h->st_pack = add_stage(h, "pack_weights", 0);
+    h->st_setup = add_stage(h, "setup", 0);
     h->st_es_fwd = add_stage(h, "es_forward", 0);
     h->st_win_fwd = add_stage(h, "window_forward", 0);
     for (int l = 0; l < pl.L; ++l) h->st_lstm_fwd[l] = add_stage(h, "lstm_forward_l%d", l);
@@ -151,8 +150,7 @@ esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengt
     float *ws = static_cast<float *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     h->forward_done = false;
-    ESRNN_TRY(run_stage(h, h->st_prep, st, [&] { return launch_prep(pl, lengths, ws, st); }));
-    ESRNN_TRY(run_stage(h, h->st_pack, st, [&] { return launch_pack_weights(pl, weights, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_setup, st, [&] { return launch_setup(pl, lengths, weights, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, lengths, es_params, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, ws, st); }));
     for (int l = 0; l < pl.L; ++l)

@@ -89,8 +89,7 @@ HeadPack head_pack_layout(const Plan &pl);
 esrnn_status build_plan(const esrnn_config &cfg, Plan &pl);
 
 // ---- kernel launchers (each returns hipGetLastError()) -----------------------------------
-hipError_t launch_prep(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
-hipError_t launch_pack_weights(const Plan &pl, const float *weights, float *ws, hipStream_t st);
+hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *weights, float *ws, hipStream_t st);
 hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,
                              float *ws, hipStream_t st);
 hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st);
