@@ -125,3 +125,80 @@ def test_results_are_deterministic():
     assert torch.equal(s1.loss, s2.loss)
     assert torch.equal(s1.grad_weights, s2.grad_weights)
     assert torch.equal(s1.grad_es_params, s2.grad_es_params)
+
+
+def test_single_window_position():
+    """T = I + H: exactly one window position, every recurrence has one step."""
+    cfg = small("one_position", T=12, I=4, H=8, B=18)
+    report(gc.run_and_check(cfg, seed=16))
+
+
+def test_dilation_longer_than_the_window_sequence():
+    """Dilations beyond the number of positions: the state never arrives, every chain has one step."""
+    cfg = small("long_dilation", T=20, I=4, H=8, blocks=((1, 12), (30,)), B=18)
+    report(gc.run_and_check(cfg, seed=17, ragged=True))
+
+
+def test_period_close_to_series_length():
+    """Seasonal period of the order of the shortest series: most initial factors are never updated."""
+    cfg = small("long_period", T=40, m1=24, I=4, H=8, B=33)
+
+    def mutate(inp):
+        inp["lengths"][1::2] = 14      # shorter than the period (I + H = 12 <= 14 < 24)
+        inp["y"][np.arange(cfg.T)[:, None] >= inp["lengths"][None, :]] = 1.0
+
+    report(gc.run_and_check(cfg, seed=18, mutate=mutate))
+
+
+def test_large_dilations_many_chains():
+    """Hourly-like dilations (24, 168) on a short batch: many workgroups per series tile."""
+    cfg = small("chains", T=260, n_seas=2, m1=24, m2=168, seas_sd2=0.1, I=24, H=48, hidden=40,
+                blocks=((1, 4), (24, 168)), B=20)
+    report(gc.run_and_check(cfg, seed=19))
+
+
+def test_extreme_smoothing_parameters():
+    """alpha -> 1 and gamma -> 0 (closed-form cases of the smoothing recursions) on the GPU."""
+    cfg = small("extreme", B=20)
+
+    def mutate(inp):
+        rows = synth.es_param_rows(cfg)
+        inp["es_params"][rows["alpha"], :10] = 1.0
+        inp["es_params"][rows["gamma1"], 5:15] = 0.0
+
+    errs = gc.run_and_check(cfg, seed=20, mutate=mutate)
+    report(errs)
+
+
+def test_backward_before_forward_is_refused():
+    import torch
+    from paper_1907_03329_amd import binding
+    cfg = small("order", B=16)
+    step = binding.TrainingStep(cfg)
+    dev = gc.to_device(synth.make_inputs(cfg, seed=21))
+    with pytest.raises(binding.EsrnnError) as ei:
+        step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    assert ei.value.status == 4
+    step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    torch.cuda.synchronize()
+    step.close()
+
+
+def test_forecasts_may_be_omitted_and_stream_is_honoured():
+    import torch
+    from paper_1907_03329_amd import binding
+    cfg = small("nofc", B=24)
+    inp = synth.make_inputs(cfg, seed=22)
+    dev = gc.to_device(inp)
+    ref = gc.run_gpu(cfg, inp)
+    step = binding.TrainingStep(cfg, want_forecasts=False)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"], stream=side)
+        step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"], stream=side)
+    side.synchronize()
+    assert torch.equal(step.loss, ref.loss)
+    assert torch.equal(step.grad_weights, ref.grad_weights)
+    assert torch.equal(step.grad_es_params, ref.grad_es_params)
