@@ -62,8 +62,9 @@ struct Plan {
     size_t A, O, gO, gTop, gX;
     size_t dx[kMaxLayers];              // gradient with respect to the input of layer l (layer 0: gX)
     size_t head_fwd_pack, head_bwd_pack; // packed head operands
-    size_t loss_partial; int n_loss_partial;   // double-aligned: [n][2] floats (pinball, level)
-    size_t head_dw_partial; int n_head_waves;  // [n_head_waves][head_dw_stride]
+    size_t loss_partial; int n_loss_partial;   // [head_fwd_blocks] pinball sums, then [es_blocks] level-penalty sums
+    int head_fwd_blocks;                       // workgroups of the output-stage forward kernel
+    size_t head_dw_partial; int n_head_waves;  // [n_head_waves][head_dw_stride]; waves of the reverse kernel
     int head_dw_stride;
     size_t head_dw_reduced;
     int es_blocks;

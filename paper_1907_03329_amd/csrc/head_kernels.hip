@@ -344,7 +344,7 @@ hipError_t launch_head_forward(const Plan &pl, const int32_t *lengths, float *ws
 {
     const HeadPack hp = head_pack_layout(pl);
     const float *f = ws + pl.head_fwd_pack;
-    const int blocks = pl.n_head_waves / 4;
+    const int blocks = pl.head_fwd_blocks;
     HeadFwdArgs a{f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z,
                   ws + pl.u, ws + pl.S1, ws + pl.S2, lengths, ws + pl.A, ws + pl.O, forecasts, ws + pl.loss_partial,
                   pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.cfg.tau};

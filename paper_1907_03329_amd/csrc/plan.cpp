@@ -156,7 +156,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         lp.hid = ws.take(PN * tileH);
         // enough workgroups to put several on every compute unit, without more
         // weight-gradient partials than the reduction can read cheaply
-        int max_chains = std::max(1, ceil_div(1024, pl.NB));
+        int max_chains = std::max(1, ceil_div(512, pl.NB));
         if (const char *e = std::getenv("ESRNN_MAX_CHAINS")) max_chains = std::max(1, std::atoi(e));
         lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
         lp.dw_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * MB * 256);
@@ -197,8 +197,10 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.head_fwd_pack = ws.take(hp.fwd_total);
     pl.head_bwd_pack = ws.take(hp.bwd_total);
     const size_t n_tiles = PN;
+    // forward: enough waves to hide memory latency; backward: fewer, every wave leaves a partial block
     const int head_blocks = (int)std::min<size_t>((n_tiles + 3) / 4, 512);
-    pl.n_head_waves = head_blocks * 4;
+    pl.head_fwd_blocks = head_blocks;
+    pl.n_head_waves = 4 * (int)std::min<size_t>((n_tiles + 3) / 4, 256);
     pl.head_dw_stride = (pl.MO * pl.MA + pl.MA * pl.MA) * 256 + 4 * pl.OT + 4 * pl.HT;
     pl.head_dw_stride = (pl.head_dw_stride + 63) & ~63;
     pl.head_dw_partial = ws.take((size_t)pl.n_head_waves * pl.head_dw_stride);
