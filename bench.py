@@ -24,6 +24,17 @@ sys.path.insert(0, ROOT)
 PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 256 MiB copy probe
+# (FETCH x 2.0, WRITE x 1.0): profiles/hbm_traffic_quarterly_B4096.txt.  Valid for that workload and batch only.
+MEASURED_TRAFFIC_BYTES = {
+    ("quarterly", 4096): {
+        "lstm_forward_l0": 244e6, "lstm_forward_l1": 309e6, "lstm_forward_l2": 309e6, "lstm_forward_l3": 309e6,
+        "lstm_backward_l0": 296e6, "lstm_backward_l1": 406e6, "lstm_backward_l2": 406e6, "lstm_backward_l3": 406e6,
+        "head_forward": 122e6, "head_backward": 179e6, "window_forward": 22.2e6, "window_backward": 15.6e6,
+        "es_forward": 6.2e6, "es_backward": 6.1e6,
+    },
+}
+
 
 def stage_model(cfg, name):
     """Algorithmic work of one launch of a stage: (bound, amount, unit).
@@ -127,7 +138,8 @@ def main():
     else:
         achieved, peak, unit = 0.0, 1.0, ""
     roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": None,
+                "frac": round(achieved / peak, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.B), {}).get(dominant),
                 "avg_launch_ms": round(stage_ms[dominant], 4)}
     stage_report = {}
     for name, ms in stage_ms.items():
