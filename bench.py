@@ -66,6 +66,45 @@ def stage_model(cfg, name):
     return None, 0.0, ""
 
 
+def es_window_sweep(args, torch, binding, synth):
+    """Smoothing and window stages alone at large batch sizes (their HBM roofline is only meaningful there:
+    at the benchmark batch a 72-step dependent chain on 64 waves is latency-bound)."""
+    import ctypes
+    for B in [int(x) for x in args.es_window_sweep.split(",")]:
+        cfg = synth.CONFIGS[args.workload].with_(B=B)
+        inp = synth.make_inputs(cfg, seed=0)
+        dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items() if k != "weights"}
+        h = binding.esrnn_create(cfg)
+        nbytes = binding.esrnn_es_window_workspace_bytes(h)
+        ws = torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda")
+        ges = torch.empty((cfg.K, B), dtype=torch.float32, device="cuda")
+
+        def one():
+            binding.esrnn_es_window_forward(h, dev["y"], dev["lengths"], dev["es_params"], ws)
+            binding.esrnn_es_window_backward(h, dev["y"], dev["lengths"], dev["es_params"], ws, ges)
+
+        for _ in range(3):
+            one()
+        torch.cuda.synchronize()
+        binding.esrnn_profile_enable(h, True)
+        for _ in range(max(1, args.profile_steps)):
+            one()
+            binding.esrnn_profile_collect(h)
+        stages = {n: t / max(c, 1) for n, t, c in binding.esrnn_profile_read(h) if c}
+        binding.esrnn_profile_enable(h, False)
+        out = {"workload": cfg.name, "B": B, "T": cfg.T, "workspace_MB": round(nbytes / 1e6, 1), "stages": {}}
+        for name, ms in stages.items():
+            bound, amt, _ = stage_model(cfg, name)
+            e = {"ms": round(ms, 4)}
+            if bound == "hbm":
+                e["gbs"] = round(amt / (ms * 1e-3) / 1e9, 1)
+                e["frac_hbm_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+            out["stages"][name] = e
+        print(json.dumps(out), flush=True)
+        binding.esrnn_destroy(h)
+        del ws, ges, dev
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +117,9 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--es-window-sweep", default="",
+                    help="comma-separated batch sizes: time only the smoothing and window stages (forward and "
+                         "adjoint) at each, one JSON line per size, instead of the training-step benchmark")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (series shard trivially across GPUs, "
@@ -87,6 +129,9 @@ def main():
     import torch
     from paper_1907_03329_amd import binding, synth
 
+    if args.es_window_sweep:
+        es_window_sweep(args, torch, binding, synth)
+        return
     cfg = synth.CONFIGS[args.workload]
     if args.batch:
         cfg = cfg.with_(B=args.batch)

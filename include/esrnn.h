@@ -124,6 +124,25 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
                             float *grad_es_params, float *grad_weights, void *stream);
 
 /*
+ * The smoothing and window stages on their own (Section 3.1 Eq. (1), (3), Section
+ * 5.3 Eq. (6), and their adjoints), for callers that fit or inspect the
+ * exponential-smoothing part without the network, and for measuring these
+ * stages at batch sizes whose network stash would not fit.  They use only the
+ * first esrnn_es_window_workspace_bytes bytes of the workspace layout (a full
+ * workspace works too).  esrnn_es_window_forward fills the level, seasonal
+ * factors, u, v and the window tiles X, Z (see esrnn_workspace_buffer).
+ * esrnn_es_window_backward takes the window gradients the caller has placed in
+ * the ESRNN_BUF_GRAD_X and ESRNN_BUF_GRAD_O tiles of the workspace (every
+ * element, padding rows included, must be finite), adds the gradient of the
+ * level penalty, and writes grad_es_params [K][B].
+ */
+esrnn_status esrnn_es_window_workspace_bytes(const esrnn_handle *h, size_t *bytes);
+esrnn_status esrnn_es_window_forward(esrnn_handle *h, const float *y, const int32_t *lengths,
+                                     const float *es_params, void *workspace, void *stream);
+esrnn_status esrnn_es_window_backward(esrnn_handle *h, const float *y, const int32_t *lengths,
+                                      const float *es_params, void *workspace, float *grad_es_params, void *stream);
+
+/*
  * Where an intermediate lives inside the workspace, for tests and profiling.
  * Layout kinds:
  *   ESRNN_LAYOUT_TIME_MAJOR  [T][Bp], Bp = 16 * ceil(B / 16)

@@ -70,6 +70,11 @@ def load_library():
     lib.esrnn_forward.argtypes = [vp, fp, i32p, fp, fp, vp, fp, fp, vp]
     lib.esrnn_backward.argtypes = [vp, fp, i32p, fp, fp, vp, fp, fp, vp]
     lib.esrnn_workspace_buffer.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(BufferView)]
+    lib.esrnn_es_window_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
+    lib.esrnn_es_window_forward.argtypes = [vp, fp, i32p, fp, vp, vp]
+    lib.esrnn_es_window_backward.argtypes = [vp, fp, i32p, fp, vp, fp, vp]
+    for fn in ("esrnn_es_window_workspace_bytes", "esrnn_es_window_forward", "esrnn_es_window_backward"):
+        getattr(lib, fn).restype = C.c_int
     lib.esrnn_profile_enable.argtypes = [vp, C.c_int32]
     lib.esrnn_profile_stage_count.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.esrnn_profile_stage_name.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p)]
@@ -230,6 +235,31 @@ def esrnn_backward(handle, y, lengths, es_params, weights, workspace, grad_es_pa
                                        _ptr(grad_weights, torch.float32), _stream(stream))
     if st != ESRNN_OK:
         raise EsrnnError(st, "esrnn_backward")
+
+
+def esrnn_es_window_workspace_bytes(handle) -> int:
+    n = C.c_size_t()
+    st = load_library().esrnn_es_window_workspace_bytes(handle, C.byref(n))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_es_window_workspace_bytes")
+    return int(n.value)
+
+
+def esrnn_es_window_forward(handle, y, lengths, es_params, workspace, stream=None) -> None:
+    import torch
+    st = load_library().esrnn_es_window_forward(handle, _ptr(y, torch.float32), _ptr(lengths, torch.int32),
+                                                _ptr(es_params, torch.float32), _ptr(workspace), _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_es_window_forward")
+
+
+def esrnn_es_window_backward(handle, y, lengths, es_params, workspace, grad_es_params, stream=None) -> None:
+    import torch
+    st = load_library().esrnn_es_window_backward(handle, _ptr(y, torch.float32), _ptr(lengths, torch.int32),
+                                                 _ptr(es_params, torch.float32), _ptr(workspace),
+                                                 _ptr(grad_es_params, torch.float32), _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_es_window_backward")
 
 
 class TrainingStep:

@@ -28,11 +28,21 @@ __device__ void prep_body(const PrepArgs &pa)
     const int B = pa.B, T = pa.T, I = pa.I, H = pa.H;
     __shared__ double s_pin[256], s_lv[256];
     double np_ = 0.0, nl = 0.0;
-    for (int b = threadIdx.x; b < B; b += 256) {
-        const int len = clamp_len(lengths[b], T);
-        const int Pb = len - I - H + 1;
-        if (Pb > 0) np_ += (double)Pb * H;
-        if (len > 2) nl += (double)(len - 2);
+    // eight independent loads in flight per thread: one workgroup has to read all lengths
+    for (int b0 = threadIdx.x; b0 < B; b0 += 8 * 256) {
+        int len[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int b = b0 + k * 256;
+            len[k] = b < B ? lengths[b] : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int l = clamp_len(len[k], T);
+            const int Pb = l - I - H + 1;
+            if (Pb > 0) np_ += (double)Pb * H;
+            if (l > 2) nl += (double)(l - 2);
+        }
     }
     s_pin[threadIdx.x] = np_;
     s_lv[threadIdx.x] = nl;
@@ -160,14 +170,14 @@ struct SetupArgs {
     PackLstmArgs lstm[kMaxLayers];
     PackHeadArgs head;
     PrepArgs prep;
-    int L;
+    int L, pack;     // pack = 0: only the loss normalisers
 };
 
 __global__ void __launch_bounds__(256) setup_kernel(SetupArgs a)
 {
     const int z = blockIdx.z;
-    if (z < a.L) pack_lstm_body(a.lstm[z]);
-    else if (z == a.L) pack_head_body(a.head);
+    if (a.pack && z < a.L) pack_lstm_body(a.lstm[z]);
+    else if (a.pack && z == a.L) pack_head_body(a.head);
     else if (blockIdx.x == 0) prep_body(a.prep);
 }
 
@@ -292,23 +302,22 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) window_forward_kernel(const float *__restrict__ u, const float *__restrict__ v,
                                                               float *__restrict__ X, float *__restrict__ Z,
-                                                              int P, int NB, int Bp, int I, int H, int xrows, int zrows)
+                                                              int P, int NB, int Bp, int I, int H, int xrows, int zrows,
+                                                              int p_per_wave)
 {
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, n = lane & 15;
-    const long long tile = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= (long long)P * NB) return;
-    const int p = (int)(tile / NB), bt = (int)(tile % NB);
+    const int bt = blockIdx.x;
+    const int p0 = (blockIdx.y * 4 + (threadIdx.x >> 6)) * p_per_wave;
     const int col = bt * 16 + n;
-    const int t = p + I - 1;
-    const float ut = u[(size_t)t * Bp + col];
-    float *xo = X + (size_t)tile * xrows * 16 + lane;
-    for (int r = g; r < xrows; r += 4) {
-        xo[(r - g) * 16] = (r < I) ? v[(size_t)(p + r) * Bp + col] - ut : 0.0f;
-    }
-    float *zo = Z + (size_t)tile * zrows * 16 + lane;
-    for (int r = g; r < zrows; r += 4) {
-        zo[(r - g) * 16] = (r < H) ? v[(size_t)(t + 1 + r) * Bp + col] - ut : 0.0f;
+    for (int p = p0; p < p0 + p_per_wave && p < P; ++p) {
+        const size_t tile = (size_t)p * NB + bt;
+        const int t = p + I - 1;
+        const float ut = u[(size_t)t * Bp + col];
+        float *xo = X + tile * xrows * 16 + lane;
+        for (int r = g; r < xrows; r += 4) xo[(r - g) * 16] = (r < I) ? v[(size_t)(p + r) * Bp + col] - ut : 0.0f;
+        float *zo = Z + tile * zrows * 16 + lane;
+        for (int r = g; r < zrows; r += 4) zo[(r - g) * 16] = (r < H) ? v[(size_t)(t + 1 + r) * Bp + col] - ut : 0.0f;
     }
 }
 
@@ -678,6 +687,12 @@ hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *wei
 {
     SetupArgs a{};
     a.L = pl.L;
+    a.pack = weights != nullptr;
+    a.prep = PrepArgs{lengths, reinterpret_cast<Scalars *>(ws + pl.scalars), pl.B, pl.T, pl.I, pl.H};
+    if (!a.pack) {
+        setup_kernel<<<dim3(1, 1, 1), 256, 0, st>>>(a);
+        return hipGetLastError();
+    }
     int max_total = 256;
     for (int l = 0; l < pl.L; ++l) {
         const LayerPlan &lp = pl.layer[l];
@@ -691,7 +706,6 @@ hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *wei
     a.head = PackHeadArgs{weights + pl.Wa_off, weights + pl.ba_off, weights + pl.Wo_off, weights + pl.bo_off,
                           f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, b + hp.WoT, b + hp.WaT,
                           pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
-    a.prep = PrepArgs{lengths, reinterpret_cast<Scalars *>(ws + pl.scalars), pl.B, pl.T, pl.I, pl.H};
     const int blocks = std::min((max_total + 255) / 256, 64);   // the bodies loop over their elements
     setup_kernel<<<dim3(blocks, 1, pl.L + 2), 256, 0, st>>>(a);
     return hipGetLastError();
@@ -722,9 +736,12 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
 
 hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st)
 {
-    const long long tiles = (long long)pl.P * pl.NB;
-    window_forward_kernel<<<(unsigned)((tiles + 3) / 4), 256, 0, st>>>(ws + pl.u, ws + pl.v, ws + pl.X, ws + pl.Z,
-                                                                      pl.P, pl.NB, pl.Bp, pl.I, pl.H, 4 * pl.IT, pl.OP);
+    // few positions per wave at small batches (enough waves), more at large ones (less per-wave overhead)
+    const int p_per_wave = pl.NB >= 2048 ? 8 : (pl.NB >= 512 ? 4 : 1);
+    const int waves_y = (pl.P + p_per_wave - 1) / p_per_wave;
+    window_forward_kernel<<<dim3(pl.NB, (waves_y + 3) / 4), 256, 0, st>>>(ws + pl.u, ws + pl.v, ws + pl.X, ws + pl.Z,
+                                                                         pl.P, pl.NB, pl.Bp, pl.I, pl.H, 4 * pl.IT,
+                                                                         pl.OP, p_per_wave);
     return hipGetLastError();
 }
 

@@ -182,6 +182,41 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
     return ESRNN_OK;
 }
 
+esrnn_status esrnn_es_window_workspace_bytes(const esrnn_handle *h, size_t *bytes)
+{
+    if (!h || !bytes) return ESRNN_ERR_NULL;
+    *bytes = h->plan.es_window_floats * sizeof(float);
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_es_window_forward(esrnn_handle *h, const float *y, const int32_t *lengths,
+                                     const float *es_params, void *workspace, void *stream)
+{
+    if (!h || !y || !lengths || !es_params || !workspace) return ESRNN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
+    const Plan &pl = h->plan;
+    float *ws = static_cast<float *>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ESRNN_TRY(run_stage(h, h->st_setup, st, [&] { return launch_setup(pl, lengths, nullptr, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, lengths, es_params, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, ws, st); }));
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_es_window_backward(esrnn_handle *h, const float *y, const int32_t *lengths,
+                                      const float *es_params, void *workspace, float *grad_es_params, void *stream)
+{
+    if (!h || !y || !lengths || !es_params || !workspace || !grad_es_params) return ESRNN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
+    const Plan &pl = h->plan;
+    float *ws = static_cast<float *>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ESRNN_TRY(run_stage(h, h->st_win_bwd, st, [&] { return launch_window_backward(pl, lengths, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_es_bwd, st,
+                        [&] { return launch_es_backward(pl, y, lengths, es_params, ws, grad_es_params, st); }));
+    return ESRNN_OK;
+}
+
 esrnn_status esrnn_profile_enable(esrnn_handle *h, int32_t on)
 {
     if (!h) return ESRNN_ERR_NULL;

@@ -47,7 +47,7 @@ struct Plan {
     int NB, Bp;          // series tiles, padded batch
     int HT, HP;          // hidden unit tiles, padded hidden (4*HT)
     int IT;              // unit tiles of the input window as used by layer 0
-    int OT, MO, OP;      // horizon: unit tiles, 16-row tiles, padded rows (16*MO)
+    int OT, MO, OP;      // horizon: unit tiles, 16-row MFMA tiles, rows of the Z / O / gO tiles (4*OT)
     int MA;              // 16-row tiles of the hidden dimension in "unit-tile" order: ceil(HT/4)
     int L;
     int K;               // rows of es_params
@@ -68,6 +68,7 @@ struct Plan {
     int head_dw_stride;
     size_t head_dw_reduced;
     int es_blocks;
+    size_t es_window_floats;   // prefix of the workspace used by the smoothing and window stages alone
     size_t total_floats;
 };
 

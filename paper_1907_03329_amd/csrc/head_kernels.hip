@@ -25,6 +25,7 @@ struct HeadFwdArgs {
     float *forecasts;       // [P][B][H] or null
     float *loss_partial;    // [gridDim.x]
     int P, NB, B, Bp, T, I, H, n_seas;
+    int orows;              // rows of the Z and O tiles: 4 * ceil(H / 4)
     float tau;
 };
 
@@ -79,7 +80,7 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = 16 * mo + 4 * g + r;
-                o.z[4 * mo + r] = a.Z[((size_t)tile * OP + j) * 16 + n];
+                o.z[4 * mo + r] = a.Z[((size_t)tile * a.orows + (j < a.orows ? j : a.orows - 1)) * 16 + n];
                 const int tj = t + 1 + j < a.T ? t + 1 + j : a.T - 1;
                 float sv = 1.0f;
                 if (a.n_seas >= 1) sv = a.S1[(size_t)tj * a.Bp + b];
@@ -128,9 +129,8 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = 16 * mo + 4 * g + r;      // 0-based step of the horizon
-                const size_t e = ((size_t)tile * OP + j) * 16 + n;
                 const float o = oc[mo][r];
-                a.O[e] = o;
+                if (j < a.orows) a.O[((size_t)tile * a.orows + j) * 16 + n] = o;
                 if (j < a.H) {
                     if (valid) {
                         const float d = cur.z[4 * mo + r] - o;
@@ -160,6 +160,7 @@ struct HeadBwdArgs {
     float *gTop;            // TL(HP): dL/d(top block output)
     float *partial;         // [n_waves][stride]
     int P, NB, B, T, I, H, stride;
+    int orows;              // rows of the Z, O and gO tiles: 4 * ceil(H / 4)
     float tau;
 };
 
@@ -219,7 +220,8 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
         o.len = a.lengths[b < a.B ? b : a.B - 1];
 #pragma unroll
         for (int ks = 0; ks < OTMAX; ++ks) {
-            const size_t e = ((size_t)tile * OP + 4 * ks + g) * 16 + n;
+            const int j = 4 * ks + g;
+            const size_t e = ((size_t)tile * a.orows + (j < a.orows ? j : a.orows - 1)) * 16 + n;
             o.d[ks] = a.Z[e] - a.O[e];
         }
 #pragma unroll
@@ -246,10 +248,9 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
 #pragma unroll
         for (int ks = 0; ks < OTMAX; ++ks) {
             const int j = 4 * ks + g;
-            const size_t e = ((size_t)tile * OP + j) * 16 + n;
             const float val = (valid && j < a.H) ? (cur.d[ks] >= 0.0f ? -a.tau : 1.0f - a.tau) * inv_n : 0.0f;
             go[ks] = val;
-            a.gO[e] = val;
+            if (j < a.orows) a.gO[((size_t)tile * a.orows + j) * 16 + n] = val;
             go_l[j * kLdsPad + n] = val;
             dbo[ks] += val;
         }
@@ -347,7 +348,7 @@ hipError_t launch_head_forward(const Plan &pl, const int32_t *lengths, float *ws
     const int blocks = pl.head_fwd_blocks;
     HeadFwdArgs a{f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z,
                   ws + pl.u, ws + pl.S1, ws + pl.S2, lengths, ws + pl.A, ws + pl.O, forecasts, ws + pl.loss_partial,
-                  pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.cfg.tau};
+                  pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.OP, pl.cfg.tau};
 #define X(HT_, MO_)                                                      \
     if (pl.HT == HT_ && pl.MO == MO_) {                                  \
         head_forward_kernel<HT_, MO_><<<blocks, 256, 0, st>>>(a);        \
@@ -365,7 +366,7 @@ hipError_t launch_head_backward(const Plan &pl, const int32_t *lengths, float *w
     const int blocks = pl.n_head_waves / 4;
     HeadBwdArgs a{bk + hp.WoT, bk + hp.WaT, ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.A, ws + pl.O, ws + pl.Z,
                   lengths, reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.gO, ws + pl.gTop,
-                  ws + pl.head_dw_partial, pl.P, pl.NB, pl.B, pl.T, pl.I, pl.H, pl.head_dw_stride, pl.cfg.tau};
+                  ws + pl.head_dw_partial, pl.P, pl.NB, pl.B, pl.T, pl.I, pl.H, pl.head_dw_stride, pl.OP, pl.cfg.tau};
 #define X(HT_, MO_)                                                      \
     if (pl.HT == HT_ && pl.MO == MO_) {                                  \
         head_backward_kernel<HT_, MO_><<<blocks, 256, 0, st>>>(a);       \

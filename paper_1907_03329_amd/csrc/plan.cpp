@@ -84,7 +84,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.HP = 4 * pl.HT;
     pl.OT = ceil_div(cfg.H, 4);
     pl.MO = ceil_div(cfg.H, 16);
-    pl.OP = 16 * pl.MO;
+    pl.OP = 4 * pl.OT;
     pl.MA = ceil_div(pl.HT, 4);
     // layer 0 input tiles: exact if that kernel shape is instantiated, else padded to HT
     pl.IT = ceil_div(cfg.I, 4);
@@ -134,15 +134,25 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     const size_t TB = (size_t)pl.T * pl.Bp;
     const size_t PN = (size_t)pl.P * pl.NB;
     const size_t tileH = (size_t)pl.HT * 64;         // floats of one (p, series-tile) block with HP rows
+    // forward: enough waves to hide memory latency; backward: fewer, every wave leaves a partial block
+    const size_t n_tiles = PN;
+    const int head_blocks = (int)std::min<size_t>((n_tiles + 3) / 4, 512);
+    pl.head_fwd_blocks = head_blocks;
+    pl.n_head_waves = 4 * (int)std::min<size_t>((n_tiles + 3) / 4, 256);
+    pl.es_blocks = ceil_div(pl.Bp, 64);
+    // first everything the smoothing and window stages touch (their own entry points need only this prefix)
     pl.scalars = ws.take(64);
+    pl.n_loss_partial = head_blocks + pl.es_blocks;
+    pl.loss_partial = ws.take((size_t)pl.n_loss_partial);
     pl.lvl = ws.take(TB); pl.S1 = ws.take(TB); pl.S2 = ws.take(TB);
     pl.u = ws.take(TB); pl.v = ws.take(TB); pl.gu = ws.take(TB); pl.gv = ws.take(TB);
     pl.X = ws.take(PN * (size_t)pl.IT * 64);
     pl.Z = ws.take(PN * (size_t)pl.OP * 16);
     pl.gX = ws.take(PN * (size_t)pl.IT * 64);
+    pl.gO = ws.take(PN * (size_t)pl.OP * 16);
+    pl.es_window_floats = ws.at;
     pl.A = ws.take(PN * tileH);
     pl.O = ws.take(PN * (size_t)pl.OP * 16);
-    pl.gO = ws.take(PN * (size_t)pl.OP * 16);
     pl.gTop = ws.take(PN * tileH);
     for (int l = 0; l < L; ++l) {
         LayerPlan &lp = pl.layer[l];
@@ -196,18 +206,10 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     const HeadPack hp = head_pack_layout(pl);
     pl.head_fwd_pack = ws.take(hp.fwd_total);
     pl.head_bwd_pack = ws.take(hp.bwd_total);
-    const size_t n_tiles = PN;
-    // forward: enough waves to hide memory latency; backward: fewer, every wave leaves a partial block
-    const int head_blocks = (int)std::min<size_t>((n_tiles + 3) / 4, 512);
-    pl.head_fwd_blocks = head_blocks;
-    pl.n_head_waves = 4 * (int)std::min<size_t>((n_tiles + 3) / 4, 256);
     pl.head_dw_stride = (pl.MO * pl.MA + pl.MA * pl.MA) * 256 + 4 * pl.OT + 4 * pl.HT;
     pl.head_dw_stride = (pl.head_dw_stride + 63) & ~63;
     pl.head_dw_partial = ws.take((size_t)pl.n_head_waves * pl.head_dw_stride);
     pl.head_dw_reduced = ws.take((size_t)kReduceSplits * pl.head_dw_stride);
-    pl.es_blocks = ceil_div(pl.Bp, 64);
-    pl.n_loss_partial = head_blocks + pl.es_blocks;
-    pl.loss_partial = ws.take((size_t)pl.n_loss_partial);
     pl.total_floats = ws.at;
     return ESRNN_OK;
 }

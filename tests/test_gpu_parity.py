@@ -202,3 +202,54 @@ def test_forecasts_may_be_omitted_and_stream_is_honoured():
     assert torch.equal(step.loss, ref.loss)
     assert torch.equal(step.grad_weights, ref.grad_weights)
     assert torch.equal(step.grad_es_params, ref.grad_es_params)
+
+
+def test_smoothing_and_window_entry_points_alone():
+    """esrnn_es_window_forward / _backward on the workspace prefix: windows against the oracle, and the
+    smoothing gradients for window gradients taken from the oracle's reverse sweep."""
+    import torch
+    from oracle import oracle
+    from paper_1907_03329_amd import binding
+    cfg = small("es_only", T=60, n_seas=2, m1=3, m2=7, seas_sd2=0.1, I=5, H=6, B=45, blocks=((1, 3), (5,)))
+    inp = synth.make_inputs(cfg, seed=23, ragged=True)
+    f = oracle.forward(cfg, inp["y"], inp["lengths"], inp["es_params"], inp["weights"])
+    g = oracle.backward(cfg, f)
+    dev = gc.to_device(inp)
+    h = binding.esrnn_create(cfg)
+    nbytes = binding.esrnn_es_window_workspace_bytes(h)
+    assert nbytes < binding.esrnn_workspace_bytes(h)
+    ws = torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda")
+    binding.esrnn_es_window_forward(h, dev["y"], dev["lengths"], dev["es_params"], ws)
+
+    def view(name):
+        v = binding.esrnn_workspace_buffer(h, name)
+        lead, Bp, R, logical = (int(x) for x in v.dims)
+        assert v.offset_bytes + 4 * lead * Bp * max(R, 1) <= nbytes
+        return v, ws[v.offset_bytes // 4: v.offset_bytes // 4 + lead * Bp * max(R, 1)]
+
+    def untile(name):
+        v, flat = view(name)
+        lead, Bp, R, logical = (int(x) for x in v.dims)
+        return flat.view(lead, Bp // 16, R, 16).permute(0, 1, 3, 2).reshape(lead, Bp, R)[:, :cfg.B, :logical].cpu().numpy()
+
+    def tile_into(name, arr):   # arr [P, B, rows]
+        v, flat = view(name)
+        lead, Bp, R, logical = (int(x) for x in v.dims)
+        full = np.zeros((lead, Bp, R), dtype=np.float32)
+        full[:, :cfg.B, :logical] = arr
+        t = torch.from_numpy(full).cuda().view(lead, Bp // 16, 16, R).permute(0, 1, 3, 2).contiguous()
+        flat.copy_(t.view(-1))
+
+    wm = gc.valid_window_mask(cfg, inp["lengths"])
+    assert gc.rel_err(untile("X"), f.X.transpose(1, 0, 2), wm) <= gc.TOL_FWD
+    assert gc.rel_err(untile("Z"), f.Z.transpose(1, 0, 2), wm) <= gc.TOL_FWD
+    tile_into("grad_X", g.gX.transpose(1, 0, 2))
+    tile_into("grad_O", g.gO.transpose(1, 0, 2))
+    ges = torch.empty((cfg.K, cfg.B), dtype=torch.float32, device="cuda")
+    binding.esrnn_es_window_backward(h, dev["y"], dev["lengths"], dev["es_params"], ws, ges)
+    torch.cuda.synchronize()
+    got = ges.cpu().numpy()
+    for name, sl in synth.es_param_rows(cfg).items():
+        e = gc.rel_err(got[sl], g.grad_es_params[sl])
+        assert e <= gc.TOL_GRAD, f"grad_{name}: {e:.3e}"
+    binding.esrnn_destroy(h)
