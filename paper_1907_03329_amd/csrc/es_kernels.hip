@@ -307,8 +307,11 @@ __global__ void __launch_bounds__(256) window_forward_kernel(const float *__rest
 {
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, n = lane & 15;
-    const int bt = blockIdx.x;
-    const int p0 = (blockIdx.y * 4 + (threadIdx.x >> 6)) * p_per_wave;
+    // the four waves of a workgroup take four adjacent series tiles at the same positions, so that the
+    // workgroup writes 1 KB (X, I = 4) and 2 KB (Z, H = 8) contiguous per position
+    const int bt = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (bt >= NB) return;
+    const int p0 = blockIdx.y * p_per_wave;
     const int col = bt * 16 + n;
     for (int p = p0; p < p0 + p_per_wave && p < P; ++p) {
         const size_t tile = (size_t)p * NB + bt;
@@ -738,8 +741,7 @@ hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st)
 {
     // few positions per wave at small batches (enough waves), more at large ones (less per-wave overhead)
     const int p_per_wave = pl.NB >= 2048 ? 8 : (pl.NB >= 512 ? 4 : 1);
-    const int waves_y = (pl.P + p_per_wave - 1) / p_per_wave;
-    window_forward_kernel<<<dim3(pl.NB, (waves_y + 3) / 4), 256, 0, st>>>(ws + pl.u, ws + pl.v, ws + pl.X, ws + pl.Z,
+    window_forward_kernel<<<dim3((pl.NB + 3) / 4, (pl.P + p_per_wave - 1) / p_per_wave), 256, 0, st>>>(ws + pl.u, ws + pl.v, ws + pl.X, ws + pl.Z,
                                                                          pl.P, pl.NB, pl.Bp, pl.I, pl.H, 4 * pl.IT,
                                                                          pl.OP, p_per_wave);
     return hipGetLastError();

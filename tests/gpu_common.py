@@ -104,15 +104,28 @@ def check_backward(cfg, inp, step, f, g, stages=True):
         errs[name] = e
         assert e <= tol, f"{name}: relative error {e:.3e} > {tol:g} ({cfg.name})"
 
+    # At the kink of the pinball loss (target == output up to float32 rounding) either one-sided
+    # derivative is a valid result, and the choice changes that series' gradients by a visible amount.
+    # One such element moves the pinball part of its series' gradients by about 2 / (valid outputs of the
+    # series).  Series where that could exceed a fifth of the gradient tolerance are compared through the
+    # shared-weight gradients only (where one element weighs 1 / n_pin); everything per series is
+    # compared on the other series.
+    near = np.abs(f.Z - f.o) <= 2e-6 * np.maximum(1.0, np.abs(f.Z))            # [B, P, H]
+    near &= wm.T[:, :, None]
+    n_out = np.maximum(wm.sum(axis=0) * cfg.H, 1)                                # [B]
+    clean = 2.0 * near.sum(axis=(1, 2)) / n_out <= 0.2 * TOL_GRAD               # [B]
+    errs["series_at_kink"] = float((~clean).sum())
+    assert (~clean).sum() <= max(3, 0.05 * cfg.B), "implausibly many outputs at the kink of the pinball loss"
     if stages:
-        chk("grad_O", step.buffer("grad_O").cpu().numpy(), g.gO.transpose(1, 0, 2), None, TOL_GRAD)
-        chk("grad_top", step.buffer("grad_top").cpu().numpy(), g.gR.transpose(1, 0, 2), wm, TOL_GRAD)
-        chk("grad_X", step.buffer("grad_X").cpu().numpy(), g.gX.transpose(1, 0, 2), wm, TOL_GRAD)
-        chk("grad_u", step.buffer("grad_u").cpu().numpy(), g.gu.T, live, TOL_GRAD)
-        chk("grad_v", step.buffer("grad_v").cpu().numpy(), g.gv.T, live, TOL_GRAD)
+        chk("grad_O", step.buffer("grad_O").cpu().numpy(), g.gO.transpose(1, 0, 2),
+            np.broadcast_to(clean[None, :, None], (wm.shape[0], cfg.B, cfg.H)), TOL_GRAD)
+        chk("grad_top", step.buffer("grad_top").cpu().numpy(), g.gR.transpose(1, 0, 2), wm & clean[None, :], TOL_GRAD)
+        chk("grad_X", step.buffer("grad_X").cpu().numpy(), g.gX.transpose(1, 0, 2), wm & clean[None, :], TOL_GRAD)
+        chk("grad_u", step.buffer("grad_u").cpu().numpy(), g.gu.T, live & clean[None, :], TOL_GRAD)
+        chk("grad_v", step.buffer("grad_v").cpu().numpy(), g.gv.T, live & clean[None, :], TOL_GRAD)
     ges = step.grad_es_params.cpu().numpy()
     for name, sl in synth.es_param_rows(cfg).items():
-        chk(f"grad_{name}", ges[sl], g.grad_es_params[sl], None, TOL_GRAD)
+        chk(f"grad_{name}", ges[sl][:, clean], g.grad_es_params[sl][:, clean], None, TOL_GRAD)
     gw = step.grad_weights.cpu().numpy()
     for name, off, shape in synth.weight_layout(cfg):
         n = int(np.prod(shape))
