@@ -40,7 +40,8 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
     constexpr int MTW = (HT + kLstmWaves - 1) / kLstmWaves;   // unit tiles per wave
     __shared__ float hbuf[2][HT * 64];
 
-    const int lane = threadIdx.x & 63, s = threadIdx.x >> 6, bt = blockIdx.x;
+    const int lane = threadIdx.x & 63, bt = blockIdx.x;
+    const int s = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
 
     float wreg[MTW][KT];
     f32x4 bias[MTW];
@@ -66,7 +67,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         // input part of the first position
         float bx[KXT];
 #pragma unroll
-        for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[((size_t)r * a.NB + bt) * xtile + ks * 64 + lane];
+        for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + ((size_t)r * a.NB + bt) * xtile + ks * 64)[lane];
         f32x4 acc[MTW];
 #pragma unroll
         for (int j = 0; j < MTW; ++j) acc[j] = bias[j];
@@ -77,13 +78,13 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         {
             const size_t nb = ((size_t)min(r + a.d, a.P - 1) * a.NB + bt) * xtile;
 #pragma unroll
-            for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
+            for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + nb + ks * 64)[lane];
         }
         // residual input of the block (last layer of a block >= 1), one position ahead like the input
         float res[MTW];
 #pragma unroll
         for (int j = 0; j < MTW; ++j)
-            res[j] = a.out ? a.resid[(((size_t)r * a.NB + bt) * HT + min(s + kLstmWaves * j, HT - 1)) * 64 + lane] : 0.0f;
+            res[j] = a.out ? (a.resid + (((size_t)r * a.NB + bt) * HT + min(s + kLstmWaves * j, HT - 1)) * 64)[lane] : 0.0f;
         lds_barrier();
 
         int it = 0;
@@ -94,7 +95,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                 const size_t nb = ((size_t)min(p + a.d, a.P - 1) * a.NB + bt) * HT;
 #pragma unroll
                 for (int j = 0; j < MTW; ++j)
-                    res_next[j] = a.resid[(nb + min(s + kLstmWaves * j, HT - 1)) * 64 + lane];
+                    res_next[j] = (a.resid + (nb + min(s + kLstmWaves * j, HT - 1)) * 64)[lane];
             }
             // recurrent part
             const float *hb = hbuf[it & 1];
@@ -117,11 +118,12 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                     const float hn = go * tanh_f(cn);
                     creg[j] = cn;
                     hn_buf[mt * 64 + lane] = hn;
-                    const size_t e = (pb * HT + mt) * 64 + lane;
-                    reinterpret_cast<float4 *>(a.gates)[e] = make_float4(gi, gf, gg, go);
-                    a.c[e] = cn;
-                    a.hid[e] = hn;
-                    if (a.out) a.out[e] = res[j] + hn;
+                    const size_t tile = (pb * HT + mt) * 64;   // wave-uniform: scalar address arithmetic
+                    // gates are read again only by the reverse pass: streaming stores
+                    __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + tile + lane);
+                    __builtin_nontemporal_store(cn, a.c + tile + lane);
+                    (a.hid + tile)[lane] = hn;
+                    if (a.out) (a.out + tile)[lane] = res[j] + hn;
                 }
             }
             // input part of the next position of the chain: independent of the
@@ -136,8 +138,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                     for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
                 const size_t nb = ((size_t)min(p + 2 * a.d, a.P - 1) * a.NB + bt) * xtile;
 #pragma unroll
-                for (int ks = 0; ks < KXT; ++ks) bx[ks] = a.xsrc[nb + ks * 64 + lane];
-
+                for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + nb + ks * 64)[lane];
             }
             if (a.out) {
 #pragma unroll
@@ -199,7 +200,8 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     __shared__ float xh_lds[XH_ROWS * kLdsPad];      // [row of x ; h][series]; rows past 4*KT are scratch
     __shared__ float part_lds[W][MB * 4][64];        // partial d[x ; h] of every wave
 
-    const int lane = threadIdx.x & 63, s = threadIdx.x >> 6, bt = blockIdx.x;
+    const int lane = threadIdx.x & 63, bt = blockIdx.x;
+    const int s = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
     const int g = lane >> 4, n = lane & 15;
     const bool last_own_valid = s + W * (MTW - 1) < HT;           // unit tile s + 4(MTW-1)
     const bool last_row_valid = (W - 1 - s) + W * (MTW - 1) < HT; // dW row (3-s) + 4(MTW-1)
@@ -239,27 +241,29 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     auto fetch = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
         const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
+        // wave-uniform tile bases plus the lane index: scalar address arithmetic
 #pragma unroll
         for (int j = 0; j < MTW; ++j) {
             const int mt = min(s + W * j, HT - 1);
-            const size_t e = (pb * HT + mt) * 64 + lane;
-            pf_gt[j] = reinterpret_cast<const float4 *>(a.gates)[e];
-            pf_c[j] = a.c[e];
-            pf_cp[j] = a.c[(pbd * HT + mt) * 64 + lane];
-            pf_g[j] = a.gsrc[0][e];
-            pf_g2[j] = a.gsrc[1][e];    // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
+            const size_t tile = (pb * HT + mt) * 64;
+            pf_gt[j] = (reinterpret_cast<const float4 *>(a.gates) + tile)[lane];
+            pf_c[j] = (a.c + tile)[lane];
+            pf_cp[j] = (a.c + (pbd * HT + mt) * 64)[lane];
+            pf_g[j] = (a.gsrc[0] + tile)[lane];
+            pf_g2[j] = (a.gsrc[1] + tile)[lane];    // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
         }
 #pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
-            const int e = min((int)threadIdx.x + i * NT, KT * 64 - 1);
-            const float *src = e < KXT * 64 ? a.xsrc + pb * xtile + e : a.hid + pbd * htile + (e - KXT * 64);
-            pf_xh[i] = *src;
+            // unit tile s + W*i of [x ; h]; tiles past the end alias the last one
+            const int q = min(s + W * i, KT - 1);
+            const float *src = q < KXT ? a.xsrc + pb * xtile + q * 64 : a.hid + pbd * htile + (q - KXT) * 64;
+            pf_xh[i] = src[lane];
         }
         if (a.n_gsrc > 2) {             // more than two residual blocks: rare, summed eagerly
 #pragma unroll
             for (int j = 0; j < MTW; ++j) {
-                const size_t e = (pb * HT + min(s + W * j, HT - 1)) * 64 + lane;
-                for (int k = 2; k < a.n_gsrc; ++k) pf_g2[j] += a.gsrc[k][e];
+                const size_t tile = (pb * HT + min(s + W * j, HT - 1)) * 64;
+                for (int k = 2; k < a.n_gsrc; ++k) pf_g2[j] += (a.gsrc[k] + tile)[lane];
             }
         }
     };
