@@ -35,7 +35,8 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
     constexpr int MA = (HT + 3) / 4;
     constexpr int OP = 16 * MO;
     __shared__ float s_part[4];
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
     const int g = lane >> 4, n = lane & 15;
 
     float wa[MA][HT], wo[MO][HT];
@@ -56,8 +57,12 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
     }
 
     float loss = 0.0f;
-    const long long n_tiles = (long long)a.P * a.NB;
-    const long long stride = (long long)gridDim.x * 4;
+    // Tiles are numbered p * NB + (series tile); a wave takes every stride-th one and keeps (p, series
+    // tile) by increments.  All of it is wave-uniform, so tile bases live on the scalar unit and the
+    // lanes only add their own index.
+    const int n_tiles = a.P * a.NB;
+    const int stride = gridDim.x * 4;
+    const int step_p = stride / a.NB, step_bt = stride % a.NB;
 
     // operands of one tile; those of the next tile are requested before this one is computed
     struct Ops {
@@ -66,35 +71,44 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
         float ut;
         int len;
     };
-    auto load_ops = [&](long long tile_, Ops &o) {
-        const long long tile = tile_ < n_tiles ? tile_ : n_tiles - 1;
-        const int p = (int)(tile / a.NB), bt = (int)(tile % a.NB);
+    auto load_ops = [&](int tile, int p, int bt, Ops &o) {
+        if (tile >= n_tiles) { tile = n_tiles - 1; p = a.P - 1; bt = a.NB - 1; }
         const int b = bt * 16 + n;
         const int t = p + a.I - 1;
+        const float *rt = a.R + (size_t)tile * HT * 64;
 #pragma unroll
-        for (int q = 0; q < HT; ++q) o.br[q] = a.R[(size_t)tile * HT * 64 + q * 64 + lane];
+        for (int q = 0; q < HT; ++q) o.br[q] = (rt + q * 64)[lane];
         o.len = a.lengths[b < a.B ? b : a.B - 1];
-        o.ut = a.u[(size_t)t * a.Bp + b];
+        o.ut = (a.u + (size_t)t * a.Bp + bt * 16)[n];
+        const float *zt = a.Z + (size_t)tile * a.orows * 16;
 #pragma unroll
         for (int mo = 0; mo < MO; ++mo)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int j = 16 * mo + 4 * g + r;
-                o.z[4 * mo + r] = a.Z[((size_t)tile * a.orows + (j < a.orows ? j : a.orows - 1)) * 16 + n];
+                o.z[4 * mo + r] = zt[(j < a.orows ? j : a.orows - 1) * 16 + n];
                 const int tj = t + 1 + j < a.T ? t + 1 + j : a.T - 1;
                 float sv = 1.0f;
-                if (a.n_seas >= 1) sv = a.S1[(size_t)tj * a.Bp + b];
-                if (a.n_seas >= 2) sv *= a.S2[(size_t)tj * a.Bp + b];
+                if (a.n_seas >= 1) sv = (a.S1 + bt * 16)[tj * a.Bp + n];
+                if (a.n_seas >= 2) sv *= (a.S2 + bt * 16)[tj * a.Bp + n];
                 o.seas[4 * mo + r] = sv;
             }
     };
+    auto advance = [&](int &tile, int &p, int &bt) {
+        tile += stride; p += step_p; bt += step_bt;
+        if (bt >= a.NB) { bt -= a.NB; ++p; }
+    };
 
     Ops cur, nxt;
-    long long tile = (long long)blockIdx.x * 4 + wv;
-    if (tile < n_tiles) load_ops(tile, cur);
-    for (; tile < n_tiles; tile += stride) {
-        load_ops(tile + stride, nxt);
-        const int p = (int)(tile / a.NB), bt = (int)(tile % a.NB);
+    int tile = blockIdx.x * 4 + wv;
+    int p = tile / a.NB, bt = tile % a.NB;
+    if (tile < n_tiles) load_ops(tile, p, bt, cur);
+    for (; tile < n_tiles; advance(tile, p, bt)) {
+        {
+            int tn = tile, pn = p, btn = bt;
+            advance(tn, pn, btn);
+            load_ops(tn, pn, btn, nxt);
+        }
         const int b = bt * 16 + n;
         int len = cur.len < 0 ? 0 : (cur.len > a.T ? a.T : cur.len);
         if (b >= a.B) len = 0;
@@ -114,7 +128,7 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
             for (int r = 0; r < 4; ++r) {
                 const int q = 4 * ma + r;
                 av[q] = tanh_f(acc[ma][r]);
-                if (q < HT) a.A[(size_t)tile * HT * 64 + q * 64 + lane] = av[q];
+                if (q < HT) (a.A + (size_t)tile * HT * 64 + q * 64)[lane] = av[q];
             }
         f32x4 oc[MO];
 #pragma unroll
@@ -130,7 +144,7 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
             for (int r = 0; r < 4; ++r) {
                 const int j = 16 * mo + 4 * g + r;      // 0-based step of the horizon
                 const float o = oc[mo][r];
-                if (j < a.orows) a.O[((size_t)tile * a.orows + j) * 16 + n] = o;
+                if (j < a.orows) (a.O + (size_t)tile * a.orows * 16)[j * 16 + n] = o;
                 if (j < a.H) {
                     if (valid) {
                         const float d = cur.z[4 * mo + r] - o;
@@ -139,7 +153,7 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
                     if (a.forecasts && b < a.B) {
                         // Eq. (5): exp(output) * level * seasonal factors of the target time
                         const float f = valid ? __expf(o + cur.ut) * cur.seas[4 * mo + r] : 0.0f;
-                        a.forecasts[((size_t)p * a.B + b) * a.H + j] = f;
+                        (a.forecasts + ((size_t)p * a.B + bt * 16) * a.H)[n * a.H + j] = f;
                     }
                 }
             }
@@ -177,7 +191,8 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
     __shared__ float s_dp[4][HP16 * kLdsPad];
     __shared__ float s_r[4][HP16 * kLdsPad];
 
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
     const int g = lane >> 4, n = lane & 15;
     const int OT = (a.H + 3) / 4;
     float *go_l = s_go[wv], *a_l = s_a[wv], *dp_l = s_dp[wv], *r_l = s_r[wv];
@@ -204,8 +219,10 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
     for (int i = 0; i < 4 * MA; ++i) dba[i] = 0.0f;
 
     const float inv_n = a.sc->inv_n_pin;
-    const long long n_tiles = (long long)a.P * a.NB;
-    const long long stride = (long long)gridDim.x * 4;
+    // wave-uniform tile bookkeeping as in the forward kernel
+    const int n_tiles = a.P * a.NB;
+    const int stride = gridDim.x * 4;
+    const int step_p = stride / a.NB, step_bt = stride % a.NB;
 
     // operands of one tile; those of the next tile are requested before this one is computed
     struct Ops {
@@ -213,31 +230,40 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
         float av[4 * MA], rv[4 * MA];
         int len;
     };
-    auto load_ops = [&](long long tile_, Ops &o) {
-        const long long tile = tile_ < n_tiles ? tile_ : n_tiles - 1;
-        const int bt = (int)(tile % a.NB);
+    auto load_ops = [&](int tile, int bt, Ops &o) {
+        if (tile >= n_tiles) { tile = n_tiles - 1; bt = a.NB - 1; }
         const int b = bt * 16 + n;
         o.len = a.lengths[b < a.B ? b : a.B - 1];
+        const float *zt = a.Z + (size_t)tile * a.orows * 16, *ot = a.O + (size_t)tile * a.orows * 16;
 #pragma unroll
         for (int ks = 0; ks < OTMAX; ++ks) {
             const int j = 4 * ks + g;
-            const size_t e = ((size_t)tile * a.orows + (j < a.orows ? j : a.orows - 1)) * 16 + n;
-            o.d[ks] = a.Z[e] - a.O[e];
+            const int e = (j < a.orows ? j : a.orows - 1) * 16 + n;
+            o.d[ks] = zt[e] - ot[e];
         }
+        const float *at = a.A + (size_t)tile * HT * 64, *rt = a.R + (size_t)tile * HT * 64;
 #pragma unroll
         for (int q = 0; q < 4 * MA; ++q) {
             const int qc = q < HT ? q : HT - 1;
-            o.av[q] = a.A[(size_t)tile * HT * 64 + qc * 64 + lane];
-            o.rv[q] = a.R[(size_t)tile * HT * 64 + qc * 64 + lane];
+            o.av[q] = (at + qc * 64)[lane];
+            o.rv[q] = (rt + qc * 64)[lane];
         }
+    };
+    auto advance = [&](int &tile, int &p, int &bt) {
+        tile += stride; p += step_p; bt += step_bt;
+        if (bt >= a.NB) { bt -= a.NB; ++p; }
     };
 
     Ops cur, nxt;
-    long long tile = (long long)blockIdx.x * 4 + wv;
-    if (tile < n_tiles) load_ops(tile, cur);
-    for (; tile < n_tiles; tile += stride) {
-        load_ops(tile + stride, nxt);
-        const int p = (int)(tile / a.NB), bt = (int)(tile % a.NB);
+    int tile = blockIdx.x * 4 + wv;
+    int p = tile / a.NB, bt = tile % a.NB;
+    if (tile < n_tiles) load_ops(tile, bt, cur);
+    for (; tile < n_tiles; advance(tile, p, bt)) {
+        {
+            int tn = tile, pn = p, btn = bt;
+            advance(tn, pn, btn);
+            load_ops(tn, btn, nxt);
+        }
         const int b = bt * 16 + n;
         int len = cur.len < 0 ? 0 : (cur.len > a.T ? a.T : cur.len);
         if (b >= a.B) len = 0;
@@ -250,7 +276,7 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
             const int j = 4 * ks + g;
             const float val = (valid && j < a.H) ? (cur.d[ks] >= 0.0f ? -a.tau : 1.0f - a.tau) * inv_n : 0.0f;
             go[ks] = val;
-            if (j < a.orows) a.gO[((size_t)tile * a.orows + j) * 16 + n] = val;
+            if (j < a.orows) (a.gO + (size_t)tile * a.orows * 16)[j * 16 + n] = val;
             go_l[j * kLdsPad + n] = val;
             dbo[ks] += val;
         }
@@ -288,7 +314,7 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int q = 4 * ma + r;
-                if (q < HT) a.gTop[(size_t)tile * HT * 64 + q * 64 + lane] = acc[ma][r];
+                if (q < HT) (a.gTop + (size_t)tile * HT * 64 + q * 64)[lane] = acc[ma][r];
             }
         // weight gradients: contraction over the 16 series of the tile
 #pragma unroll
