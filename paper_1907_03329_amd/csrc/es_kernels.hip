@@ -195,6 +195,7 @@ struct EsArgs {
     const float *es;          // [K][B]
     float *lvl, *S1, *S2, *u, *v;   // [T][Bp]
     float *lv_partial;        // [gridDim.x]
+    float *sink;              // [64] target of the stores of lanes past the padded batch
     int B, Bp, T, n_seas, m1, m2, logit;
     int row_gamma1, row_gamma2, row_s1, row_s2;
 };
@@ -230,66 +231,90 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
             float s = in_batch ? a.es[(size_t)(a.row_s2 + k) * a.B + b] : 1.0f;
             ring2[k * 64 + lane] = (a.logit && in_batch) ? expf(s) : s;
         }
+    // Lanes past the padded batch (last workgroup only) keep storing, into a sink, with stride 0:
+    // no store is ever skipped, so every path through a step issues the same memory operations.
     const bool store = b < a.Bp;
+    const int row_stride = store ? a.Bp : 0;
+    float *const lvl_b = store ? a.lvl + b : a.sink + lane;
+    float *const u_b = store ? a.u + b : a.sink + lane;
+    float *const v_b = store ? a.v + b : a.sink + lane;
+    float *const S1_b = store ? a.S1 + b : a.sink + lane;
+    float *const S2_b = store ? a.S2 + b : a.sink + lane;
     float l_prev = 1.0f, u1 = 0.0f, u2 = 0.0f, lv_sum = 0.0f;
     int i1 = 0, i2 = 0;
     const float one_m_alpha = 1.0f - alpha;
-    // observations are requested a chunk ahead so that no step waits for memory
+    // factors for the current time, read from the ring one step ahead of their use
+    float s1_cur = 1.0f, s2_cur = 1.0f;
+    if (NS >= 1) s1_cur = ring1[lane];
+    if (NS >= 2) s2_cur = ring2[lane];
+    auto step = [&](int t, float yraw) {
+        const bool live = t < len;
+        const float yt = live ? yraw : 1.0f;
+        const float s1 = s1_cur, s2 = s2_cur;
+        // slot of time t+1: last written m-1 steps ago unless m = 1 (then it is the value written below)
+        const int j1 = i1 + 1 == a.m1 ? 0 : i1 + 1, j2 = i2 + 1 == a.m2 ? 0 : i2 + 1;
+        float s1_nxt = 1.0f, s2_nxt = 1.0f;
+        if (NS >= 1) s1_nxt = ring1[j1 * 64 + lane];
+        if (NS >= 2) s2_nxt = ring2[j2 * 64 + lane];
+        const float q = (yt) * fast_rcp(s1 * s2);
+        // reading for the state before the first observation: l_{-1} = y_0 / S[0]
+        const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
+        if (t >= 1) {
+            // Eq. (3): divide by the previous level (and the other factor)
+            const float ry = (yt) * fast_rcp(l_prev);
+            if (NS >= 1) {
+                const float w = g1 * (ry) * fast_rcp(s2) + (1.0f - g1) * s1;
+                ring1[i1 * 64 + lane] = w;
+                if (a.m1 == 1) s1_nxt = w;
+            }
+            if (NS >= 2) {
+                const float w = g2 * (ry) * fast_rcp(s1) + (1.0f - g2) * s2;
+                ring2[i2 * 64 + lane] = w;
+                if (a.m2 == 1) s2_nxt = w;
+            }
+        }
+        s1_cur = s1_nxt; s2_cur = s2_nxt;
+        const float ut = live ? __logf(lt) : 0.0f;
+        const float vt = live ? __logf(q) : 0.0f;      // ln y - ln(S1 S2)
+        const int o = t * row_stride;
+        lvl_b[o] = live ? lt : 1.0f;
+        u_b[o] = ut;
+        v_b[o] = vt;
+        if (NS >= 1) S1_b[o] = live ? s1 : 1.0f;
+        if (NS >= 2) S2_b[o] = live ? s2 : 1.0f;
+        // Section 8.4: squared second difference of the log level
+        const float e = ut - 2.0f * u1 + u2;
+        lv_sum += (live && t >= 2) ? e * e : 0.0f;
+        u2 = u1; u1 = ut;
+        if (live) l_prev = lt;
+        i1 = j1; i2 = j2;
+    };
+    // Observations are requested a chunk ahead so that no step waits for memory.  The body of a whole
+    // chunk has no wave-level branch: memory operations complete in order, and only with a fixed number
+    // of stores between a request and its use can the wait for the request leave those stores in flight.
     constexpr int CH = 8;
     float ybuf[CH], ynext[CH];
     auto load_chunk = [&](int t0, float *dst) {
 #pragma unroll
         for (int k = 0; k < CH; ++k) {
             const int t = t0 + k;
-            const float val = a.y[(size_t)(t < len ? t : 0) * a.B + (in_batch ? b : 0)];
-            dst[k] = t < len ? val : 1.0f;
+            // raw value; the step replaces what lies past the series' length (no use of the load here,
+            // so that nothing waits for it before the chunk is needed)
+            dst[k] = a.y[(size_t)(t < len ? t : 0) * a.B + (in_batch ? b : 0)];
         }
     };
     load_chunk(0, ybuf);
-    for (int t0 = 0; t0 < a.T; t0 += CH) {
+    int t0 = 0;
+    for (; t0 + CH <= a.T; t0 += CH) {
         load_chunk(t0 + CH, ynext);
 #pragma unroll
-        for (int k = 0; k < CH; ++k) {
-            const int t = t0 + k;
-            if (t < a.T) {
-                const bool live = t < len;
-                const float yt = ybuf[k];
-                float s1 = 1.0f, s2 = 1.0f;
-                if (NS >= 1) s1 = ring1[i1 * 64 + lane];
-                if (NS >= 2) s2 = ring2[i2 * 64 + lane];
-                const float q = (yt) * fast_rcp(s1 * s2);
-                // reading for the state before the first observation: l_{-1} = y_0 / S[0]
-                const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
-                if (t >= 1) {
-                    // Eq. (3): divide by the previous level (and the other factor)
-                    const float ry = (yt) * fast_rcp(l_prev);
-                    if (NS >= 1) ring1[i1 * 64 + lane] = g1 * (ry) * fast_rcp(s2) + (1.0f - g1) * s1;
-                    if (NS >= 2) ring2[i2 * 64 + lane] = g2 * (ry) * fast_rcp(s1) + (1.0f - g2) * s2;
-                }
-                const float ut = live ? __logf(lt) : 0.0f;
-                const float vt = live ? __logf(q) : 0.0f;      // ln y - ln(S1 S2)
-                if (store) {
-                    const size_t o = (size_t)t * a.Bp + b;
-                    a.lvl[o] = live ? lt : 1.0f;
-                    a.u[o] = ut;
-                    a.v[o] = vt;
-                    if (NS >= 1) a.S1[o] = live ? s1 : 1.0f;
-                    if (NS >= 2) a.S2[o] = live ? s2 : 1.0f;
-                }
-                // Section 8.4: squared second difference of the log level
-                if (live && t >= 2) {
-                    const float e = ut - 2.0f * u1 + u2;
-                    lv_sum += e * e;
-                }
-                u2 = u1; u1 = ut;
-                if (live) l_prev = lt;
-                if (NS >= 1 && ++i1 == a.m1) i1 = 0;
-                if (NS >= 2 && ++i2 == a.m2) i2 = 0;
-            }
-        }
+        for (int k = 0; k < CH; ++k) step(t0 + k, ybuf[k]);
 #pragma unroll
         for (int k = 0; k < CH; ++k) ybuf[k] = ynext[k];
     }
+#pragma unroll
+    for (int k = 0; k < CH; ++k)
+        if (t0 + k < a.T) step(t0 + k, ybuf[k]);
     const float tot = wave_sum(lv_sum);
     if (lane == 0) a.lv_partial[blockIdx.x] = tot;
 }
@@ -436,72 +461,86 @@ __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
     for (int k = 0; k < a.m2; ++k) ring2[k * 64 + lane] = 0.0f;
     float ab = 0.0f, g1b = 0.0f, g2b = 0.0f;
     float Lb_carry = 0.0f;      // contributions to the adjoint of l[t] from later steps
-    int i1 = 0, i2 = 0;
-    if (len > 0) {
-        if (NS >= 1) i1 = (len - 1) % a.m1;
-        if (NS >= 2) i2 = (len - 1) % a.m2;
-    }
-    // operands are requested a chunk of steps ahead (descending in time)
+    // The sweep runs over the same times T-1 ... 1 in every lane; a lane takes part from its own last
+    // observation on (its state updates are switched off before that).  Time, ring slots and row
+    // addresses are then wave-uniform, and a step has no branch: memory operations complete in
+    // order, and only with a fixed number of them between a request and its use can the operands be
+    // requested a chunk ahead without waiting for anything younger.
+    // Rows past a series' length hold defined values (level 1, factors 1, zero adjoints).
     constexpr int CH = 4;
     struct Chunk { float gu[CH], gv[CH], y[CH], lp[CH], s1[CH], s2[CH]; };
     Chunk cur, nxt;
     auto load_chunk = [&](int t_hi, Chunk &c) {
 #pragma unroll
         for (int k = 0; k < CH; ++k) {
-            const int t = t_hi - k;
-            const int tc = t >= 1 ? t : 1;                 // steps below 1 are not executed
-            const size_t o = (size_t)tc * a.Bp + b;
-            c.gu[k] = a.gu[o];
-            c.gv[k] = a.gv[o];
-            c.y[k] = a.y[(size_t)tc * a.B + b];
-            c.lp[k] = a.lvl[o - a.Bp];
-            c.s1[k] = NS >= 1 ? a.S1[o] : 1.0f;
-            c.s2[k] = NS >= 2 ? a.S2[o] : 1.0f;
+            const int tc = max(t_hi - k, 1);                // steps below 1 are not executed
+            const size_t row = (size_t)tc * a.Bp;           // wave-uniform
+            c.gu[k] = (a.gu + row)[b];
+            c.gv[k] = (a.gv + row)[b];
+            c.y[k] = (a.y + (size_t)tc * a.B)[b];
+            c.lp[k] = (a.lvl + row - a.Bp)[b];
+            c.s1[k] = NS >= 1 ? (a.S1 + row)[b] : 1.0f;
+            c.s2[k] = NS >= 2 ? (a.S2 + row)[b] : 1.0f;
         }
     };
-    float lt = len >= 1 ? a.lvl[(size_t)(len - 1) * a.Bp + b] : 1.0f;
-    if (len >= 2) load_chunk(len - 1, cur);
-    for (int t_hi = len - 1; t_hi >= 1; t_hi -= CH) {
-        if (t_hi - CH >= 1) load_chunk(t_hi - CH, nxt);
-#pragma unroll
-        for (int k = 0; k < CH; ++k) {
-            const int t = t_hi - k;
-            if (t >= 1) {
-                const float yt = cur.y[k], lp = cur.lp[k], s1 = cur.s1[k], s2 = cur.s2[k], gvt = cur.gv[k];
-                const float Lb = (cur.gu[k]) * fast_rcp(lt) + Lb_carry;
-                float S1b = NS >= 1 ? -(gvt) * fast_rcp(s1) : 0.0f;
-                float S2b = NS >= 2 ? -(gvt) * fast_rcp(s2) : 0.0f;
-                float Lb_prev = 0.0f;
-                const float ry = (yt) * fast_rcp(lp);
-                if (NS >= 1) {
-                    const float A = (t + a.m1 <= len - 1) ? ring1[i1 * 64 + lane] : 0.0f;
-                    const float r = (ry) * fast_rcp(s2);
-                    g1b += A * (r - s1);
-                    Lb_prev -= (A * g1 * r) * fast_rcp(lp);
-                    S2b -= (A * g1 * r) * fast_rcp(s2);
-                    S1b += A * (1.0f - g1);
-                }
-                if (NS >= 2) {
-                    const float A = (t + a.m2 <= len - 1) ? ring2[i2 * 64 + lane] : 0.0f;
-                    const float r = (ry) * fast_rcp(s1);
-                    g2b += A * (r - s2);
-                    Lb_prev -= (A * g2 * r) * fast_rcp(lp);
-                    S1b -= (A * g2 * r) * fast_rcp(s1);
-                    S2b += A * (1.0f - g2);
-                }
-                const float q = (yt) * fast_rcp(s1 * s2);
-                ab += Lb * (q - lp);
-                S1b -= (Lb * alpha * q) * fast_rcp(s1);
-                S2b -= (Lb * alpha * q) * fast_rcp(s2);
-                Lb_prev += Lb * (1.0f - alpha);
-                if (NS >= 1) { ring1[i1 * 64 + lane] = S1b; if (--i1 < 0) i1 = a.m1 - 1; }
-                if (NS >= 2) { ring2[i2 * 64 + lane] = S2b; if (--i2 < 0) i2 = a.m2 - 1; }
-                Lb_carry = Lb_prev;
-                lt = lp;
-            }
+    const int t_top = a.T - 1;
+    float lt = a.lvl[(size_t)t_top * a.Bp + b];
+    int i1 = NS >= 1 ? t_top % a.m1 : 0, i2 = NS >= 2 ? t_top % a.m2 : 0;   // ring slot of time t: t mod m
+    // adjoint of the factor for time t + m, requested one step ahead of its use
+    float A1 = 0.0f, A2 = 0.0f;
+    auto step = [&](int t, int k) {
+        const bool active = t <= len - 1;
+        const float yt = cur.y[k], lp = cur.lp[k], s1 = cur.s1[k], s2 = cur.s2[k], gvt = cur.gv[k];
+        // slot of the next step (time t-1): last written m-1 steps ago unless m = 1
+        const int j1 = i1 == 0 ? a.m1 - 1 : i1 - 1, j2 = i2 == 0 ? a.m2 - 1 : i2 - 1;
+        float A1n = 0.0f, A2n = 0.0f;
+        if (NS >= 1) A1n = ring1[j1 * 64 + lane];
+        if (NS >= 2) A2n = ring2[j2 * 64 + lane];
+        const float Lb = (cur.gu[k]) * fast_rcp(lt) + Lb_carry;
+        float S1b = NS >= 1 ? -(gvt) * fast_rcp(s1) : 0.0f;
+        float S2b = NS >= 2 ? -(gvt) * fast_rcp(s2) : 0.0f;
+        float Lb_prev = 0.0f;
+        const float ry = (yt) * fast_rcp(lp);
+        if (NS >= 1) {
+            const float A = A1;
+            const float r = (ry) * fast_rcp(s2);
+            g1b += active ? A * (r - s1) : 0.0f;
+            Lb_prev -= (A * g1 * r) * fast_rcp(lp);
+            S2b -= (A * g1 * r) * fast_rcp(s2);
+            S1b += A * (1.0f - g1);
         }
+        if (NS >= 2) {
+            const float A = A2;
+            const float r = (ry) * fast_rcp(s1);
+            g2b += active ? A * (r - s2) : 0.0f;
+            Lb_prev -= (A * g2 * r) * fast_rcp(lp);
+            S1b -= (A * g2 * r) * fast_rcp(s1);
+            S2b += A * (1.0f - g2);
+        }
+        const float q = (yt) * fast_rcp(s1 * s2);
+        ab += active ? Lb * (q - lp) : 0.0f;
+        S1b -= (Lb * alpha * q) * fast_rcp(s1);
+        S2b -= (Lb * alpha * q) * fast_rcp(s2);
+        Lb_prev += Lb * (1.0f - alpha);
+        // an inactive lane leaves the slot as it is (zero)
+        if (NS >= 1) { ring1[i1 * 64 + lane] = active ? S1b : A1; A1 = (a.m1 == 1 && active) ? S1b : A1n; i1 = j1; }
+        if (NS >= 2) { ring2[i2 * 64 + lane] = active ? S2b : A2; A2 = (a.m2 == 1 && active) ? S2b : A2n; i2 = j2; }
+        Lb_carry = active ? Lb_prev : 0.0f;
+        lt = lp;
+    };
+    if (NS >= 1) A1 = ring1[i1 * 64 + lane];
+    if (NS >= 2) A2 = ring2[i2 * 64 + lane];
+    load_chunk(t_top, cur);
+    int t_hi = t_top;
+    for (; t_hi - CH >= 0; t_hi -= CH) {        // whole chunks: steps t_hi ... t_hi-CH+1, all >= 1
+        load_chunk(t_hi - CH, nxt);
+#pragma unroll
+        for (int k = 0; k < CH; ++k) step(t_hi - k, k);
         cur = nxt;
     }
+#pragma unroll
+    for (int k = 0; k < CH; ++k)
+        if (t_hi - k >= 1) step(t_hi - k, k);
     if (len >= 1) {
         // t = 0: l[0] = y0 / (S1[0] S2[0]); the first produced factors equal the initial ones
         const size_t o = b;
@@ -719,7 +758,7 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
 {
     const esrnn_config &c = pl.cfg;
     EsArgs a{y, lengths, es, ws + pl.lvl, ws + pl.S1, ws + pl.S2, ws + pl.u, ws + pl.v,
-             ws + pl.loss_partial + (pl.n_loss_partial - pl.es_blocks),
+             ws + pl.loss_partial + (pl.n_loss_partial - pl.es_blocks), ws + pl.sink,
              pl.B, pl.Bp, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
              c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
     const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);

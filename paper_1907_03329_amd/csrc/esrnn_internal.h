@@ -56,6 +56,7 @@ struct Plan {
     size_t Wa_off, ba_off, Wo_off, bo_off, n_weights;
     // workspace map (offsets in floats)
     size_t scalars;      // float[16]: see Scalars
+    size_t sink;         // float[64]: where the lanes past the padded batch put their stores
     size_t lvl, S1, S2, u, v, gu, gv;   // [T][Bp]
     size_t X, Z;         // TL(4*IT), TL(OP)
     size_t blk_out[ESRNN_MAX_BLOCKS];
