@@ -62,6 +62,7 @@ struct Plan {
     size_t blk_out[ESRNN_MAX_BLOCKS];
     size_t A, O, gO, gTop, gX;
     size_t dx[kMaxLayers];              // gradient with respect to the input of layer l (layer 0: gX)
+    size_t gsum;                        // TL(HP) sum of gradient sources (three or more blocks only)
     size_t head_fwd_pack, head_bwd_pack; // packed head operands
     size_t loss_partial; int n_loss_partial;   // [head_fwd_blocks] pinball sums, then [es_blocks] level-penalty sums
     int head_fwd_blocks;                       // workgroups of the output-stage forward kernel

@@ -175,8 +175,8 @@ struct LstmBwdArgs {
     const float *wpack;   // [MB][4*HT][64]
     const float *xsrc;    // TL(4*KXT)
     const float *gates, *c, *hid;
-    const float *gsrc[4]; // TL(HP): the gradient arriving at the hidden output is the sum of these
-    int n_gsrc;
+    const float *gsrc[2]; // TL(HP): the gradient arriving at the hidden output is the sum of these
+    int n_gsrc;           // 1 or 2; gsrc[1] repeats gsrc[0] when there is one
     float *gdst;          // TL(4*KXT)
     float *dw_partial;    // [NB*chains][HT*MB][4][64]
     float *db_partial;    // [NB*chains][HT][4][4]
@@ -259,13 +259,6 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             const float *src = q < KXT ? a.xsrc + pb * xtile + q * 64 : a.hid + pbd * htile + (q - KXT) * 64;
             pf_xh[i] = src[lane];
         }
-        if (a.n_gsrc > 2) {             // more than two residual blocks: rare, summed eagerly
-#pragma unroll
-            for (int j = 0; j < MTW; ++j) {
-                const size_t tile = (pb * HT + min(s + W * j, HT - 1)) * 64;
-                for (int k = 2; k < a.n_gsrc; ++k) pf_g2[j] += (a.gsrc[k] + tile)[lane];
-            }
-        }
     };
 
     const float g2_scale = a.n_gsrc >= 2 ? 1.0f : 0.0f;
@@ -322,16 +315,14 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     };
     // ---- end of position p: sum the partials this wave needs (recurrent dh of its
     // units) or stores (input gradient), and pull the operands of step C into registers
-    float xb[MB][4], ar[MTW][4];
+    float xb[MB][4], ar[MTW][4], dxv[QXW];
     auto finish = [&](int p) {
-        const size_t pb = (size_t)p * a.NB + bt;
         lds_barrier();              // partials, da, [x ; h] of position p complete
 #pragma unroll
         for (int j = 0; j < MTW; ++j) {
             const int q = min(KXT + s + W * j, KT - 1);   // row of part_lds = unit tile of [x ; h]
             dhreg[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
         }
-        float dxv[QXW];
 #pragma unroll
         for (int j = 0; j < QXW; ++j) {
             const int q = min(s + W * j, KXT - 1);
@@ -347,9 +338,15 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             for (int ks = 0; ks < 4; ++ks)
                 ar[j][ks] = da_lds[(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
         lds_barrier();              // everything of position p has been read
+    };
+    // The input gradient of position p leaves after the elementwise work of the next position and
+    // ahead of the next operand requests.  Memory operations complete in order: a store issued between
+    // a request and its use would have to complete before that use; here it has a whole position.
+    auto store_dx = [&](int p) {
+        const size_t pb = (size_t)p * a.NB + bt;
 #pragma unroll
         for (int j = 0; j < QXW; ++j)
-            if (j < QXW - 1 || last_qx_valid) a.gdst[pb * xtile + (s + W * j) * 64 + lane] = dxv[j];
+            if (j < QXW - 1 || last_qx_valid) (a.gdst + pb * xtile + (s + W * j) * 64)[lane] = dxv[j];
     };
     auto dw_row = [&](int j) {
 #pragma unroll
@@ -382,11 +379,13 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
                 dw_row(j);
             }
             step_a_tile(MTW - 1, has_prev);
+            store_dx(p);
             fetch(max(p - 2 * a.d, r0));
             if (last_row_valid) dw_row(MTW - 1);
             step_b();
         }
         finish(r0);
+        store_dx(r0);
 #pragma unroll
         for (int j = 0; j < MTW - 1; ++j) dw_row(j);
         if (last_row_valid) dw_row(MTW - 1);
@@ -415,6 +414,22 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             if (n == 0 && mt < HT) a.db_partial[(part * HT + mt) * 16 + g * 4 + rr] = tot;
         }
     }
+}
+
+// out = a + b (+ c): gradient sources of a layer behind three or more residual blocks
+__global__ void __launch_bounds__(256) sum_sources_kernel(const float4 *__restrict__ a, const float4 *__restrict__ b,
+                                                           const float4 *__restrict__ c, float4 *__restrict__ out, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float4 v = a[i];
+    const float4 w = b[i];
+    v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+    if (c) {
+        const float4 u = c[i];
+        v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+    }
+    out[i] = v;
 }
 
 template <int HT, int KXT>
@@ -451,8 +466,21 @@ hipError_t launch_lstm_backward(const Plan &pl, int layer, float *ws, hipStream_
     const LayerPlan &lp = pl.layer[layer];
     LstmBwdArgs a{};
     a.wpack = ws + lp.wpack_bwd; a.xsrc = ws + lp.xsrc; a.gates = ws + lp.gates; a.c = ws + lp.c; a.hid = ws + lp.hid;
-    a.n_gsrc = lp.n_gsrc;
-    for (int k = 0; k < 4; ++k) a.gsrc[k] = ws + lp.gsrc[k < lp.n_gsrc ? k : 0];
+    a.n_gsrc = lp.n_gsrc < 2 ? lp.n_gsrc : 2;
+    a.gsrc[0] = ws + lp.gsrc[0];
+    a.gsrc[1] = ws + lp.gsrc[lp.n_gsrc >= 2 ? 1 : 0];
+    if (lp.n_gsrc > 2) {
+        // three or more residual blocks: the sources past the first are summed into a buffer of their
+        // own first (they stay intact for the layers that consume them separately)
+        const size_t n4 = (size_t)pl.P * pl.NB * pl.HT * 16;   // float4 elements of a TL(HP) array
+        const float *s3 = lp.n_gsrc > 3 ? ws + lp.gsrc[3] : nullptr;
+        sum_sources_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(
+            reinterpret_cast<const float4 *>(ws + lp.gsrc[1]), reinterpret_cast<const float4 *>(ws + lp.gsrc[2]),
+            reinterpret_cast<const float4 *>(s3), reinterpret_cast<float4 *>(ws + pl.gsum), n4);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        a.gsrc[1] = ws + pl.gsum;
+    }
     a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
     a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
 #define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains, st);

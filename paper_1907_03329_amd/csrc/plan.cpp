@@ -204,6 +204,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
             lp.gsrc[lp.n_gsrc++] = pl.dx[l + 1];
         }
     }
+    if (cfg.n_blocks >= 3) pl.gsum = ws.take(PN * tileH);
     const HeadPack hp = head_pack_layout(pl);
     pl.head_fwd_pack = ws.take(hp.fwd_total);
     pl.head_bwd_pack = ws.take(hp.bwd_total);

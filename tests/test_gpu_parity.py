@@ -74,6 +74,12 @@ def test_three_blocks_and_single_layer_blocks():
     report(gc.run_and_check(cfg, seed=8, ragged=True))
 
 
+def test_four_blocks():
+    # the last layer of the first block receives gradient from the output stage and from three later blocks
+    cfg = small("four_blocks", blocks=((1, 2), (1,), (3,), (2, 4)), hidden=7, I=4, H=3, B=21)
+    report(gc.run_and_check(cfg, seed=21, ragged=True))
+
+
 def test_input_window_padded_to_hidden_tiles():
     # I = 13 has no dedicated kernel shape with hidden 30: the input is padded to the hidden tile count
     cfg = small("padded_input", hidden=30, I=13, H=3, T=48)
