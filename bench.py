@@ -30,7 +30,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("quarterly", 4096): {
         "lstm_forward_l0": 244e6, "lstm_forward_l1": 309e6, "lstm_forward_l2": 309e6, "lstm_forward_l3": 309e6,
         "lstm_backward_l0": 296e6, "lstm_backward_l1": 406e6, "lstm_backward_l2": 406e6, "lstm_backward_l3": 406e6,
-        "head_forward": 122e6, "head_backward": 179e6, "window_forward": 22.2e6, "window_backward": 15.6e6,
+        "window_forward": 22.2e6, "window_backward": 15.6e6,
         "es_forward": 6.2e6, "es_backward": 6.1e6,
     },
 }
@@ -51,10 +51,10 @@ def stage_model(cfg, name):
         if name.startswith("lstm_backward"):
             per *= 2                      # transposed contraction + weight gradient
         return "mfma", float(per) * B * P, "flop"
-    if name == "head_forward":
-        return "mfma", 2.0 * (h * h + H * h) * B * P, "flop"
-    if name == "head_backward":
-        return "mfma", 4.0 * (h * h + H * h) * B * P, "flop"
+    if name == "head_forward_backward":
+        # bound by its streams: read the top block output and the targets; write outputs, forecasts,
+        # the loss gradient and the gradient of the top block output
+        return "hbm", 4.0 * B * P * (2 * h + 4 * H), "byte"
     if name == "es_forward":
         return "hbm", 4.0 * B * T * (1 + 3 + n_seas) + 4.0 * B * cfg.K, "byte"       # read y; write level, u, v, factors
     if name == "es_backward":
@@ -108,7 +108,7 @@ def es_window_sweep(args, torch, binding, synth):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="quarterly")
     ap.add_argument("--batch", type=int, default=0, help="override the number of series")
@@ -243,6 +243,7 @@ def main():
         "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "seasons": [m for m in (cfg.m1, cfg.m2) if m],
                    "I": cfg.I, "H": cfg.H, "hidden": cfg.hidden, "dilations": [list(b) for b in cfg.blocks],
                    "tau": cfg.tau, "lambda_lv": cfg.lambda_lv, "window_steps": cfg.B * cfg.P},
+        "window_steps_per_s": round(cfg.B * cfg.P / (elapsed / args.steps), 1),
         "loss": loss,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -92,6 +92,10 @@ const char *esrnn_status_string(esrnn_status s);
 
 /*
  * Forward pass: smoothing recursions, windows, network, loss, forecasts.
+ * The output stage (Sections 3.4, 3.5) also runs its own reverse pass here,
+ * while its activations are on chip: the gradient of the pinball loss with
+ * respect to an output needs only that output, its target and the count of
+ * unmasked outputs.  Its results wait in the workspace for esrnn_backward.
  *
  *   y          [T][B] time-major.  Series b occupies t = 0 .. lengths[b]-1.
  *   lengths    [B] int32, I + H <= lengths[b] <= T (values outside are clamped).
@@ -159,8 +163,9 @@ typedef enum {
     ESRNN_BUF_GATES,                                                             /* gate tile, index = layer */
     ESRNN_BUF_C, ESRNN_BUF_HID,                                                  /* tile, index = layer */
     ESRNN_BUF_BLOCK_OUT,                                                         /* tile, index = block */
-    ESRNN_BUF_A, ESRNN_BUF_O,                                                    /* tile */
-    ESRNN_BUF_GRAD_O, ESRNN_BUF_GRAD_TOP, ESRNN_BUF_GRAD_X,                      /* tile (after backward) */
+    ESRNN_BUF_O,                                                                 /* tile: linear-layer outputs */
+    ESRNN_BUF_GRAD_O, ESRNN_BUF_GRAD_TOP,                                        /* tile (filled by esrnn_forward) */
+    ESRNN_BUF_GRAD_X,                                                            /* tile (after backward) */
     ESRNN_BUF_GRAD_U, ESRNN_BUF_GRAD_V,                                          /* time-major (after backward) */
     ESRNN_BUF_COUNT_
 } esrnn_buffer;

@@ -18,7 +18,7 @@ ESRNN_OK = 0
 PARAMS_DIRECT, PARAMS_LOGIT = 0, 1
 LAYOUT_TIME_MAJOR, LAYOUT_TILE, LAYOUT_GATE_TILE = 0, 1, 2
 BUFFERS = {name: i for i, name in enumerate([
-    "level", "S1", "S2", "u", "v", "X", "Z", "gates", "c", "hid", "block_out", "A", "O",
+    "level", "S1", "S2", "u", "v", "X", "Z", "gates", "c", "hid", "block_out", "O",
     "grad_O", "grad_top", "grad_X", "grad_u", "grad_v"])}
 
 

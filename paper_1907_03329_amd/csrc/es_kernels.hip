@@ -136,13 +136,15 @@ __device__ void pack_head_body(const PackHeadArgs &a)
         j -= nbaF;
         if (j < nWoF) {
             const int lane = j & 63, q = (j >> 6) % a.HT, mo = (j >> 6) / a.HT;
-            const int row = 16 * mo + (lane & 15), in = 4 * q + (lane >> 4);
+            const int i = lane & 15;
+            const int row = 4 * (4 * mo + (i & 3)) + (i >> 2), in = 4 * q + (lane >> 4);
             a.WoF[j] = (row < a.H && in < a.h) ? a.Wo[row * a.h + in] : 0.0f;
             continue;
         }
         j -= nWoF;
         if (j < nboF) {
-            const int row = 16 * (j >> 4) + (j & 15);   // 4g + r within the tile
+            const int r = j & 3, g = (j >> 2) & 3, mo = j >> 4;
+            const int row = 4 * (4 * mo + r) + g;
             a.boF[j] = row < a.H ? a.bo[row] : 0.0f;
             continue;
         }

@@ -25,8 +25,8 @@ struct esrnn_handle {
     int n_stages;
     Stage stage[kMaxStages];
     // stage indices
-    int st_setup, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head_fwd, st_loss;
-    int st_head_bwd, st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce;
+    int st_setup, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head, st_loss;
+    int st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce;
 };
 
 namespace {
@@ -84,9 +84,8 @@ esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
     h->st_es_fwd = add_stage(h, "es_forward", 0);
     h->st_win_fwd = add_stage(h, "window_forward", 0);
     for (int l = 0; l < pl.L; ++l) h->st_lstm_fwd[l] = add_stage(h, "lstm_forward_l%d", l);
-    h->st_head_fwd = add_stage(h, "head_forward", 0);
+    h->st_head = add_stage(h, "head_forward_backward", 0);
     h->st_loss = add_stage(h, "loss_finalize", 0);
-    h->st_head_bwd = add_stage(h, "head_backward", 0);
     for (int l = pl.L - 1; l >= 0; --l) h->st_lstm_bwd[l] = add_stage(h, "lstm_backward_l%d", l);
     h->st_win_bwd = add_stage(h, "window_backward", 0);
     h->st_es_bwd = add_stage(h, "es_backward", 0);
@@ -155,7 +154,8 @@ esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengt
     ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, ws, st); }));
     for (int l = 0; l < pl.L; ++l)
         ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ws, st); }));
-    ESRNN_TRY(run_stage(h, h->st_head_fwd, st, [&] { return launch_head_forward(pl, lengths, ws, forecasts, st); }));
+    // the output stage runs its reverse pass in the same launch: the loss gradient needs nothing beyond it
+    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, lengths, ws, forecasts, st); }));
     ESRNN_TRY(run_stage(h, h->st_loss, st, [&] { return launch_loss_finalize(pl, ws, loss, st); }));
     h->forward_done = true;
     return ESRNN_OK;
@@ -172,7 +172,6 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
     const Plan &pl = h->plan;
     float *ws = static_cast<float *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    ESRNN_TRY(run_stage(h, h->st_head_bwd, st, [&] { return launch_head_backward(pl, lengths, ws, st); }));
     for (int l = pl.L - 1; l >= 0; --l)
         ESRNN_TRY(run_stage(h, h->st_lstm_bwd[l], st, [&] { return launch_lstm_backward(pl, l, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_win_bwd, st, [&] { return launch_window_backward(pl, lengths, ws, st); }));
@@ -295,7 +294,6 @@ esrnn_status esrnn_workspace_buffer(const esrnn_handle *h, int32_t which, int32_
     case ESRNN_BUF_Z: off = pl.Z; rows = pl.OP; logical = pl.H; break;
     case ESRNN_BUF_O: off = pl.O; rows = pl.OP; logical = pl.H; break;
     case ESRNN_BUF_GRAD_O: off = pl.gO; rows = pl.OP; logical = pl.H; break;
-    case ESRNN_BUF_A: off = pl.A; rows = pl.HP; logical = pl.h; break;
     case ESRNN_BUF_GRAD_TOP: off = pl.gTop; rows = pl.HP; logical = pl.h; break;
     case ESRNN_BUF_GATES:
         if (!layer_ok(index)) return ESRNN_ERR_CONFIG;

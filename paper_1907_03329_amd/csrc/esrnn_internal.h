@@ -60,13 +60,13 @@ struct Plan {
     size_t lvl, S1, S2, u, v, gu, gv;   // [T][Bp]
     size_t X, Z;         // TL(4*IT), TL(OP)
     size_t blk_out[ESRNN_MAX_BLOCKS];
-    size_t A, O, gO, gTop, gX;
+    size_t O, gO, gTop, gX;
     size_t dx[kMaxLayers];              // gradient with respect to the input of layer l (layer 0: gX)
     size_t gsum;                        // TL(HP) sum of gradient sources (three or more blocks only)
     size_t head_fwd_pack, head_bwd_pack; // packed head operands
-    size_t loss_partial; int n_loss_partial;   // [head_fwd_blocks] pinball sums, then [es_blocks] level-penalty sums
-    int head_fwd_blocks;                       // workgroups of the output-stage forward kernel
-    size_t head_dw_partial; int n_head_waves;  // [n_head_waves][head_dw_stride]; waves of the reverse kernel
+    size_t loss_partial; int n_loss_partial;   // [head_blocks] pinball sums, then [es_blocks] level-penalty sums
+    int head_blocks;                           // workgroups of the output-stage kernel
+    size_t head_dw_partial; int n_head_waves;  // [n_head_waves][head_dw_stride]; 4 waves per workgroup
     int head_dw_stride;
     size_t head_dw_reduced;
     int es_blocks;
@@ -83,7 +83,7 @@ struct Scalars {
 // offsets inside the packed head operand blocks (floats), filled by plan.cpp
 struct HeadPack {
     // forward: Wa as A operand in unit-tile order [MA][HT][64], ba [MA][4][4],
-    //          Wo as A operand, rows in natural order [MO][HT][64], bo [MO][4][4]
+    //          Wo as A operand in unit-tile order [MO][HT][64], bo [MO][4][4]
     size_t WaF, baF, WoF, boF, fwd_total;
     // backward: Wo^T [MA][OT][64], Wa^T [MA][HT][64]
     size_t WoT, WaT, bwd_total;
@@ -98,11 +98,10 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
                              float *ws, hipStream_t st);
 hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st);
 hipError_t launch_lstm_forward(const Plan &pl, int layer, float *ws, hipStream_t st);
-hipError_t launch_head_forward(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts,
-                               hipStream_t st);
+// output stage, forward and reverse in one launch (needs the loss normalisers of launch_setup)
+hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st);
 hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStream_t st);
 
-hipError_t launch_head_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
 hipError_t launch_lstm_backward(const Plan &pl, int layer, float *ws, hipStream_t st);
 hipError_t launch_window_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
 hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,

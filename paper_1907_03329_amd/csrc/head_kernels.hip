@@ -1,13 +1,19 @@
 // Output stage of the network (Section 3.4: tanh layer, then linear layer), the
 // pinball loss over unmasked outputs (Section 3.5), the forecasts of Eq. (5),
-// and the reverse pass of all three.  Every (window position, 16-series) tile is
-// independent: one wave processes one tile at a time with both weight matrices
-// as register-resident A operands of the 16x16x4 fp32 MFMA.
+// and the reverse pass of all three, in ONE kernel: the gradient of the loss
+// with respect to an output depends only on that output, its target and the
+// number of unmasked outputs (known from the lengths), so the reverse pass of
+// this stage can run while the activations are still in registers.  Every
+// (window position, 16-series) tile is independent: one wave processes one
+// tile at a time with the four weight operands (both matrices, both
+// orientations) register-resident for the 16x16x4 fp32 MFMA.
 //
-// Row orders.  "Unit-tile order" of a 16-row output tile ma: row 4g+r is hidden
-// unit 4(4ma+r)+g, so that component r of lane (g, n) is unit tile 4ma+r in the
-// one-float-per-lane layout and can be fed back as the B operand of k-step
-// 4ma+r.  The linear layer's output rows are in natural order.
+// Row order.  "Unit-tile order" of a 16-row output tile m: row 4g+r is logical
+// row 4(4m+r)+g, so that component r of lane (g, n) belongs to unit tile 4m+r
+// in the one-float-per-lane layout and can be fed back, as it stands, as the B
+// operand of k-step 4m+r.  Both forward products use it: the tanh layer's
+// output feeds the linear layer, and the linear layer's output (hence the loss
+// gradient) feeds the transposed products.
 #include "device_utils.h"
 #include "esrnn_internal.h"
 
@@ -15,36 +21,58 @@ namespace esrnn {
 
 namespace {
 
-struct HeadFwdArgs {
-    const float *WaF, *baF, *WoF, *boF;
+struct HeadArgs {
+    const float *WaF, *baF, *WoF, *boF;   // forward A operands and biases
+    const float *WoT, *WaT;               // transposed A operands
     const float *R;         // TL(HP) top block output
-    const float *Z;         // TL(OP)
+    const float *Z;         // TL(OP) targets
     const float *u, *S1, *S2;   // [T][Bp]
     const int32_t *lengths;
-    float *A, *O;           // TL(HP), TL(OP)
+    const Scalars *sc;
+    float *O;               // TL(OP) outputs
     float *forecasts;       // [P][B][H] or null
     float *loss_partial;    // [gridDim.x]
-    int P, NB, B, Bp, T, I, H, n_seas;
-    int orows;              // rows of the Z and O tiles: 4 * ceil(H / 4)
+    float *gO;              // TL(OP): dL/d(output); the target's gradient is its negative
+    float *gTop;            // TL(HP): dL/d(top block output)
+    float *partial;         // [4 * gridDim.x][stride] weight-gradient partials of every wave
+    int P, NB, B, Bp, T, I, H, n_seas, stride;
+    int orows;              // rows of the Z, O and gO tiles: 4 * ceil(H / 4)
     float tau;
 };
 
 template <int HT, int MO>
-__global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
+__global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
 {
     constexpr int MA = (HT + 3) / 4;
     constexpr int OP = 16 * MO;
+    constexpr int OTMAX = 4 * MO;                 // k-steps that cover OP rows
+    constexpr int HP16 = 16 * MA;                 // hidden rows padded to whole 16-row tiles
+    // per-wave staging for the transposed operand reads of the weight-gradient tiles
+    __shared__ float s_go[4][OP * kLdsPad];
+    __shared__ float s_a[4][HP16 * kLdsPad];
+    __shared__ float s_dp[4][HP16 * kLdsPad];
+    __shared__ float s_r[4][HP16 * kLdsPad];
     __shared__ float s_part[4];
+
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
     const int g = lane >> 4, n = lane & 15;
+    const int OT = (a.H + 3) / 4;
+    float *go_l = s_go[wv], *a_l = s_a[wv], *dp_l = s_dp[wv], *r_l = s_r[wv];
+    for (int i = lane; i < OP * kLdsPad; i += 64) go_l[i] = 0.0f;
+    for (int i = lane; i < HP16 * kLdsPad; i += 64) { a_l[i] = 0.0f; dp_l[i] = 0.0f; r_l[i] = 0.0f; }
 
-    float wa[MA][HT], wo[MO][HT];
+    float wa[MA][HT], wo[MO][HT], woT[MA][OTMAX], waT[MA][HT];
     f32x4 ba[MA], bo[MO];
 #pragma unroll
     for (int ma = 0; ma < MA; ++ma) {
 #pragma unroll
-        for (int q = 0; q < HT; ++q) wa[ma][q] = a.WaF[(ma * HT + q) * 64 + lane];
+        for (int q = 0; q < HT; ++q) {
+            wa[ma][q] = a.WaF[(ma * HT + q) * 64 + lane];
+            waT[ma][q] = a.WaT[(ma * HT + q) * 64 + lane];
+        }
+#pragma unroll
+        for (int ks = 0; ks < OTMAX; ++ks) woT[ma][ks] = ks < OT ? a.WoT[(ma * OT + ks) * 64 + lane] : 0.0f;
         const float4 v = *reinterpret_cast<const float4 *>(a.baF + (ma * 4 + g) * 4);
         ba[ma] = f32x4{v.x, v.y, v.z, v.w};
     }
@@ -55,7 +83,18 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
         const float4 v = *reinterpret_cast<const float4 *>(a.boF + (mo * 4 + g) * 4);
         bo[mo] = f32x4{v.x, v.y, v.z, v.w};
     }
+    f32x4 dWo[MO * MA], dWa[MA * MA];
+#pragma unroll
+    for (int i = 0; i < MO * MA; ++i) dWo[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < MA * MA; ++i) dWa[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float dbo[OTMAX], dba[4 * MA];
+#pragma unroll
+    for (int i = 0; i < OTMAX; ++i) dbo[i] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4 * MA; ++i) dba[i] = 0.0f;
 
+    const float inv_n = a.sc->inv_n_pin;
     float loss = 0.0f;
     // Tiles are numbered p * NB + (series tile); a wave takes every stride-th one and keeps (p, series
     // tile) by increments.  All of it is wave-uniform, so tile bases live on the scalar unit and the
@@ -67,7 +106,7 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
     // operands of one tile; those of the next tile are requested before this one is computed
     struct Ops {
         float br[HT];
-        float z[4 * MO], seas[4 * MO];
+        float z[OTMAX], seas[OTMAX];   // row 4*ks + g
         float ut;
         int len;
     };
@@ -82,17 +121,17 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
         o.ut = (a.u + (size_t)t * a.Bp + bt * 16)[n];
         const float *zt = a.Z + (size_t)tile * a.orows * 16;
 #pragma unroll
-        for (int mo = 0; mo < MO; ++mo)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = 16 * mo + 4 * g + r;
-                o.z[4 * mo + r] = zt[(j < a.orows ? j : a.orows - 1) * 16 + n];
-                const int tj = t + 1 + j < a.T ? t + 1 + j : a.T - 1;
-                float sv = 1.0f;
+        for (int ks = 0; ks < OTMAX; ++ks) {
+            const int j = 4 * ks + g;
+            o.z[ks] = zt[(j < a.orows ? j : a.orows - 1) * 16 + n];
+            const int tj = t + 1 + j < a.T ? t + 1 + j : a.T - 1;
+            float sv = 1.0f;
+            if (a.forecasts) {
                 if (a.n_seas >= 1) sv = (a.S1 + bt * 16)[tj * a.Bp + n];
                 if (a.n_seas >= 2) sv *= (a.S2 + bt * 16)[tj * a.Bp + n];
-                o.seas[4 * mo + r] = sv;
             }
+            o.seas[ks] = sv;
+        }
     };
     auto advance = [&](int &tile, int &p, int &bt) {
         tile += stride; p += step_p; bt += step_bt;
@@ -114,6 +153,7 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
         if (b >= a.B) len = 0;
         const bool valid = p < len - a.I - a.H + 1;
 
+        // ---- forward: tanh layer, linear layer
         f32x4 acc[MA];
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma) acc[ma] = ba[ma];
@@ -125,11 +165,7 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int q = 4 * ma + r;
-                av[q] = tanh_f(acc[ma][r]);
-                if (q < HT) (a.A + (size_t)tile * HT * 64 + q * 64)[lane] = av[q];
-            }
+            for (int r = 0; r < 4; ++r) av[4 * ma + r] = (4 * ma + r < HT) ? tanh_f(acc[ma][r]) : 0.0f;
         f32x4 oc[MO];
 #pragma unroll
         for (int mo = 0; mo < MO; ++mo) oc[mo] = bo[mo];
@@ -138,150 +174,31 @@ __global__ void __launch_bounds__(256) head_forward_kernel(HeadFwdArgs a)
 #pragma unroll
             for (int mo = 0; mo < MO; ++mo) oc[mo] = mfma16(wo[mo][q], av[q], oc[mo]);
 
-#pragma unroll
-        for (int mo = 0; mo < MO; ++mo)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = 16 * mo + 4 * g + r;      // 0-based step of the horizon
-                const float o = oc[mo][r];
-                if (j < a.orows) (a.O + (size_t)tile * a.orows * 16)[j * 16 + n] = o;
-                if (j < a.H) {
-                    if (valid) {
-                        const float d = cur.z[4 * mo + r] - o;
-                        loss += d >= 0.0f ? a.tau * d : (a.tau - 1.0f) * d;
-                    }
-                    if (a.forecasts && b < a.B) {
-                        // Eq. (5): exp(output) * level * seasonal factors of the target time
-                        const float f = valid ? __expf(o + cur.ut) * cur.seas[4 * mo + r] : 0.0f;
-                        (a.forecasts + ((size_t)p * a.B + bt * 16) * a.H)[n * a.H + j] = f;
-                    }
-                }
-            }
-        cur = nxt;
-    }
-    const float tot = wave_sum(loss);
-    if (lane == 0) s_part[wv] = tot;
-    __syncthreads();
-    if (threadIdx.x == 0) a.loss_partial[blockIdx.x] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
-}
-
-struct HeadBwdArgs {
-    const float *WoT, *WaT;
-    const float *R, *A, *O, *Z;
-    const int32_t *lengths;
-    const Scalars *sc;
-    float *gO;              // TL(OP): dL/d(output); the target's gradient is its negative
-    float *gTop;            // TL(HP): dL/d(top block output)
-    float *partial;         // [n_waves][stride]
-    int P, NB, B, T, I, H, stride;
-    int orows;              // rows of the Z, O and gO tiles: 4 * ceil(H / 4)
-    float tau;
-};
-
-template <int HT, int MO>
-__global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
-{
-    constexpr int MA = (HT + 3) / 4;
-    constexpr int OP = 16 * MO;
-    constexpr int OTMAX = 4 * MO;                 // k-steps that cover OP rows
-    constexpr int HP16 = 16 * MA;                 // hidden rows padded to whole 16-row tiles
-    // per-wave staging for the transposed operand reads of the weight-gradient tiles
-    __shared__ float s_go[4][OP * kLdsPad];
-    __shared__ float s_a[4][HP16 * kLdsPad];
-    __shared__ float s_dp[4][HP16 * kLdsPad];
-    __shared__ float s_r[4][HP16 * kLdsPad];
-
-    const int lane = threadIdx.x & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
-    const int g = lane >> 4, n = lane & 15;
-    const int OT = (a.H + 3) / 4;
-    float *go_l = s_go[wv], *a_l = s_a[wv], *dp_l = s_dp[wv], *r_l = s_r[wv];
-    for (int i = lane; i < OP * kLdsPad; i += 64) go_l[i] = 0.0f;
-    for (int i = lane; i < HP16 * kLdsPad; i += 64) { a_l[i] = 0.0f; dp_l[i] = 0.0f; r_l[i] = 0.0f; }
-
-    float woT[MA][OTMAX], waT[MA][HT];
-#pragma unroll
-    for (int ma = 0; ma < MA; ++ma) {
-#pragma unroll
-        for (int ks = 0; ks < OTMAX; ++ks) woT[ma][ks] = ks < OT ? a.WoT[(ma * OT + ks) * 64 + lane] : 0.0f;
-#pragma unroll
-        for (int q = 0; q < HT; ++q) waT[ma][q] = a.WaT[(ma * HT + q) * 64 + lane];
-    }
-    f32x4 dWo[MO * MA], dWa[MA * MA];
-#pragma unroll
-    for (int i = 0; i < MO * MA; ++i) dWo[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < MA * MA; ++i) dWa[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float dbo[OTMAX], dba[4 * MA];
-#pragma unroll
-    for (int i = 0; i < OTMAX; ++i) dbo[i] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 4 * MA; ++i) dba[i] = 0.0f;
-
-    const float inv_n = a.sc->inv_n_pin;
-    // wave-uniform tile bookkeeping as in the forward kernel
-    const int n_tiles = a.P * a.NB;
-    const int stride = gridDim.x * 4;
-    const int step_p = stride / a.NB, step_bt = stride % a.NB;
-
-    // operands of one tile; those of the next tile are requested before this one is computed
-    struct Ops {
-        float d[OTMAX];          // target minus output, row 4*ks + g
-        float av[4 * MA], rv[4 * MA];
-        int len;
-    };
-    auto load_ops = [&](int tile, int bt, Ops &o) {
-        if (tile >= n_tiles) { tile = n_tiles - 1; bt = a.NB - 1; }
-        const int b = bt * 16 + n;
-        o.len = a.lengths[b < a.B ? b : a.B - 1];
-        const float *zt = a.Z + (size_t)tile * a.orows * 16, *ot = a.O + (size_t)tile * a.orows * 16;
-#pragma unroll
-        for (int ks = 0; ks < OTMAX; ++ks) {
-            const int j = 4 * ks + g;
-            const int e = (j < a.orows ? j : a.orows - 1) * 16 + n;
-            o.d[ks] = zt[e] - ot[e];
-        }
-        const float *at = a.A + (size_t)tile * HT * 64, *rt = a.R + (size_t)tile * HT * 64;
-#pragma unroll
-        for (int q = 0; q < 4 * MA; ++q) {
-            const int qc = q < HT ? q : HT - 1;
-            o.av[q] = (at + qc * 64)[lane];
-            o.rv[q] = (rt + qc * 64)[lane];
-        }
-    };
-    auto advance = [&](int &tile, int &p, int &bt) {
-        tile += stride; p += step_p; bt += step_bt;
-        if (bt >= a.NB) { bt -= a.NB; ++p; }
-    };
-
-    Ops cur, nxt;
-    int tile = blockIdx.x * 4 + wv;
-    int p = tile / a.NB, bt = tile % a.NB;
-    if (tile < n_tiles) load_ops(tile, bt, cur);
-    for (; tile < n_tiles; advance(tile, p, bt)) {
-        {
-            int tn = tile, pn = p, btn = bt;
-            advance(tn, pn, btn);
-            load_ops(tn, btn, nxt);
-        }
-        const int b = bt * 16 + n;
-        int len = cur.len < 0 ? 0 : (cur.len > a.T ? a.T : cur.len);
-        if (b >= a.B) len = 0;
-        const bool valid = p < len - a.I - a.H + 1;
-
-        // gradient of the pinball loss, one row (horizon step) per k-step lane group
+        // ---- outputs, loss, forecasts and the gradient of the pinball loss; k-step ks holds rows 4ks..4ks+3
         float go[OTMAX];
+        float *ot = a.O + (size_t)tile * a.orows * 16, *got = a.gO + (size_t)tile * a.orows * 16;
 #pragma unroll
         for (int ks = 0; ks < OTMAX; ++ks) {
-            const int j = 4 * ks + g;
-            const float val = (valid && j < a.H) ? (cur.d[ks] >= 0.0f ? -a.tau : 1.0f - a.tau) * inv_n : 0.0f;
+            const int j = 4 * ks + g;               // 0-based step of the horizon
+            const float o = oc[ks >> 2][ks & 3];
+            const float d = cur.z[ks] - o;
+            const bool counted = valid && j < a.H;
+            if (counted) loss += d >= 0.0f ? a.tau * d : (a.tau - 1.0f) * d;
+            const float val = counted ? (d >= 0.0f ? -a.tau : 1.0f - a.tau) * inv_n : 0.0f;
             go[ks] = val;
-            if (j < a.orows) (a.gO + (size_t)tile * a.orows * 16)[j * 16 + n] = val;
+            if (j < a.orows) {
+                ot[j * 16 + n] = o;
+                got[j * 16 + n] = val;
+            }
+            if (a.forecasts && b < a.B && j < a.H) {
+                // Eq. (5): exp(output) * level * seasonal factors of the target time
+                const float f = valid ? __expf(o + cur.ut) * cur.seas[ks] : 0.0f;
+                (a.forecasts + ((size_t)p * a.B + bt * 16) * a.H)[n * a.H + j] = f;
+            }
             go_l[j * kLdsPad + n] = val;
             dbo[ks] += val;
         }
-        // dA = Wo^T gO (unit-tile order), through the tanh
-        f32x4 acc[MA];
+        // ---- reverse: dA = Wo^T gO (unit-tile order), through the tanh
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma) acc[ma] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -294,11 +211,11 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int q = 4 * ma + r;
-                const float av = q < HT ? cur.av[q] : 0.0f, rv = q < HT ? cur.rv[q] : 0.0f;
-                dp[q] = acc[ma][r] * (1.0f - av * av);
+                const float rv = q < HT ? cur.br[q < HT ? q : 0] : 0.0f;   // rows past HT are padding
+                dp[q] = acc[ma][r] * (1.0f - av[q] * av[q]);
                 dba[q] += dp[q];
                 const int row = 4 * q + g;
-                a_l[row * kLdsPad + n] = av;
+                a_l[row * kLdsPad + n] = av[q];
                 dp_l[row * kLdsPad + n] = dp[q];
                 r_l[row * kLdsPad + n] = rv;
             }
@@ -359,6 +276,11 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
         const float tot = group16_sum(dba[q]);
         if (n == 0 && q < HT) dst[4 * q + g] = tot;
     }
+
+    const float tot = wave_sum(loss);
+    if (lane == 0) s_part[wv] = tot;
+    __syncthreads();
+    if (threadIdx.x == 0) a.loss_partial[blockIdx.x] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
 }
 
 #define ESRNN_HEAD_SHAPES(X) \
@@ -367,36 +289,20 @@ __global__ void __launch_bounds__(256) head_backward_kernel(HeadBwdArgs a)
 
 }  // namespace
 
-hipError_t launch_head_forward(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st)
+hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st)
 {
     const HeadPack hp = head_pack_layout(pl);
-    const float *f = ws + pl.head_fwd_pack;
-    const int blocks = pl.head_fwd_blocks;
-    HeadFwdArgs a{f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z,
-                  ws + pl.u, ws + pl.S1, ws + pl.S2, lengths, ws + pl.A, ws + pl.O, forecasts, ws + pl.loss_partial,
-                  pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.OP, pl.cfg.tau};
-#define X(HT_, MO_)                                                      \
-    if (pl.HT == HT_ && pl.MO == MO_) {                                  \
-        head_forward_kernel<HT_, MO_><<<blocks, 256, 0, st>>>(a);        \
-        return hipGetLastError();                                        \
-    }
-    ESRNN_HEAD_SHAPES(X)
-#undef X
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_head_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st)
-{
-    const HeadPack hp = head_pack_layout(pl);
-    const float *bk = ws + pl.head_bwd_pack;
+    const float *f = ws + pl.head_fwd_pack, *bk = ws + pl.head_bwd_pack;
     const int blocks = pl.n_head_waves / 4;
-    HeadBwdArgs a{bk + hp.WoT, bk + hp.WaT, ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.A, ws + pl.O, ws + pl.Z,
-                  lengths, reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.gO, ws + pl.gTop,
-                  ws + pl.head_dw_partial, pl.P, pl.NB, pl.B, pl.T, pl.I, pl.H, pl.head_dw_stride, pl.OP, pl.cfg.tau};
-#define X(HT_, MO_)                                                      \
-    if (pl.HT == HT_ && pl.MO == MO_) {                                  \
-        head_backward_kernel<HT_, MO_><<<blocks, 256, 0, st>>>(a);       \
-        return hipGetLastError();                                        \
+    HeadArgs a{f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, bk + hp.WoT, bk + hp.WaT,
+               ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z, ws + pl.u, ws + pl.S1, ws + pl.S2, lengths,
+               reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.O, forecasts, ws + pl.loss_partial,
+               ws + pl.gO, ws + pl.gTop, ws + pl.head_dw_partial,
+               pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.head_dw_stride, pl.OP, pl.cfg.tau};
+#define X(HT_, MO_)                                              \
+    if (pl.HT == HT_ && pl.MO == MO_) {                          \
+        head_kernel<HT_, MO_><<<blocks, 256, 0, st>>>(a);        \
+        return hipGetLastError();                                \
     }
     ESRNN_HEAD_SHAPES(X)
 #undef X

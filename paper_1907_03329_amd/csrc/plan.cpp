@@ -134,11 +134,11 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     const size_t TB = (size_t)pl.T * pl.Bp;
     const size_t PN = (size_t)pl.P * pl.NB;
     const size_t tileH = (size_t)pl.HT * 64;         // floats of one (p, series-tile) block with HP rows
-    // forward: enough waves to hide memory latency; backward: fewer, every wave leaves a partial block
+    // output stage: every wave leaves a block of weight-gradient partials, so no more waves than fill the chip
     const size_t n_tiles = PN;
-    const int head_blocks = (int)std::min<size_t>((n_tiles + 3) / 4, 512);
-    pl.head_fwd_blocks = head_blocks;
-    pl.n_head_waves = 4 * (int)std::min<size_t>((n_tiles + 3) / 4, 256);
+    const int head_blocks = (int)std::min<size_t>((n_tiles + 3) / 4, 256);
+    pl.head_blocks = head_blocks;
+    pl.n_head_waves = 4 * head_blocks;
     pl.es_blocks = ceil_div(pl.Bp, 64);
     // first everything the smoothing and window stages touch (their own entry points need only this prefix)
     pl.scalars = ws.take(64);
@@ -152,7 +152,6 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.gX = ws.take(PN * (size_t)pl.IT * 64);
     pl.gO = ws.take(PN * (size_t)pl.OP * 16);
     pl.es_window_floats = ws.at;
-    pl.A = ws.take(PN * tileH);
     pl.O = ws.take(PN * (size_t)pl.OP * 16);
     pl.gTop = ws.take(PN * tileH);
     for (int l = 0; l < L; ++l) {

@@ -83,7 +83,6 @@ def check_forward(cfg, inp, step, f, stages=True):
             chk(f"h{l}", step.buffer("hid", l).cpu().numpy(), f.h[l].transpose(1, 0, 2), wm, TOL_FWD)
         for k in range(len(cfg.blocks)):
             chk(f"block{k}", step.buffer("block_out", k).cpu().numpy(), f.blk[k].transpose(1, 0, 2), wm, TOL_FWD)
-        chk("A", step.buffer("A").cpu().numpy(), f.a.transpose(1, 0, 2), wm, TOL_FWD)
         chk("O", step.buffer("O").cpu().numpy(), f.o.transpose(1, 0, 2), wm, TOL_FWD)
     chk("loss", step.loss.cpu().numpy(), np.array([f.loss]), None, TOL_FWD)
     fc = step.forecasts.cpu().numpy()
