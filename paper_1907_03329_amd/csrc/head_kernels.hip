@@ -53,6 +53,18 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
     __shared__ float s_dp[4][HP16 * kLdsPad];
     __shared__ float s_r[4][HP16 * kLdsPad];
     __shared__ float s_part[4];
+    // The transposed weight operands stay in registers where all four operand sets fit; for the larger
+    // shapes they are read from LDS, one copy per workgroup (the register file holds the forward operands,
+    // the weight-gradient accumulators and two tiles of inputs).
+    constexpr bool kTLds = (HT >= 13 && MO >= 2) || MO >= 4;
+    // ... and the forward operands too for the largest shapes, as long as the workgroup stays within
+    // 128 KB of LDS (this build keeps every kernel below that)
+    constexpr int kStagingFloats = 4 * (OP + 3 * HP16) * kLdsPad + 4;
+    constexpr int kTFloats = MA * (OTMAX + HT) * 64, kFFloats = (MA + MO) * HT * 64;
+    constexpr bool kFLds = HT >= 13 && MO >= 3 && (kStagingFloats + kTFloats + kFFloats) * 4 <= 128 * 1024;
+    static_assert((kStagingFloats + (kTLds ? kTFloats : 0)) * 4 <= 128 * 1024, "LDS budget of the output-stage kernel");
+    __shared__ float s_wT[kTLds ? MA * (OTMAX + HT) * 64 : 1];
+    __shared__ float s_wF[kFLds ? (MA + MO) * HT * 64 : 1];
 
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
@@ -62,24 +74,49 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
     for (int i = lane; i < OP * kLdsPad; i += 64) go_l[i] = 0.0f;
     for (int i = lane; i < HP16 * kLdsPad; i += 64) { a_l[i] = 0.0f; dp_l[i] = 0.0f; r_l[i] = 0.0f; }
 
-    float wa[MA][HT], wo[MO][HT], woT[MA][OTMAX], waT[MA][HT];
+    float wa[kFLds ? 1 : MA][kFLds ? 1 : HT], wo[kFLds ? 1 : MO][kFLds ? 1 : HT];
+    float woT[kTLds ? 1 : MA][kTLds ? 1 : OTMAX], waT[kTLds ? 1 : MA][kTLds ? 1 : HT];
     f32x4 ba[MA], bo[MO];
 #pragma unroll
     for (int ma = 0; ma < MA; ++ma) {
 #pragma unroll
         for (int q = 0; q < HT; ++q) {
-            wa[ma][q] = a.WaF[(ma * HT + q) * 64 + lane];
-            waT[ma][q] = a.WaT[(ma * HT + q) * 64 + lane];
+            if (!kFLds) wa[ma][q] = a.WaF[(ma * HT + q) * 64 + lane];
+            if (!kTLds) waT[ma][q] = a.WaT[(ma * HT + q) * 64 + lane];
         }
+        if (!kTLds) {
 #pragma unroll
-        for (int ks = 0; ks < OTMAX; ++ks) woT[ma][ks] = ks < OT ? a.WoT[(ma * OT + ks) * 64 + lane] : 0.0f;
+            for (int ks = 0; ks < OTMAX; ++ks) woT[ma][ks] = ks < OT ? a.WoT[(ma * OT + ks) * 64 + lane] : 0.0f;
+        }
         const float4 v = *reinterpret_cast<const float4 *>(a.baF + (ma * 4 + g) * 4);
         ba[ma] = f32x4{v.x, v.y, v.z, v.w};
     }
+    if (kTLds) {
+        // [ma][OTMAX][64] then [ma][HT][64]
+        for (int i = threadIdx.x; i < MA * OTMAX * 64; i += 256) {
+            const int l = i & 63, ks = (i >> 6) % OTMAX, ma = (i >> 6) / OTMAX;
+            s_wT[i] = ks < OT ? a.WoT[(ma * OT + ks) * 64 + l] : 0.0f;
+        }
+        for (int i = threadIdx.x; i < MA * HT * 64; i += 256) s_wT[MA * OTMAX * 64 + i] = a.WaT[i];
+        if (kFLds) {
+            for (int i = threadIdx.x; i < MA * HT * 64; i += 256) s_wF[i] = a.WaF[i];
+            for (int i = threadIdx.x; i < MO * HT * 64; i += 256) s_wF[MA * HT * 64 + i] = a.WoF[i];
+        }
+        __syncthreads();
+    }
+    auto wa_op = [&](int ma, int q) { return kFLds ? s_wF[(ma * HT + q) * 64 + lane] : wa[kFLds ? 0 : ma][kFLds ? 0 : q]; };
+    auto wo_op = [&](int mo, int q) {
+        return kFLds ? s_wF[((MA + mo) * HT + q) * 64 + lane] : wo[kFLds ? 0 : mo][kFLds ? 0 : q];
+    };
+    auto woT_op = [&](int ma, int ks) { return kTLds ? s_wT[(ma * OTMAX + ks) * 64 + lane] : woT[kTLds ? 0 : ma][kTLds ? 0 : ks]; };
+    auto waT_op = [&](int ma, int q) {
+        return kTLds ? s_wT[(MA * OTMAX + ma * HT + q) * 64 + lane] : waT[kTLds ? 0 : ma][kTLds ? 0 : q];
+    };
 #pragma unroll
     for (int mo = 0; mo < MO; ++mo) {
 #pragma unroll
-        for (int q = 0; q < HT; ++q) wo[mo][q] = a.WoF[(mo * HT + q) * 64 + lane];
+        for (int q = 0; q < HT; ++q)
+            if (!kFLds) wo[mo][q] = a.WoF[(mo * HT + q) * 64 + lane];
         const float4 v = *reinterpret_cast<const float4 *>(a.boF + (mo * 4 + g) * 4);
         bo[mo] = f32x4{v.x, v.y, v.z, v.w};
     }
@@ -160,7 +197,7 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
 #pragma unroll
         for (int q = 0; q < HT; ++q)
 #pragma unroll
-            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(wa[ma][q], cur.br[q], acc[ma]);
+            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(wa_op(ma, q), cur.br[q], acc[ma]);
         float av[4 * MA];
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma)
@@ -172,7 +209,7 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
 #pragma unroll
         for (int q = 0; q < HT; ++q)
 #pragma unroll
-            for (int mo = 0; mo < MO; ++mo) oc[mo] = mfma16(wo[mo][q], av[q], oc[mo]);
+            for (int mo = 0; mo < MO; ++mo) oc[mo] = mfma16(wo_op(mo, q), av[q], oc[mo]);
 
         // ---- outputs, loss, forecasts and the gradient of the pinball loss; k-step ks holds rows 4ks..4ks+3
         float go[OTMAX];
@@ -204,7 +241,7 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
 #pragma unroll
         for (int ks = 0; ks < OTMAX; ++ks)
 #pragma unroll
-            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(woT[ma][ks], go[ks], acc[ma]);
+            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(woT_op(ma, ks), go[ks], acc[ma]);
         float dp[4 * MA];
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma)
@@ -225,7 +262,7 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
 #pragma unroll
         for (int q = 0; q < HT; ++q)
 #pragma unroll
-            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(waT[ma][q], dp[q], acc[ma]);
+            for (int ma = 0; ma < MA; ++ma) acc[ma] = mfma16(waT_op(ma, q), dp[q], acc[ma]);
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma)
 #pragma unroll

@@ -192,6 +192,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     constexpr int MTW = (HT + W - 1) / W;            // unit tiles per wave
     constexpr int QXW = (KXT + W - 1) / W;           // input unit tiles finalised per wave
     constexpr int NT = 64 * W;
+    constexpr bool kDxLate = (KXT % W) != 0 && HT > 8;   // measured: at HT = 8 the early placement is faster either way
     constexpr int DA_ROWS = 16 * W * MTW;            // includes dummy rows for tiles past HT
     constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
     constexpr int XH_ROWS = (16 * MB > 16 * XH_PER_THREAD) ? 16 * MB : 16 * XH_PER_THREAD;
@@ -199,6 +200,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     __shared__ float da_lds[DA_ROWS * kLdsPad];      // [mt][4*gate + unit][series]
     __shared__ float xh_lds[XH_ROWS * kLdsPad];      // [row of x ; h][series]; rows past 4*KT are scratch
     __shared__ float part_lds[W][MB * 4][64];        // partial d[x ; h] of every wave
+    static_assert((DA_ROWS * kLdsPad + XH_ROWS * kLdsPad + W * MB * 4 * 64) * 4 <= 128 * 1024, "LDS budget of the reverse kernel");
 
     const int lane = threadIdx.x & 63, bt = blockIdx.x;
     const int s = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
@@ -339,9 +341,13 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
                 ar[j][ks] = da_lds[(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
         lds_barrier();              // everything of position p has been read
     };
-    // The input gradient of position p leaves after the elementwise work of the next position and
-    // ahead of the next operand requests.  Memory operations complete in order: a store issued between
-    // a request and its use would have to complete before that use; here it has a whole position.
+    // Memory operations complete in order, and the compiler's wait for the operands requested one
+    // position ahead counts the stores issued since with the smallest number any wave issues.  When
+    // the waves own different numbers of input tiles (KXT not a multiple of the wave count), a store
+    // placed between request and use would therefore have to complete before that use on the waves
+    // with one tile more; the input gradient then leaves after the elementwise work of the next
+    // position, ahead of the next requests (kDxLate).  With equal counts the wait is exact, and the
+    // stores go out at once, which frees their registers.
     auto store_dx = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
 #pragma unroll
@@ -370,6 +376,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 
         for (int p = p_last; p >= a.d; p -= a.d) {
             finish(p);
+            if (!kDxLate) store_dx(p);
             // gate gradients of position p - d (elementwise) interleaved with the dW MFMAs of p
             const bool has_prev = p >= 2 * a.d;
             store_xh(has_prev);
@@ -379,7 +386,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
                 dw_row(j);
             }
             step_a_tile(MTW - 1, has_prev);
-            store_dx(p);
+            if (kDxLate) store_dx(p);
             fetch(max(p - 2 * a.d, r0));
             if (last_row_valid) dw_row(MTW - 1);
             step_b();

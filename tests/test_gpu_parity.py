@@ -80,6 +80,19 @@ def test_four_blocks():
     report(gc.run_and_check(cfg, seed=21, ragged=True))
 
 
+def test_maximum_sizes():
+    # hidden, input window and horizon at the limits of the library (largest kernel shapes; the output
+    # stage reads all its weight operands from LDS)
+    cfg = small("max_sizes", hidden=64, I=64, H=64, T=140, B=20, blocks=((1, 2), (3,)), m1=12)
+    report(gc.run_and_check(cfg, seed=22, ragged=True))
+
+
+def test_wide_horizon_medium_hidden():
+    # hidden 50 with a 40-step horizon: output stage with its transposed operands in LDS
+    cfg = small("h50_H40", hidden=50, I=12, H=40, T=100, B=35, blocks=((1, 3), (6,)), m1=12)
+    report(gc.run_and_check(cfg, seed=23, ragged=True))
+
+
 def test_input_window_padded_to_hidden_tiles():
     # I = 13 has no dedicated kernel shape with hidden 30: the input is padded to the hidden tile count
     cfg = small("padded_input", hidden=30, I=13, H=3, T=48)
