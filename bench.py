@@ -28,9 +28,9 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # (FETCH x 2.0, WRITE x 1.0): profiles/hbm_traffic_quarterly_B4096.txt.  Valid for that workload and batch only.
 MEASURED_TRAFFIC_BYTES = {
     ("quarterly", 4096): {
-        "lstm_forward_l0": 244e6, "lstm_forward_l1": 309e6, "lstm_forward_l2": 309e6, "lstm_forward_l3": 309e6,
-        "lstm_backward_l0": 296e6, "lstm_backward_l1": 406e6, "lstm_backward_l2": 406e6, "lstm_backward_l3": 406e6,
-        "window_forward": 22.2e6, "window_backward": 15.6e6,
+        "lstm_forward_l0": 244e6, "lstm_forward_l1": 308e6, "lstm_forward_l2": 308e6, "lstm_forward_l3": 308e6,
+        "lstm_backward_l0": 296e6, "lstm_backward_l1": 397e6, "lstm_backward_l2": 397e6, "lstm_backward_l3": 397e6,
+        "head_forward_backward": 127e6, "window_forward": 14.2e6, "window_backward": 15.6e6,
         "es_forward": 6.2e6, "es_backward": 6.1e6,
     },
 }

@@ -1,7 +1,6 @@
 // Host-side launch plan: validates a configuration, lays out the workspace and
 // the packed operand blocks.  No device work happens here.
 #include <algorithm>
-#include <cstdlib>
 #include <cstring>
 
 #include "esrnn_internal.h"
@@ -166,8 +165,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         lp.hid = ws.take(PN * tileH);
         // enough workgroups to put several on every compute unit, without more
         // weight-gradient partials than the reduction can read cheaply
-        int max_chains = std::max(1, ceil_div(512, pl.NB));
-        if (const char *e = std::getenv("ESRNN_MAX_CHAINS")) max_chains = std::max(1, std::atoi(e));
+        const int max_chains = std::max(1, ceil_div(512, pl.NB));
         lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
         lp.dw_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * MB * 256);
         lp.db_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * 16);
