@@ -608,3 +608,125 @@ int eso_backward(const eso_config *cfg, const double *y, const int32_t *lengths,
     free(gw_all);
     return 0;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Out-of-sample forecast, one series at a time                               */
+/* ------------------------------------------------------------------------- */
+
+/* Section 3.4 ("testing of the network") with Eq. (4) and (5): the smoothing
+ * recursions run over the whole series; every position with a complete input
+ * window goes through the network (no targets are needed); the output at the
+ * last position, whose window ends at the last observation t = len-1, is
+ * de-normalised with the level l_t and re-seasonalised.  The seasonal factor
+ * of forecast step h is the one Eq. (4) names, s_{t-m+h_m^+} with
+ * h_m^+ = ((h-1) mod m) + 1: the last m factors the recursion has produced,
+ * repeated with period m.  In the indexing used here (S[t] is the factor that
+ * applies at time t; Eq. (3) at step t produces S[t+m]) that is
+ * S[t + ((h-1) mod m) + 1].  Written out on its own arrays, sized by the
+ * series, so that it can be compared with the training pass rather than
+ * derived from it. */
+int eso_predict(const eso_config *cfg, const double *y, const int32_t *lengths,
+                const double *es_params, const double *weights, double *forecasts)
+{
+    plan_t pl;
+    if (make_plan(cfg, &pl)) return 1;
+    const int B = cfg->B, I = cfg->I, H = cfg->H, h = cfg->hidden;
+    const int m1 = cfg->n_seas >= 1 ? cfg->m1 : 0, m2 = cfg->n_seas >= 2 ? cfg->m2 : 0;
+    const int logit = (cfg->param_space == 1);
+    for (int b = 0; b < B; ++b)
+        if (lengths[b] < I || lengths[b] > cfg->T) return 2;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int len = lengths[b];
+        const int Pp = len - I + 1;                 /* positions with a complete input window */
+        const int ext = len + (m1 > m2 ? m1 : m2);  /* factors exist up to index len-1+m */
+        double *l = (double *)malloc(sizeof(double) * len);
+        double *S1 = (double *)malloc(sizeof(double) * (ext + 1));
+        double *S2 = (double *)malloc(sizeof(double) * (ext + 1));
+        double *cur = (double *)malloc(sizeof(double) * Pp * (I > h ? I : h));   /* input of the current layer */
+        double *blk_in = (double *)malloc(sizeof(double) * Pp * h);              /* input of the current block */
+        double *hs = (double *)malloc(sizeof(double) * Pp * h);
+        double *cs = (double *)malloc(sizeof(double) * Pp * h);
+        double *g = (double *)malloc(sizeof(double) * 4 * h);
+        double *a = (double *)malloc(sizeof(double) * h);
+        if (!l || !S1 || !S2 || !cur || !blk_in || !hs || !cs || !g || !a) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+            double alpha = es_params[b], g1 = 0.0, g2 = 0.0;
+            if (logit) alpha = sigmoid(alpha);
+            if (m1) { g1 = es_params[(int64_t)pl.row_gamma1 * B + b]; if (logit) g1 = sigmoid(g1); }
+            if (m2) { g2 = es_params[(int64_t)pl.row_gamma2 * B + b]; if (logit) g2 = sigmoid(g2); }
+            for (int t = 0; t <= ext; ++t) { S1[t] = 1.0; S2[t] = 1.0; }
+            for (int k = 0; k < m1; ++k) { double v0 = es_params[(int64_t)(pl.row_s1 + k) * B + b]; S1[k] = logit ? exp(v0) : v0; }
+            for (int k = 0; k < m2; ++k) { double v0 = es_params[(int64_t)(pl.row_s2 + k) * B + b]; S2[k] = logit ? exp(v0) : v0; }
+            /* Eq. (1), (3); state before the first observation as in the training pass */
+            l[0] = y[b] / (S1[0] * S2[0]);
+            if (m1) S1[m1] = S1[0];
+            if (m2) S2[m2] = S2[0];
+            for (int t = 1; t < len; ++t) {
+                const double yt = y[(int64_t)t * B + b];
+                l[t] = alpha * (yt / (S1[t] * S2[t])) + (1.0 - alpha) * l[t - 1];
+                if (m1) S1[t + m1] = g1 * yt / (l[t - 1] * S2[t]) + (1.0 - g1) * S1[t];
+                if (m2) S2[t + m2] = g2 * yt / (l[t - 1] * S1[t]) + (1.0 - g2) * S2[t];
+            }
+            /* Eq. (6) inputs: ln( y / (level at the window end * own seasonal factor) ) */
+            for (int p = 0; p < Pp; ++p) {
+                const int t = p + I - 1;
+                for (int i = 0; i < I; ++i)
+                    cur[p * I + i] = log(y[(int64_t)(p + i) * B + b] / (l[t] * S1[p + i] * S2[p + i]));
+            }
+            /* Section 3.2: dilated LSTM layers, residual around every block but the first */
+            int width = I;
+            for (int layer = 0; layer < pl.L; ++layer) {
+                const int in = pl.in_dim[layer], d = pl.dil[layer];
+                const double *W = weights + pl.W_off[layer], *bias = weights + pl.b_off[layer];
+                if (pl.first_in_block[layer] && layer > 0) memcpy(blk_in, cur, sizeof(double) * Pp * h);
+                for (int p = 0; p < Pp; ++p) {
+                    for (int r = 0; r < 4 * h; ++r) {
+                        double acc = bias[r];
+                        for (int q = 0; q < in; ++q) acc += W[(int64_t)r * (in + h) + q] * cur[p * width + q];
+                        if (p - d >= 0)
+                            for (int q = 0; q < h; ++q) acc += W[(int64_t)r * (in + h) + in + q] * hs[(p - d) * h + q];
+                        g[r] = acc;
+                    }
+                    for (int j = 0; j < h; ++j) {
+                        const double gi = sigmoid(g[j]), gf = sigmoid(g[h + j]), gg = tanh(g[2 * h + j]), go = sigmoid(g[3 * h + j]);
+                        const double cn = gf * (p - d >= 0 ? cs[(p - d) * h + j] : 0.0) + gi * gg;
+                        cs[p * h + j] = cn;
+                        hs[p * h + j] = go * tanh(cn);
+                    }
+                }
+                /* the layer's hidden sequence is the next layer's input; a block past the first adds its input */
+                for (int p = 0; p < Pp; ++p)
+                    for (int j = 0; j < h; ++j) {
+                        double val = hs[p * h + j];
+                        if (pl.last_in_block[layer] && pl.block_of[layer] >= 1) val += blk_in[p * h + j];
+                        cur[p * h + j] = val;
+                    }
+                width = h;
+            }
+            /* Section 3.4 at the last position; Eq. (5) with the factors of Eq. (4) */
+            const double *Wa = weights + pl.Wa_off, *ba = weights + pl.ba_off, *Wo = weights + pl.Wo_off, *bo = weights + pl.bo_off;
+            const double *R = cur + (int64_t)(Pp - 1) * h;
+            const int t = len - 1;
+            for (int j = 0; j < h; ++j) {
+                double acc = ba[j];
+                for (int q = 0; q < h; ++q) acc += Wa[(int64_t)j * h + q] * R[q];
+                a[j] = tanh(acc);
+            }
+            for (int hh = 1; hh <= H; ++hh) {
+                double o = bo[hh - 1];
+                for (int q = 0; q < h; ++q) o += Wo[(int64_t)(hh - 1) * h + q] * a[q];
+                double seas = 1.0;
+                if (m1) seas *= S1[t + ((hh - 1) % m1) + 1];
+                if (m2) seas *= S2[t + ((hh - 1) % m2) + 1];
+                forecasts[(int64_t)b * H + (hh - 1)] = exp(o) * l[t] * seas;
+            }
+        }
+        free(l); free(S1); free(S2); free(cur); free(blk_in); free(hs); free(cs); free(g); free(a);
+    }
+    return fail ? 3 : 0;
+}
+

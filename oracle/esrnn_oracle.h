@@ -21,6 +21,8 @@
  *   - Section 3.3: per-series smoothing coefficients and initial seasonality
  *     are trained jointly with the network, hence the reverse sweep through
  *     the smoothing recursions.
+ *   - Section 3.4 with Eq. (4): out-of-sample forecasts from the last input
+ *     window, seasonal factors repeated with their period (eso_predict).
  *
  * Readings taken where the paper is silent are stated next to the code that
  * takes them.  Pins: closed forms, invariants, a library LSTM, brute force and
@@ -98,6 +100,12 @@ int eso_backward(const eso_config *cfg, const double *y, const int32_t *lengths,
                  const double *es_params, const double *weights,
                  const eso_tape *tape, eso_adjoint *adj,
                  double *grad_es_params, double *grad_weights);
+
+/* Out-of-sample forecasts of the H steps after each series' last observation
+ * (Section 3.4, Eq. (4), (5)): forecasts [B][H], original scale.  Needs
+ * lengths[b] >= I; targets play no part.  Returns 0 on success. */
+int eso_predict(const eso_config *cfg, const double *y, const int32_t *lengths,
+                const double *es_params, const double *weights, double *forecasts);
 
 #ifdef __cplusplus
 }

@@ -58,6 +58,7 @@ def lib():
         _lib.eso_max_threads.restype = C.c_int
         _lib.eso_forward.restype = C.c_int
         _lib.eso_backward.restype = C.c_int
+        _lib.eso_predict.restype = C.c_int
     return _lib
 
 
@@ -167,3 +168,48 @@ def backward(cfg, fwd, want_adjoints=True):
 
 def loss_only(cfg, y, lengths, es_params, weights, **kw) -> float:
     return forward(cfg, y, lengths, es_params, weights, want_forecasts=False, **kw).loss
+
+
+def predict(cfg, y, lengths, es_params, weights):
+    """Out-of-sample forecasts [B, H] of the H steps after each series' last
+    observation (Section 3.4, Eq. (4), (5)); rows of y past a length are not read."""
+    L_ = lib()
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    es_params = np.ascontiguousarray(es_params, dtype=np.float64)
+    weights = np.ascontiguousarray(weights, dtype=np.float64)
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    T, B = y.shape
+    assert T == cfg.T
+    cc = _c_config(cfg, B=B)
+    out = np.zeros((B, cfg.H))
+    rc = L_.eso_predict(C.byref(cc), _ptr(y), lengths.ctypes.data_as(C.POINTER(C.c_int32)),
+                        _ptr(es_params), _ptr(weights), _ptr(out))
+    if rc != 0:
+        raise ValueError(f"oracle predict failed with code {rc}")
+    return out
+
+
+def smape(forecasts, actuals):
+    """Symmetric mean absolute percentage error per series, in percent, as used
+    in the M4 competition (Section 3.5 names the metric): mean over the horizon
+    of 200 |a - f| / (|a| + |f|).  forecasts, actuals: [B, H]."""
+    f = np.asarray(forecasts, dtype=np.float64)
+    a = np.asarray(actuals, dtype=np.float64)
+    return np.mean(200.0 * np.abs(a - f) / (np.abs(a) + np.abs(f)), axis=1)
+
+
+def mase(forecasts, actuals, y, lengths, m):
+    """Mean absolute scaled error per series (M4 definition): mean absolute
+    forecast error divided by the in-sample mean absolute error of the seasonal
+    naive forecast with period m, mean over t = m .. len-1 of |y_t - y_{t-m}|.
+    y: [T, B] time-major, only rows below lengths[b] are read."""
+    f = np.asarray(forecasts, dtype=np.float64)
+    a = np.asarray(actuals, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    out = np.zeros(f.shape[0])
+    for b in range(f.shape[0]):
+        s = y[:int(lengths[b]), b]
+        scale = np.mean(np.abs(s[m:] - s[:-m]))
+        out[b] = np.mean(np.abs(a[b] - f[b])) / scale
+    return out
+
