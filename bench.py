@@ -117,6 +117,9 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--predict", action="store_true",
+                    help="time esrnn_predict (out-of-sample forecasts of every series, lengths T - H) instead of "
+                         "the training step; one JSON line, not the headline metric")
     ap.add_argument("--es-window-sweep", default="",
                     help="comma-separated batch sizes: time only the smoothing and window stages (forward and "
                          "adjoint) at each, one JSON line per size, instead of the training-step benchmark")
@@ -146,6 +149,30 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.predict:
+        import numpy as np
+        n = torch.from_numpy(np.full(cfg.B, cfg.T - cfg.H, dtype=np.int32)).cuda()
+        for _ in range(args.warmup):
+            out = step.predict(dev["y"], n, dev["es_params"], dev["weights"])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            out = step.predict(dev["y"], n, dev["es_params"], dev["weights"])
+        torch.cuda.synchronize()
+        el = (time.perf_counter() - t0) / args.steps
+        binding.esrnn_profile_enable(step.handle, True)
+        for _ in range(max(1, args.profile_steps)):
+            step.predict(dev["y"], n, dev["es_params"], dev["weights"])
+            binding.esrnn_profile_collect(step.handle)
+        stages = {name: round(tot / max(cnt, 1), 4) for name, tot, cnt in binding.esrnn_profile_read(step.handle) if cnt}
+        print(json.dumps({"metric": "out-of-sample forecast series/sec (H steps each)", "value": round(cfg.B / el, 1),
+                          "unit": "series/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": round(1e3 * el, 4), "higher_is_better": True, "dtype": "f32",
+                          "data": "synthetic", "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "H": cfg.H},
+                          "series_steps_per_s": round(cfg.B * (cfg.T - cfg.H) / el, 1), "stages_ms": stages,
+                          "mean_forecast": float(out.mean().item())}))
+        return
 
     def one_step():
         step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])

@@ -128,6 +128,36 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
                             float *grad_es_params, float *grad_weights, void *stream);
 
 /*
+ * Out-of-sample forecasts (Section 3.4 "testing of the network", Eq. (4), (5)):
+ * the H steps after each series' last observation, from the window of the last
+ * I observations, de-normalised with the last level and re-seasonalised with
+ * the last m factors of the recursion repeated with period m.
+ *
+ *   forecasts  [B][H], original scale.  A series with lengths[b] < I or
+ *              lengths[b] + H > T gets zeros: the pass runs on lengths extended
+ *              by H, so y needs H rows past every series to be forecast.  Those
+ *              rows are read; their values do not reach the forecasts.
+ *
+ * Inputs and workspace as for esrnn_forward.  The workspace afterwards holds the
+ * state of the extended problem: esrnn_backward must not follow (it returns
+ * ESRNN_ERR_ORDER).
+ */
+esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengths, const float *es_params,
+                           const float *weights, void *workspace, float *forecasts, void *stream);
+
+/*
+ * Accuracy per series of forecasts [B][H] against actual values [B][H], with the
+ * two metrics of the M4 competition that Section 3.5 names:
+ *   smape [B]  mean over the horizon of 200 |a - f| / (|a| + |f|)   (percent)
+ *   mase  [B]  mean |a - f| over the horizon, divided by the mean of
+ *              |y_t - y_{t-m}| over t = m .. lengths[b]-1 (in-sample seasonal
+ *              naive forecast; m = the seasonal period, 1 for none).
+ * y [T][B] and lengths as for esrnn_forward; lengths[b] > m is required.
+ */
+esrnn_status esrnn_forecast_metrics(esrnn_handle *h, const float *forecasts, const float *actuals, const float *y,
+                                    const int32_t *lengths, int32_t m, float *smape, float *mase, void *stream);
+
+/*
  * The smoothing and window stages on their own (Section 3.1 Eq. (1), (3), Section
  * 5.3 Eq. (6), and their adjoints), for callers that fit or inspect the
  * exponential-smoothing part without the network, and for measuring these

@@ -75,6 +75,10 @@ def load_library():
     lib.esrnn_es_window_backward.argtypes = [vp, fp, i32p, fp, vp, fp, vp]
     for fn in ("esrnn_es_window_workspace_bytes", "esrnn_es_window_forward", "esrnn_es_window_backward"):
         getattr(lib, fn).restype = C.c_int
+    lib.esrnn_predict.argtypes = [vp, fp, i32p, fp, fp, vp, fp, vp]
+    lib.esrnn_forecast_metrics.argtypes = [vp, fp, fp, fp, i32p, C.c_int32, fp, fp, vp]
+    for fn in ("esrnn_predict", "esrnn_forecast_metrics"):
+        getattr(lib, fn).restype = C.c_int
     lib.esrnn_profile_enable.argtypes = [vp, C.c_int32]
     lib.esrnn_profile_stage_count.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.esrnn_profile_stage_name.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p)]
@@ -262,6 +266,24 @@ def esrnn_es_window_backward(handle, y, lengths, es_params, workspace, grad_es_p
         raise EsrnnError(st, "esrnn_es_window_backward")
 
 
+def esrnn_predict(handle, y, lengths, es_params, weights, workspace, forecasts, stream=None) -> None:
+    import torch
+    st = load_library().esrnn_predict(handle, _ptr(y, torch.float32), _ptr(lengths, torch.int32),
+                                      _ptr(es_params, torch.float32), _ptr(weights, torch.float32), _ptr(workspace),
+                                      _ptr(forecasts, torch.float32), _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_predict")
+
+
+def esrnn_forecast_metrics(handle, forecasts, actuals, y, lengths, m, smape, mase, stream=None) -> None:
+    import torch
+    st = load_library().esrnn_forecast_metrics(handle, _ptr(forecasts, torch.float32), _ptr(actuals, torch.float32),
+                                               _ptr(y, torch.float32), _ptr(lengths, torch.int32), int(m),
+                                               _ptr(smape, torch.float32), _ptr(mase, torch.float32), _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_forecast_metrics")
+
+
 class TrainingStep:
     """Owns a handle plus the device buffers of one forward/backward pair."""
 
@@ -288,6 +310,13 @@ class TrainingStep:
     def backward(self, y, lengths, es_params, weights, stream=None):
         esrnn_backward(self.handle, y, lengths, es_params, weights, self.workspace, self.grad_es_params,
                        self.grad_weights, stream)
+
+    def predict(self, y, lengths, es_params, weights, stream=None):
+        """Out-of-sample forecasts [B, H] (new tensor).  A later backward() needs a new forward()."""
+        import torch
+        out = torch.empty((self.cfg.B, self.cfg.H), dtype=torch.float32, device=self.device)
+        esrnn_predict(self.handle, y, lengths, es_params, weights, self.workspace, out, stream)
+        return out
 
     def buffer(self, which, index: int = 0):
         """Logical view of a workspace intermediate as a new tensor:

@@ -826,6 +826,95 @@ hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *len
     return run(es_backward_kernel<2>);
 }
 
+// ---------------------------------------------------------------------------
+// Out-of-sample forecasts, Section 3.4 with Eq. (4) and (5).  The forward pass is
+// run with every length extended by H: the window that ends at a series' last
+// observation then counts as a complete window (its "targets" are rows past the
+// series and never reach the forecast), and the network is causal in the window
+// position, so its output there is the out-of-sample output.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) extend_lengths_kernel(const int32_t *__restrict__ lengths, int32_t *__restrict__ ext,
+                                                              int B, int T, int I, int H)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    const int len = lengths[b];
+    ext[b] = (len >= I && len <= T - H) ? len + H : 0;   // 0: the series takes no part
+}
+
+// forecast[b][h-1] = exp(output_h + ln l_t) * S1[t + ((h-1) mod m1) + 1] * S2[...], t = len-1: the last m
+// factors the recursion produced, repeated with their period (Eq. (4)).
+__global__ void __launch_bounds__(256) forecast_tail_kernel(const float *__restrict__ O, const float *__restrict__ u,
+                                                             const float *__restrict__ S1, const float *__restrict__ S2,
+                                                             const int32_t *__restrict__ lengths, float *__restrict__ out,
+                                                             int B, int Bp, int NB, int T, int I, int H, int orows,
+                                                             int m1, int m2)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= B * H) return;
+    const int b = idx / H, j = idx % H;
+    const int len = lengths[b];
+    float f = 0.0f;
+    if (len >= I && len <= T - H) {
+        const int t = len - 1, p = len - I;
+        const float o = O[(((size_t)p * NB + (b >> 4)) * orows + j) * 16 + (b & 15)];
+        float sv = 1.0f;
+        if (m1 > 0) sv = S1[(size_t)(t + (j % m1) + 1) * Bp + b];
+        if (m2 > 0) sv *= S2[(size_t)(t + (j % m2) + 1) * Bp + b];
+        f = __expf(o + u[(size_t)t * Bp + b]) * sv;
+    }
+    out[idx] = f;
+}
+
+// Accuracy of forecasts against actual values, per series (Section 3.5 names the two metrics of the
+// M4 competition): sMAPE = mean_h 200 |a - f| / (|a| + |f|); MASE = mean_h |a - f| divided by the
+// in-sample mean of |y_t - y_{t-m}|, t = m .. len-1 (seasonal naive forecast of period m).
+__global__ void __launch_bounds__(256) forecast_metrics_kernel(const float *__restrict__ f, const float *__restrict__ a,
+                                                                const float *__restrict__ y, const int32_t *__restrict__ lengths,
+                                                                float *__restrict__ smape, float *__restrict__ mase,
+                                                                int B, int T, int H, int m)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    float s_sym = 0.0f, s_abs = 0.0f;
+    for (int j = 0; j < H; ++j) {
+        const float fv = f[(size_t)b * H + j], av = a[(size_t)b * H + j];
+        const float d = fabsf(av - fv);
+        s_sym += 200.0f * d / (fabsf(av) + fabsf(fv));
+        s_abs += d;
+    }
+    const int len = clamp_len(lengths[b], T);
+    float s_naive = 0.0f;
+    for (int t = m; t < len; ++t) s_naive += fabsf(y[(size_t)t * B + b] - y[(size_t)(t - m) * B + b]);
+    smape[b] = s_sym / (float)H;
+    mase[b] = (s_abs / (float)H) / (s_naive / (float)(len - m));
+}
+
+hipError_t launch_extend_lengths(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st)
+{
+    extend_lengths_kernel<<<(pl.B + 255) / 256, 256, 0, st>>>(lengths, reinterpret_cast<int32_t *>(ws + pl.len_ext),
+                                                               pl.B, pl.T, pl.I, pl.H);
+    return hipGetLastError();
+}
+
+hipError_t launch_forecast_tail(const Plan &pl, const int32_t *lengths, float *ws, float *out, hipStream_t st)
+{
+    const esrnn_config &c = pl.cfg;
+    const int n = pl.B * pl.H;
+    forecast_tail_kernel<<<(n + 255) / 256, 256, 0, st>>>(ws + pl.O, ws + pl.u, ws + pl.S1, ws + pl.S2, lengths, out,
+                                                          pl.B, pl.Bp, pl.NB, pl.T, pl.I, pl.H, pl.OP,
+                                                          c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_forecast_metrics(const Plan &pl, const float *forecasts, const float *actuals, const float *y,
+                                   const int32_t *lengths, int m, float *smape, float *mase, hipStream_t st)
+{
+    forecast_metrics_kernel<<<(pl.B + 255) / 256, 256, 0, st>>>(forecasts, actuals, y, lengths, smape, mase,
+                                                                 pl.B, pl.T, pl.H, m);
+    return hipGetLastError();
+}
+
 hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_weights, hipStream_t st)
 {
     ReduceJobs jobs{};

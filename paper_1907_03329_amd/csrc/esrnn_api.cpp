@@ -26,7 +26,7 @@ struct esrnn_handle {
     Stage stage[kMaxStages];
     // stage indices
     int st_setup, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head, st_loss;
-    int st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce;
+    int st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce, st_tail;
 };
 
 namespace {
@@ -90,6 +90,7 @@ esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
     h->st_win_bwd = add_stage(h, "window_backward", 0);
     h->st_es_bwd = add_stage(h, "es_backward", 0);
     h->st_reduce = add_stage(h, "reduce_weight_grads", 0);
+    h->st_tail = add_stage(h, "forecast_tail", 0);
     *out = h;
     return ESRNN_OK;
 }
@@ -178,6 +179,37 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
     ESRNN_TRY(run_stage(h, h->st_es_bwd, st,
                         [&] { return launch_es_backward(pl, y, lengths, es_params, ws, grad_es_params, st); }));
     ESRNN_TRY(run_stage(h, h->st_reduce, st, [&] { return launch_reduce_weight_grads(pl, ws, grad_weights, st); }));
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengths, const float *es_params,
+                           const float *weights, void *workspace, float *forecasts, void *stream)
+{
+    if (!h || !y || !lengths || !es_params || !weights || !workspace || !forecasts) return ESRNN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
+    const Plan &pl = h->plan;
+    float *ws = static_cast<float *>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    h->forward_done = false;    // the workspace now holds the state of the extended problem, not of a training pass
+    const int32_t *ext = reinterpret_cast<const int32_t *>(ws + pl.len_ext);
+    ESRNN_TRY(launch_extend_lengths(pl, lengths, ws, st));
+    ESRNN_TRY(run_stage(h, h->st_setup, st, [&] { return launch_setup(pl, ext, weights, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, ext, es_params, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, ws, st); }));
+    for (int l = 0; l < pl.L; ++l)
+        ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, ext, ws, nullptr, st); }));
+    ESRNN_TRY(run_stage(h, h->st_tail, st, [&] { return launch_forecast_tail(pl, lengths, ws, forecasts, st); }));
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_forecast_metrics(esrnn_handle *h, const float *forecasts, const float *actuals, const float *y,
+                                    const int32_t *lengths, int32_t m, float *smape, float *mase, void *stream)
+{
+    if (!h || !forecasts || !actuals || !y || !lengths || !smape || !mase) return ESRNN_ERR_NULL;
+    if (m < 1 || m >= h->plan.T) return ESRNN_ERR_CONFIG;
+    ESRNN_TRY(launch_forecast_metrics(h->plan, forecasts, actuals, y, lengths, m, smape, mase,
+                                      static_cast<hipStream_t>(stream)));
     return ESRNN_OK;
 }
 

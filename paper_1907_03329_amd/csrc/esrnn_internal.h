@@ -57,6 +57,7 @@ struct Plan {
     // workspace map (offsets in floats)
     size_t scalars;      // float[16]: see Scalars
     size_t sink;         // float[64]: where the lanes past the padded batch put their stores
+    size_t len_ext;      // int32[B]: lengths extended by the horizon (out-of-sample forecasts)
     size_t lvl, S1, S2, u, v, gu, gv;   // [T][Bp]
     size_t X, Z;         // TL(4*IT), TL(OP)
     size_t blk_out[ESRNN_MAX_BLOCKS];
@@ -107,6 +108,11 @@ hipError_t launch_window_backward(const Plan &pl, const int32_t *lengths, float 
 hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,
                               float *ws, float *grad_es, hipStream_t st);
 hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_weights, hipStream_t st);
+
+hipError_t launch_extend_lengths(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
+hipError_t launch_forecast_tail(const Plan &pl, const int32_t *lengths, float *ws, float *out, hipStream_t st);
+hipError_t launch_forecast_metrics(const Plan &pl, const float *forecasts, const float *actuals, const float *y,
+                                   const int32_t *lengths, int m, float *smape, float *mase, hipStream_t st);
 
 // Supported (HT, KXT) instantiations of the LSTM kernels.
 bool lstm_shape_supported(int HT, int KXT);

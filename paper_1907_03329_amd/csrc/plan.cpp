@@ -142,6 +142,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     // first everything the smoothing and window stages touch (their own entry points need only this prefix)
     pl.scalars = ws.take(64);
     pl.sink = ws.take(64);
+    pl.len_ext = ws.take((size_t)pl.B);
     pl.n_loss_partial = head_blocks + pl.es_blocks;
     pl.loss_partial = ws.take((size_t)pl.n_loss_partial);
     pl.lvl = ws.take(TB); pl.S1 = ws.take(TB); pl.S2 = ws.take(TB);
