@@ -117,6 +117,9 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--with-update", action="store_true",
+                    help="add the clipped Adam update (esrnn_adam_update) to every step: the training loop rather "
+                         "than the headline forward+backward step")
     ap.add_argument("--predict", action="store_true",
                     help="time esrnn_predict (out-of-sample forecasts of every series, lengths T - H) instead of "
                          "the training step; one JSON line, not the headline metric")
@@ -174,9 +177,19 @@ def main():
                           "mean_forecast": float(out.mean().item())}))
         return
 
+    if args.with_update:
+        opt = binding.AdamConfig(1e-4, 1e-4, 0.9, 0.999, 1e-8, 20.0)
+        mom = [torch.zeros_like(dev["weights"]), torch.zeros_like(dev["weights"]),
+               torch.zeros_like(dev["es_params"]), torch.zeros_like(dev["es_params"])]
+        counter = [0]
+
     def one_step():
         step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
         step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+        if args.with_update:
+            counter[0] += 1
+            binding.esrnn_adam_update(step.handle, opt, counter[0], dev["weights"], step.grad_weights, mom[0], mom[1],
+                                      dev["es_params"], step.grad_es_params, mom[2], mom[3], step.workspace)
 
     for _ in range(args.warmup):
         one_step()
@@ -269,7 +282,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "seasons": [m for m in (cfg.m1, cfg.m2) if m],
                    "I": cfg.I, "H": cfg.H, "hidden": cfg.hidden, "dilations": [list(b) for b in cfg.blocks],
-                   "tau": cfg.tau, "lambda_lv": cfg.lambda_lv, "window_steps": cfg.B * cfg.P},
+                   "tau": cfg.tau, "lambda_lv": cfg.lambda_lv, "window_steps": cfg.B * cfg.P,
+                   "parameter_update": bool(args.with_update)},
         "window_steps_per_s": round(cfg.B * cfg.P / (elapsed / args.steps), 1),
         "loss": loss,
         "roofline": roofline,

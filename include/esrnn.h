@@ -128,6 +128,30 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
                             float *grad_es_params, float *grad_weights, void *stream);
 
 /*
+ * Parameter update after esrnn_backward, for callers that train in a loop.
+ * Section 3.3 trains the per-series smoothing parameters jointly with the
+ * network weights; the paper does not name its optimiser.  This is the Adam
+ * rule as published (Kingma & Ba 2015, Algorithm 1, with bias correction),
+ * preceded by clipping of the gradient by its global L2 norm over both
+ * parameter sets: g <- g * min(1, clip_norm / (||g|| + 1e-6)).
+ *   m <- beta1 m + (1 - beta1) g,  v <- beta2 v + (1 - beta2) g^2,
+ *   p <- p - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ * step counts from 1.  weights, es_params and the four moment arrays (same
+ * shapes as their parameters, zero before the first step) are updated in place;
+ * the gradients are read only.  Uses a few KB of the workspace.
+ */
+typedef struct {
+    float lr_weights, lr_es;  /* learning rates of the shared weights and of the per-series parameters */
+    float beta1, beta2, eps;
+    float clip_norm;          /* <= 0: no clipping */
+} esrnn_adam_config;
+
+esrnn_status esrnn_adam_update(esrnn_handle *h, const esrnn_adam_config *opt, int32_t step,
+                               float *weights, const float *grad_weights, float *m_weights, float *v_weights,
+                               float *es_params, const float *grad_es_params, float *m_es, float *v_es,
+                               void *workspace, void *stream);
+
+/*
  * Out-of-sample forecasts (Section 3.4 "testing of the network", Eq. (4), (5)):
  * the H steps after each series' last observation, from the window of the last
  * I observations, de-normalised with the last level and re-seasonalised with

@@ -213,3 +213,28 @@ def mase(forecasts, actuals, y, lengths, m):
         out[b] = np.mean(np.abs(a[b] - f[b])) / scale
     return out
 
+
+def adam_update(params, grads, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, clip_norm=0.0):
+    """One Adam step (Kingma & Ba 2015, Algorithm 1 with bias correction) on a list of float64 arrays,
+    after clipping the gradients by their global L2 norm: g <- g * min(1, clip_norm / (||g|| + 1e-6)).
+    ``lr`` is one rate or one per array.  Returns new (params, m, v) lists; inputs are not modified.
+    The paper names no optimiser (Section 3.3 only says the two parameter sets are trained jointly);
+    this is the published rule."""
+    grads = [np.asarray(g, dtype=np.float64) for g in grads]
+    lrs = list(lr) if isinstance(lr, (list, tuple)) else [lr] * len(grads)
+    scale = 1.0
+    if clip_norm > 0.0:
+        norm = np.sqrt(sum(float(np.sum(g * g)) for g in grads))
+        scale = min(1.0, clip_norm / (norm + 1e-6))
+    new_p, new_m, new_v = [], [], []
+    for p, g, m_, v_, a in zip(params, grads, m, v, lrs):
+        g = g * scale
+        m2 = beta1 * np.asarray(m_, dtype=np.float64) + (1.0 - beta1) * g
+        v2 = beta2 * np.asarray(v_, dtype=np.float64) + (1.0 - beta2) * g * g
+        mhat = m2 / (1.0 - beta1 ** step)
+        vhat = v2 / (1.0 - beta2 ** step)
+        new_p.append(np.asarray(p, dtype=np.float64) - a * mhat / (np.sqrt(vhat) + eps))
+        new_m.append(m2)
+        new_v.append(v2)
+    return new_p, new_m, new_v
+

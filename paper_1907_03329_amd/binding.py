@@ -36,6 +36,11 @@ class EsrnnConfig(C.Structure):
     ]
 
 
+class AdamConfig(C.Structure):
+    _fields_ = [("lr_weights", C.c_float), ("lr_es", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("clip_norm", C.c_float)]
+
+
 class BufferView(C.Structure):
     _fields_ = [("offset_bytes", C.c_size_t), ("layout", C.c_int32), ("dims", C.c_int32 * 4)]
 
@@ -75,6 +80,8 @@ def load_library():
     lib.esrnn_es_window_backward.argtypes = [vp, fp, i32p, fp, vp, fp, vp]
     for fn in ("esrnn_es_window_workspace_bytes", "esrnn_es_window_forward", "esrnn_es_window_backward"):
         getattr(lib, fn).restype = C.c_int
+    lib.esrnn_adam_update.argtypes = [vp, C.POINTER(AdamConfig), C.c_int32, fp, fp, fp, fp, fp, fp, fp, fp, vp, vp]
+    lib.esrnn_adam_update.restype = C.c_int
     lib.esrnn_predict.argtypes = [vp, fp, i32p, fp, fp, vp, fp, vp]
     lib.esrnn_forecast_metrics.argtypes = [vp, fp, fp, fp, i32p, C.c_int32, fp, fp, vp]
     for fn in ("esrnn_predict", "esrnn_forecast_metrics"):
@@ -264,6 +271,18 @@ def esrnn_es_window_backward(handle, y, lengths, es_params, workspace, grad_es_p
                                                  _ptr(grad_es_params, torch.float32), _stream(stream))
     if st != ESRNN_OK:
         raise EsrnnError(st, "esrnn_es_window_backward")
+
+
+def esrnn_adam_update(handle, opt: "AdamConfig", step, weights, grad_weights, m_weights, v_weights,
+                      es_params, grad_es_params, m_es, v_es, workspace, stream=None) -> None:
+    import torch
+    f = torch.float32
+    st = load_library().esrnn_adam_update(handle, C.byref(opt), int(step), _ptr(weights, f), _ptr(grad_weights, f),
+                                          _ptr(m_weights, f), _ptr(v_weights, f), _ptr(es_params, f),
+                                          _ptr(grad_es_params, f), _ptr(m_es, f), _ptr(v_es, f), _ptr(workspace),
+                                          _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_adam_update")
 
 
 def esrnn_predict(handle, y, lengths, es_params, weights, workspace, forecasts, stream=None) -> None:

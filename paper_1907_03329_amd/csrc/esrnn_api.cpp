@@ -182,6 +182,25 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
     return ESRNN_OK;
 }
 
+esrnn_status esrnn_adam_update(esrnn_handle *h, const esrnn_adam_config *opt, int32_t step,
+                               float *weights, const float *grad_weights, float *m_weights, float *v_weights,
+                               float *es_params, const float *grad_es_params, float *m_es, float *v_es,
+                               void *workspace, void *stream)
+{
+    if (!h || !opt || !weights || !grad_weights || !m_weights || !v_weights || !es_params || !grad_es_params ||
+        !m_es || !v_es || !workspace)
+        return ESRNN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
+    if (step < 1 || !(opt->beta1 >= 0.0f && opt->beta1 < 1.0f) || !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) ||
+        !(opt->eps > 0.0f))
+        return ESRNN_ERR_CONFIG;
+    ESRNN_TRY(launch_adam_update(h->plan, *opt, step, weights, grad_weights, m_weights, v_weights, es_params,
+                                 grad_es_params, m_es, v_es, static_cast<float *>(workspace),
+                                 static_cast<hipStream_t>(stream)));
+    h->forward_done = false;    // the parameters have changed: a new forward pass comes before the next backward
+    return ESRNN_OK;
+}
+
 esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengths, const float *es_params,
                            const float *weights, void *workspace, float *forecasts, void *stream)
 {

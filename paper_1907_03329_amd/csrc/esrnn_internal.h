@@ -3,6 +3,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <algorithm>
+#include <cmath>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -58,6 +60,7 @@ struct Plan {
     size_t scalars;      // float[16]: see Scalars
     size_t sink;         // float[64]: where the lanes past the padded batch put their stores
     size_t len_ext;      // int32[B]: lengths extended by the horizon (out-of-sample forecasts)
+    size_t opt_partial;  // float[512]: sums of squares of the gradients, per workgroup (parameter update)
     size_t lvl, S1, S2, u, v, gu, gv;   // [T][Bp]
     size_t X, Z;         // TL(4*IT), TL(OP)
     size_t blk_out[ESRNN_MAX_BLOCKS];
@@ -109,6 +112,9 @@ hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *len
                               float *ws, float *grad_es, hipStream_t st);
 hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_weights, hipStream_t st);
 
+hipError_t launch_adam_update(const Plan &pl, const esrnn_adam_config &opt, int step, float *weights,
+                              const float *grad_weights, float *m_w, float *v_w, float *es_params,
+                              const float *grad_es, float *m_es, float *v_es, float *ws, hipStream_t st);
 hipError_t launch_extend_lengths(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
 hipError_t launch_forecast_tail(const Plan &pl, const int32_t *lengths, float *ws, float *out, hipStream_t st);
 hipError_t launch_forecast_metrics(const Plan &pl, const float *forecasts, const float *actuals, const float *y,

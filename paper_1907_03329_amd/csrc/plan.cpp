@@ -143,6 +143,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.scalars = ws.take(64);
     pl.sink = ws.take(64);
     pl.len_ext = ws.take((size_t)pl.B);
+    pl.opt_partial = ws.take(512);
     pl.n_loss_partial = head_blocks + pl.es_blocks;
     pl.loss_partial = ws.take((size_t)pl.n_loss_partial);
     pl.lvl = ws.take(TB); pl.S1 = ws.take(TB); pl.S2 = ws.take(TB);
