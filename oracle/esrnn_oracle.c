@@ -39,6 +39,7 @@ static int make_plan(const eso_config *c, plan_t *pl)
     if (c->n_seas >= 2 && (c->m2 < 1 || c->m2 > c->T)) return 1;
     if (c->I + c->H > c->T) return 1;
     if (c->n_blocks < 1 || c->n_blocks > 4) return 1;
+    if (c->n_cat < 0 || c->n_cat > 16 || (c->n_cat > 0 && !c->categories)) return 1;
     if (!(c->tau > 0.0 && c->tau < 1.0)) return 1;
     int L = 0;
     int64_t off = 0;
@@ -51,7 +52,7 @@ static int make_plan(const eso_config *c, plan_t *pl)
             pl->block_of[L] = k;
             pl->first_in_block[L] = (j == 0);
             pl->last_in_block[L] = (j == c->layers_in_block[k] - 1);
-            pl->in_dim[L] = (L == 0) ? c->I : h;
+            pl->in_dim[L] = (L == 0) ? c->I + c->n_cat : h;   /* window, then the category one-hot (Section 5.3) */
             pl->W_off[L] = off;
             off += (int64_t)4 * h * (pl->in_dim[L] + h);
             pl->b_off[L] = off;
@@ -174,14 +175,17 @@ static void es_forward_series(const eso_config *c, const plan_t *pl, int b, int 
 static void window_series(const eso_config *c, const plan_t *pl, int b, int len, eso_tape *tp)
 {
     const int T = c->T, I = c->I, H = c->H, P = pl->P;
+    const int Iw = I + c->n_cat;   /* width of the network input */
     const double *u = tp->u + (int64_t)b * T, *v = tp->v + (int64_t)b * T;
-    double *X = tp->X + (int64_t)b * P * I, *Z = tp->Z + (int64_t)b * P * H;
-    memset(X, 0, sizeof(double) * P * I);
+    double *X = tp->X + (int64_t)b * P * Iw, *Z = tp->Z + (int64_t)b * P * H;
+    memset(X, 0, sizeof(double) * P * Iw);
     memset(Z, 0, sizeof(double) * P * H);
     const int Pb = len - I - H + 1;
     for (int p = 0; p < Pb; ++p) {
         const int t = p + I - 1;
-        for (int i = 0; i < I; ++i) X[p * I + i] = v[p + i] - u[t];
+        for (int i = 0; i < I; ++i) X[p * Iw + i] = v[p + i] - u[t];
+        /* Section 5.3: a one-hot representation of the series' category follows the window */
+        for (int k = 0; k < c->n_cat; ++k) X[p * Iw + I + k] = (c->categories[b] == k) ? 1.0 : 0.0;
         for (int j = 1; j <= H; ++j) Z[p * H + (j - 1)] = v[t + j] - u[t];
     }
 }
@@ -193,7 +197,7 @@ static void window_series(const eso_config *c, const plan_t *pl, int b, int len,
 static void network_series(const eso_config *c, const plan_t *pl, int b, int Pb,
                            const double *w, eso_tape *tp)
 {
-    const int h = c->hidden, P = pl->P, H = c->H, B = c->B, I = c->I;
+    const int h = c->hidden, P = pl->P, H = c->H, B = c->B, Iw = c->I + c->n_cat;
     for (int layer = 0; layer < pl->L; ++layer) {
         const int in = pl->in_dim[layer], d = pl->dil[layer], k = pl->block_of[layer];
         const double *W = w + pl->W_off[layer], *bias = w + pl->b_off[layer];
@@ -205,7 +209,7 @@ static void network_series(const eso_config *c, const plan_t *pl, int b, int Pb,
         memset(Hh, 0, sizeof(double) * P * h);
         for (int p = 0; p < Pb; ++p) {
             const double *x;
-            if (layer == 0) x = tp->X + ((int64_t)b * P + p) * I;
+            if (layer == 0) x = tp->X + ((int64_t)b * P + p) * Iw;
             else if (pl->first_in_block[layer]) x = tp->blk + (((int64_t)(k - 1) * B + b) * P + p) * h;
             else x = tp->h + (((int64_t)(layer - 1) * B + b) * P + p) * h;
             const double *hprev = (p - d >= 0) ? Hh + (int64_t)(p - d) * h : NULL;
@@ -336,7 +340,7 @@ static void network_backward_series(const eso_config *c, const plan_t *pl, int b
                                     const double *w, const eso_tape *tp, double n_pin,
                                     double *gO, double *gR, double *gX, double *gw)
 {
-    const int h = c->hidden, P = pl->P, H = c->H, B = c->B, I = c->I;
+    const int h = c->hidden, P = pl->P, H = c->H, B = c->B, Iw = c->I + c->n_cat;
     const double *Z = tp->Z + (int64_t)b * P * H, *O = tp->o + (int64_t)b * P * H;
     const double *A = tp->a + (int64_t)b * P * h;
     const double *R = tp->blk + ((int64_t)(c->n_blocks - 1) * B + b) * P * h;
@@ -345,7 +349,7 @@ static void network_backward_series(const eso_config *c, const plan_t *pl, int b
 
     memset(gO, 0, sizeof(double) * P * H);
     memset(gR, 0, sizeof(double) * P * h);
-    memset(gX, 0, sizeof(double) * P * I);
+    memset(gX, 0, sizeof(double) * P * Iw);
     double *da = (double *)calloc(h, sizeof(double));
     for (int p = 0; p < Pb; ++p) {
         for (int j = 0; j < H; ++j) {
@@ -381,7 +385,7 @@ static void network_backward_series(const eso_config *c, const plan_t *pl, int b
     double *g_h = (double *)malloc(sizeof(double) * P * h);
     double *dh_rec = (double *)malloc(sizeof(double) * P * h);
     double *dc_rec = (double *)malloc(sizeof(double) * P * h);
-    double *dx = (double *)malloc(sizeof(double) * P * (h > I ? h : I));
+    double *dx = (double *)malloc(sizeof(double) * P * (h > Iw ? h : Iw));
     double *dgate = (double *)malloc(sizeof(double) * 4 * h);
     memcpy(g_out, gR, sizeof(double) * P * h);
 
@@ -403,7 +407,7 @@ static void network_backward_series(const eso_config *c, const plan_t *pl, int b
         memset(dx, 0, sizeof(double) * P * in);
         for (int p = Pb - 1; p >= 0; --p) {
             const double *x;
-            if (layer == 0) x = tp->X + ((int64_t)b * P + p) * I;
+            if (layer == 0) x = tp->X + ((int64_t)b * P + p) * Iw;
             else if (pl->first_in_block[layer]) x = tp->blk + (((int64_t)(k - 1) * B + b) * P + p) * h;
             else x = tp->h + (((int64_t)(layer - 1) * B + b) * P + p) * h;
             const double *hprev = (p - d >= 0) ? Hh + (int64_t)(p - d) * h : NULL;
@@ -438,7 +442,7 @@ static void network_backward_series(const eso_config *c, const plan_t *pl, int b
             }
         }
         if (layer == 0) {
-            memcpy(gX, dx, sizeof(double) * P * I);
+            memcpy(gX, dx, sizeof(double) * P * Iw);
         } else if (pl->first_in_block[layer]) {
             /* the block input feeds both the first layer and the residual sum */
             for (int64_t q = 0; q < (int64_t)P * h; ++q) g_out[q] = g_in[q] + dx[q];
@@ -455,7 +459,7 @@ static void window_backward_series(const eso_config *c, const plan_t *pl, int b,
                                    const eso_tape *tp, const double *gX, const double *gO,
                                    double n_lv, double *gu, double *gv)
 {
-    const int T = c->T, I = c->I, H = c->H;
+    const int T = c->T, I = c->I, H = c->H, Iw = c->I + c->n_cat;
     const int Pb = len - I - H + 1;
     const double *u = tp->u + (int64_t)b * T;
     (void)pl;
@@ -463,8 +467,8 @@ static void window_backward_series(const eso_config *c, const plan_t *pl, int b,
     for (int p = 0; p < Pb; ++p) {
         const int t = p + I - 1;
         for (int i = 0; i < I; ++i) {
-            gv[p + i] += gX[p * I + i];
-            gu[t] -= gX[p * I + i];
+            gv[p + i] += gX[p * Iw + i];      /* the one-hot columns past I carry no gradient further */
+            gu[t] -= gX[p * Iw + i];
         }
         for (int j = 1; j <= H; ++j) {
             double gz = -gO[p * H + (j - 1)];   /* the loss depends on z - o only */
@@ -567,7 +571,7 @@ int eso_backward(const eso_config *cfg, const double *y, const int32_t *lengths,
 {
     plan_t pl;
     if (make_plan(cfg, &pl)) return 1;
-    const int P = pl.P, h = cfg->hidden, T = cfg->T, I = cfg->I, H = cfg->H;
+    const int P = pl.P, h = cfg->hidden, T = cfg->T, I = cfg->I, H = cfg->H, Iw = cfg->I + cfg->n_cat;
     double n_pin, n_lv;
     loss_counts(cfg, lengths, &n_pin, &n_lv);
     memset(grad_weights, 0, sizeof(double) * pl.n_weights);
@@ -584,7 +588,7 @@ int eso_backward(const eso_config *cfg, const double *y, const int32_t *lengths,
         double *gw = gw_all + (size_t)tid * pl.n_weights;
         double *gO = (double *)malloc(sizeof(double) * P * H);
         double *gR = (double *)malloc(sizeof(double) * P * h);
-        double *gX = (double *)malloc(sizeof(double) * P * I);
+        double *gX = (double *)malloc(sizeof(double) * P * Iw);
         double *gu = (double *)malloc(sizeof(double) * T);
         double *gv = (double *)malloc(sizeof(double) * T);
 #pragma omp for schedule(dynamic, 1)
@@ -596,7 +600,7 @@ int eso_backward(const eso_config *cfg, const double *y, const int32_t *lengths,
             if (adj) {
                 if (adj->gO) memcpy(adj->gO + (int64_t)b * P * H, gO, sizeof(double) * P * H);
                 if (adj->gR) memcpy(adj->gR + (int64_t)b * P * h, gR, sizeof(double) * P * h);
-                if (adj->gX) memcpy(adj->gX + (int64_t)b * P * I, gX, sizeof(double) * P * I);
+                if (adj->gX) memcpy(adj->gX + (int64_t)b * P * Iw, gX, sizeof(double) * P * Iw);
                 if (adj->gu) memcpy(adj->gu + (int64_t)b * T, gu, sizeof(double) * T);
                 if (adj->gv) memcpy(adj->gv + (int64_t)b * T, gv, sizeof(double) * T);
             }
@@ -644,7 +648,8 @@ int eso_predict(const eso_config *cfg, const double *y, const int32_t *lengths,
         double *l = (double *)malloc(sizeof(double) * len);
         double *S1 = (double *)malloc(sizeof(double) * (ext + 1));
         double *S2 = (double *)malloc(sizeof(double) * (ext + 1));
-        double *cur = (double *)malloc(sizeof(double) * Pp * (I > h ? I : h));   /* input of the current layer */
+        const int Iw = I + cfg->n_cat;
+        double *cur = (double *)malloc(sizeof(double) * Pp * (Iw > h ? Iw : h));   /* input of the current layer */
         double *blk_in = (double *)malloc(sizeof(double) * Pp * h);              /* input of the current block */
         double *hs = (double *)malloc(sizeof(double) * Pp * h);
         double *cs = (double *)malloc(sizeof(double) * Pp * h);
@@ -675,10 +680,11 @@ int eso_predict(const eso_config *cfg, const double *y, const int32_t *lengths,
             for (int p = 0; p < Pp; ++p) {
                 const int t = p + I - 1;
                 for (int i = 0; i < I; ++i)
-                    cur[p * I + i] = log(y[(int64_t)(p + i) * B + b] / (l[t] * S1[p + i] * S2[p + i]));
+                    cur[p * Iw + i] = log(y[(int64_t)(p + i) * B + b] / (l[t] * S1[p + i] * S2[p + i]));
+                for (int k = 0; k < cfg->n_cat; ++k) cur[p * Iw + I + k] = (cfg->categories[b] == k) ? 1.0 : 0.0;
             }
             /* Section 3.2: dilated LSTM layers, residual around every block but the first */
-            int width = I;
+            int width = Iw;
             for (int layer = 0; layer < pl.L; ++layer) {
                 const int in = pl.in_dim[layer], d = pl.dil[layer];
                 const double *W = weights + pl.W_off[layer], *bias = weights + pl.b_off[layer];

@@ -36,7 +36,7 @@
  * layouts: y [T][B] time-major, es_params [K][B] (rows: alpha, gamma1, gamma2,
  * s1_init[0..m1), s2_init[0..m2); absent rows omitted), weights flat (per
  * layer W [4h][in+h] row-major with gate rows input, forget, candidate, output
- * and columns input-then-recurrent, then bias [4h]; then Wa [h][h], ba [h],
+ * and columns input-then-recurrent (first layer: window, category one-hot), then bias [4h]; then Wa [h][h], ba [h],
  * Wo [H][h], bo [H]), forecasts [P][B][H].  Tape arrays are series-major.
  */
 #ifndef ESRNN_ORACLE_H
@@ -60,6 +60,9 @@ typedef struct {
     double tau;               /* pinball quantile */
     double lambda_lv;         /* weight of the level penalty */
     double n_pin, n_lv;       /* > 0: use as normalisers instead of the counts from lengths */
+    int32_t n_cat;            /* 0: none; else the network input is the window followed by a one-hot block of
+                                 this many entries for the series' category (Section 5.3) */
+    const int32_t *categories; /* [B], values in [0, n_cat); NULL if n_cat == 0 */
 } eso_config;
 
 /* Forward intermediates; every array is caller-allocated and series-major.
@@ -68,7 +71,7 @@ typedef struct {
     double *alpha, *gamma1, *gamma2;  /* [B] coefficients after the transform */
     double *l, *S1, *S2;              /* [B][T] level, seasonal factor applying at t */
     double *u, *v;                    /* [B][T] ln l, ln y - ln(S1*S2) */
-    double *X;                        /* [B][P][I] */
+    double *X;                        /* [B][P][I + n_cat] */
     double *Z;                        /* [B][P][H] */
     double *gates;                    /* [L][B][P][4][h] activated i, f, g, o */
     double *c, *h;                    /* [L][B][P][h] */
@@ -82,7 +85,7 @@ typedef struct {
 typedef struct {
     double *gO;        /* [B][P][H] dL/do  (dL/dz is its negative) */
     double *gR;        /* [B][P][h] dL/d(top block output) */
-    double *gX;        /* [B][P][I] */
+    double *gX;        /* [B][P][I + n_cat] */
     double *gu, *gv;   /* [B][T] */
 } eso_adjoint;
 

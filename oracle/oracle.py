@@ -31,6 +31,7 @@ class _Config(C.Structure):
         ("param_space", C.c_int32),
         ("tau", C.c_double), ("lambda_lv", C.c_double),
         ("n_pin", C.c_double), ("n_lv", C.c_double),
+        ("n_cat", C.c_int32), ("categories", C.POINTER(C.c_int32)),
     ]
 
 
@@ -66,8 +67,16 @@ def max_threads() -> int:
     return int(lib().eso_max_threads())
 
 
-def _c_config(cfg, n_pin=0.0, n_lv=0.0, B=None) -> _Config:
+def _c_config(cfg, n_pin=0.0, n_lv=0.0, B=None, categories=None) -> _Config:
     c = _Config()
+    c.n_cat = int(getattr(cfg, "n_cat", 0))
+    if c.n_cat > 0:
+        if categories is None:
+            raise ValueError("oracle: this configuration needs the categories of the series")
+        cat = np.ascontiguousarray(categories, dtype=np.int32)
+        assert cat.min() >= 0 and cat.max() < c.n_cat
+        c._keep = cat                                   # keeps the array alive as long as the struct
+        c.categories = cat.ctypes.data_as(C.POINTER(C.c_int32))
     c.B, c.T = int(cfg.B if B is None else B), int(cfg.T)
     c.n_seas, c.m1, c.m2 = int(cfg.n_seas), int(cfg.m1), int(cfg.m2)
     c.I, c.H, c.hidden = int(cfg.I), int(cfg.H), int(cfg.hidden)
@@ -86,7 +95,7 @@ def _ptr(a):
     return a.ctypes.data_as(_dp)
 
 
-def forward(cfg, y, lengths, es_params, weights, n_pin=0.0, n_lv=0.0, want_forecasts=True):
+def forward(cfg, y, lengths, es_params, weights, n_pin=0.0, n_lv=0.0, want_forecasts=True, categories=None):
     """Run the oracle forward.  Inputs are converted to float64; returns a
     namespace with loss, forecasts [P,B,H] and every intermediate (series-major
     arrays, see esrnn_oracle.h)."""
@@ -96,7 +105,7 @@ def forward(cfg, y, lengths, es_params, weights, n_pin=0.0, n_lv=0.0, want_forec
     weights = np.ascontiguousarray(weights, dtype=np.float64)
     lengths = np.ascontiguousarray(lengths, dtype=np.int32)
     T, B = y.shape
-    cc = _c_config(cfg, n_pin, n_lv, B=B)
+    cc = _c_config(cfg, n_pin, n_lv, B=B, categories=categories)
     assert T == cfg.T
     K = L_.eso_es_param_rows(C.byref(cc))
     nw = L_.eso_weight_count(C.byref(cc))
@@ -111,7 +120,8 @@ def forward(cfg, y, lengths, es_params, weights, n_pin=0.0, n_lv=0.0, want_forec
     r = SimpleNamespace()
     r.alpha, r.gamma1, r.gamma2 = (np.zeros(B) for _ in range(3))
     r.l, r.S1, r.S2, r.u, r.v = (np.zeros((B, T)) for _ in range(5))
-    r.X = np.zeros((B, P, I))
+    Iw = I + int(getattr(cfg, "n_cat", 0))
+    r.X = np.zeros((B, P, Iw))
     r.Z = np.zeros((B, P, H))
     r.gates = np.zeros((nl, B, P, 4, h))
     r.c = np.zeros((nl, B, P, h))
@@ -152,7 +162,7 @@ def backward(cfg, fwd, want_adjoints=True):
     if want_adjoints:
         g.gO = np.zeros((B, P, H))
         g.gR = np.zeros((B, P, h))
-        g.gX = np.zeros((B, P, I))
+        g.gX = np.zeros((B, P, I + int(getattr(cfg, "n_cat", 0))))
         g.gu = np.zeros((B, T))
         g.gv = np.zeros((B, T))
         for name in ("gO", "gR", "gX", "gu", "gv"):
@@ -170,7 +180,7 @@ def loss_only(cfg, y, lengths, es_params, weights, **kw) -> float:
     return forward(cfg, y, lengths, es_params, weights, want_forecasts=False, **kw).loss
 
 
-def predict(cfg, y, lengths, es_params, weights):
+def predict(cfg, y, lengths, es_params, weights, categories=None):
     """Out-of-sample forecasts [B, H] of the H steps after each series' last
     observation (Section 3.4, Eq. (4), (5)); rows of y past a length are not read."""
     L_ = lib()
@@ -180,7 +190,7 @@ def predict(cfg, y, lengths, es_params, weights):
     lengths = np.ascontiguousarray(lengths, dtype=np.int32)
     T, B = y.shape
     assert T == cfg.T
-    cc = _c_config(cfg, B=B)
+    cc = _c_config(cfg, B=B, categories=categories)
     out = np.zeros((B, cfg.H))
     rc = L_.eso_predict(C.byref(cc), _ptr(y), lengths.ctypes.data_as(C.POINTER(C.c_int32)),
                         _ptr(es_params), _ptr(weights), _ptr(out))

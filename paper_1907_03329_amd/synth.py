@@ -39,6 +39,7 @@ class Config:
     tau: float = 0.48
     lambda_lv: float = 50.0
     param_space: int = PARAMS_DIRECT
+    n_cat: int = 0     # series categories fed to the network as a one-hot block after the input window (Section 5.3); 0: none
     # generator knobs (standard deviations; see make_inputs)
     step_mu: float = 0.0
     step_sd: float = 0.02
@@ -66,7 +67,7 @@ class Config:
     def weight_count(self) -> int:
         h, n = self.hidden, 0
         for layer in range(self.n_layers):
-            k = (self.I if layer == 0 else h) + h
+            k = (self.I + self.n_cat if layer == 0 else h) + h
             n += 4 * h * k + 4 * h
         return n + h * h + h + self.H * h + self.H
 
@@ -96,13 +97,14 @@ def weight_layout(cfg: Config) -> List[Tuple[str, int, Tuple[int, ...]]]:
     """(name, offset, shape) of every block of the flat weight vector.
 
     Per LSTM layer: ``W`` of shape [4h, in+h] row-major, gate rows in the order
-    input, forget, cell candidate, output, columns first the layer input then
-    the recurrent state; then the bias [4h].  After the layers: adapter
+    input, forget, cell candidate, output, columns first the layer input (for
+    the first layer: the window, then the one-hot category block) then the
+    recurrent state; then the bias [4h].  After the layers: adapter
     ``Wa`` [h, h], ``ba`` [h], head ``Wo`` [H, h], ``bo`` [H].
     """
     h, out, off = cfg.hidden, [], 0
     for layer in range(cfg.n_layers):
-        k = (cfg.I if layer == 0 else h) + h
+        k = (cfg.I + cfg.n_cat if layer == 0 else h) + h      # first layer: window, then the category one-hot
         out.append((f"W{layer}", off, (4 * h, k)))
         off += 4 * h * k
         out.append((f"b{layer}", off, (4 * h,)))
@@ -137,8 +139,9 @@ def make_inputs(cfg: Config, seed: int = 0, ragged: bool = False) -> Dict[str, n
     """Draw one batch.  Fixed draw order, float64 draws cast to float32 once.
 
     Returns ``y`` [T, B] float32 (time-major, pad value 1 past each length),
-    ``lengths`` [B] int32, ``es_params`` [K, B] float32 (in ``cfg.param_space``)
-    and ``weights`` [weight_count] float32.
+    ``lengths`` [B] int32, ``es_params`` [K, B] float32 (in ``cfg.param_space``),
+    ``weights`` [weight_count] float32 and, if ``cfg.n_cat > 0``, ``categories``
+    [B] int32 in [0, n_cat).
     """
     rng = np.random.Generator(np.random.PCG64(seed))
     B, T, h = cfg.B, cfg.T, cfg.hidden
@@ -193,20 +196,27 @@ def make_inputs(cfg: Config, seed: int = 0, ragged: bool = False) -> Dict[str, n
         if B > 1:
             lengths[-1] = lo
         y[t[:, None] >= lengths[None, :]] = 1.0
-    return {
+    out = {
         "y": np.ascontiguousarray(y, dtype=np.float32),
         "lengths": lengths,
         "es_params": np.ascontiguousarray(es, dtype=np.float32),
         "weights": np.ascontiguousarray(w, dtype=np.float32),
     }
+    # categories after everything else, and only when asked for: batches without them stay as they were
+    if cfg.n_cat > 0:
+        out["categories"] = rng.integers(0, cfg.n_cat, size=B).astype(np.int32)
+    return out
 
 
 def take_series(inputs: Dict[str, np.ndarray], idx) -> Dict[str, np.ndarray]:
     """Restrict a batch to the series in ``idx`` (weights are shared)."""
     idx = np.asarray(idx)
-    return {
+    out = {
         "y": np.ascontiguousarray(inputs["y"][:, idx]),
         "lengths": np.ascontiguousarray(inputs["lengths"][idx]),
         "es_params": np.ascontiguousarray(inputs["es_params"][:, idx]),
         "weights": inputs["weights"],
     }
+    if "categories" in inputs:
+        out["categories"] = np.ascontiguousarray(inputs["categories"][idx])
+    return out
