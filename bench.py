@@ -46,7 +46,7 @@ def stage_model(cfg, name):
     n_seas = cfg.n_seas
     if name.startswith("lstm_forward_l") or name.startswith("lstm_backward_l"):
         layer = int(name.rsplit("l", 1)[1])
-        k = (I if layer == 0 else h) + h
+        k = (I + cfg.n_cat if layer == 0 else h) + h
         per = 2 * k * 4 * h
         if name.startswith("lstm_backward"):
             per *= 2                      # transposed contraction + weight gradient
@@ -117,6 +117,9 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--categories", type=int, default=0,
+                    help="feed a one-hot block of this many series categories after the input window (the paper "
+                         "uses 6); 0 = the headline configuration")
     ap.add_argument("--with-update", action="store_true",
                     help="add the clipped Adam update (esrnn_adam_update) to every step: the training loop rather "
                          "than the headline forward+backward step")
@@ -141,10 +144,14 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     if args.batch:
         cfg = cfg.with_(B=args.batch)
+    if args.categories:
+        cfg = cfg.with_(n_cat=args.categories)
     inp = synth.make_inputs(cfg, seed=0)
     torch.cuda.set_device(0)
     dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
     step = binding.TrainingStep(cfg, want_forecasts=True)
+    if args.categories:
+        step.set_categories(dev["categories"])
 
     if args.copy_probe_mib:
         src = torch.ones(args.copy_probe_mib * 262144, dtype=torch.float32, device="cuda")
@@ -251,7 +258,8 @@ def main():
         reps = 2
 
         def oracle_step():
-            f = oracle.forward(scfg, sub["y"], sub["lengths"], sub["es_params"], sub["weights"], want_forecasts=True)
+            f = oracle.forward(scfg, sub["y"], sub["lengths"], sub["es_params"], sub["weights"], want_forecasts=True,
+                               categories=sub.get("categories"))
             oracle.backward(scfg, f, want_adjoints=False)
             return f
 
@@ -283,7 +291,7 @@ def main():
         "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "seasons": [m for m in (cfg.m1, cfg.m2) if m],
                    "I": cfg.I, "H": cfg.H, "hidden": cfg.hidden, "dilations": [list(b) for b in cfg.blocks],
                    "tau": cfg.tau, "lambda_lv": cfg.lambda_lv, "window_steps": cfg.B * cfg.P,
-                   "parameter_update": bool(args.with_update)},
+                   "parameter_update": bool(args.with_update), "categories": cfg.n_cat},
         "window_steps_per_s": round(cfg.B * cfg.P / (elapsed / args.steps), 1),
         "loss": loss,
         "roofline": roofline,

@@ -46,7 +46,8 @@ extern "C" {
 #define ESRNN_MAX_BLOCKS 4
 #define ESRNN_MAX_LAYERS_PER_BLOCK 4
 #define ESRNN_MAX_HIDDEN 64
-#define ESRNN_MAX_WINDOW 64   /* limit for both I and H */
+#define ESRNN_MAX_WINDOW 64   /* limit for both I + n_categories and H */
+#define ESRNN_MAX_CATEGORIES 16
 
 typedef enum {
     ESRNN_OK = 0,
@@ -74,6 +75,9 @@ typedef struct {
     float tau;                /* pinball quantile in (0,1) */
     float lambda_lv;          /* weight of the level penalty; 0 disables it */
     int32_t param_space;      /* esrnn_param_space */
+    int32_t n_categories;     /* 0: none; else the network input is the window followed by a one-hot block of this
+                                 many entries for the series' category (Section 5.3; the paper's data has 6), and the
+                                 first layer's W is [4*hidden][I + n_categories + hidden].  See esrnn_set_categories */
 } esrnn_config;
 
 typedef struct esrnn_handle esrnn_handle;
@@ -83,6 +87,11 @@ typedef struct esrnn_handle esrnn_handle;
  * Host-only; touches no device. */
 esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out);
 esrnn_status esrnn_destroy(esrnn_handle *h);
+
+/* Category of every series (Section 5.3): device array [B] of int32 in [0, n_categories), read by every
+ * later esrnn_forward, esrnn_predict and esrnn_es_window_forward on this handle; it must stay valid until
+ * then.  Required before those calls when n_categories > 0 (they return ESRNN_ERR_NULL otherwise). */
+esrnn_status esrnn_set_categories(esrnn_handle *h, const int32_t *categories);
 
 /* Sizes the caller needs to allocate buffers. */
 esrnn_status esrnn_workspace_bytes(const esrnn_handle *h, size_t *bytes);

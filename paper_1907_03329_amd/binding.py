@@ -33,6 +33,7 @@ class EsrnnConfig(C.Structure):
         ("dilation", (C.c_int32 * 4) * 4),
         ("tau", C.c_float), ("lambda_lv", C.c_float),
         ("param_space", C.c_int32),
+        ("n_categories", C.c_int32),
     ]
 
 
@@ -80,6 +81,8 @@ def load_library():
     lib.esrnn_es_window_backward.argtypes = [vp, fp, i32p, fp, vp, fp, vp]
     for fn in ("esrnn_es_window_workspace_bytes", "esrnn_es_window_forward", "esrnn_es_window_backward"):
         getattr(lib, fn).restype = C.c_int
+    lib.esrnn_set_categories.argtypes = [vp, i32p]
+    lib.esrnn_set_categories.restype = C.c_int
     lib.esrnn_adam_update.argtypes = [vp, C.POINTER(AdamConfig), C.c_int32, fp, fp, fp, fp, fp, fp, fp, fp, vp, vp]
     lib.esrnn_adam_update.restype = C.c_int
     lib.esrnn_predict.argtypes = [vp, fp, i32p, fp, fp, vp, fp, vp]
@@ -107,7 +110,7 @@ def status_string(status: int) -> str:
 
 def make_config(cfg) -> EsrnnConfig:
     """Build the C struct from any object with fields B, T, n_seas, m1, m2, I, H,
-    hidden, blocks, tau, lambda_lv, param_space."""
+    hidden, blocks, tau, lambda_lv, param_space and, optionally, n_cat."""
     c = EsrnnConfig()
     c.B, c.T = int(cfg.B), int(cfg.T)
     c.n_seas, c.m1, c.m2 = int(cfg.n_seas), int(cfg.m1), int(cfg.m2)
@@ -121,6 +124,7 @@ def make_config(cfg) -> EsrnnConfig:
             c.dilation[k][j] = int(d)
     c.tau, c.lambda_lv = float(cfg.tau), float(cfg.lambda_lv)
     c.param_space = int(cfg.param_space)
+    c.n_categories = int(getattr(cfg, "n_cat", 0))
     return c
 
 
@@ -273,6 +277,13 @@ def esrnn_es_window_backward(handle, y, lengths, es_params, workspace, grad_es_p
         raise EsrnnError(st, "esrnn_es_window_backward")
 
 
+def esrnn_set_categories(handle, categories) -> None:
+    import torch
+    st = load_library().esrnn_set_categories(handle, _ptr(categories, torch.int32, allow_none=True))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_set_categories")
+
+
 def esrnn_adam_update(handle, opt: "AdamConfig", step, weights, grad_weights, m_weights, v_weights,
                       es_params, grad_es_params, m_es, v_es, workspace, stream=None) -> None:
     import torch
@@ -322,6 +333,11 @@ class TrainingStep:
                           if want_forecasts else None)
         self.grad_es_params = torch.empty((self.K, cfg.B), dtype=torch.float32, device=self.device)
         self.grad_weights = torch.empty(self.n_weights, dtype=torch.float32, device=self.device)
+
+    def set_categories(self, categories):
+        """Device int32 tensor [B]; kept referenced here so that it outlives the calls that read it."""
+        self._categories = categories
+        esrnn_set_categories(self.handle, categories)
 
     def forward(self, y, lengths, es_params, weights, stream=None):
         esrnn_forward(self.handle, y, lengths, es_params, weights, self.workspace, self.loss, self.forecasts, stream)

@@ -330,7 +330,8 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
 __global__ void __launch_bounds__(256) window_forward_kernel(const float *__restrict__ u, const float *__restrict__ v,
                                                               float *__restrict__ X, float *__restrict__ Z,
                                                               int P, int NB, int Bp, int I, int H, int xrows, int zrows,
-                                                              int p_per_wave)
+                                                              int p_per_wave, const int32_t *__restrict__ categories,
+                                                              int n_cat, int B)
 {
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, n = lane & 15;
@@ -340,12 +341,15 @@ __global__ void __launch_bounds__(256) window_forward_kernel(const float *__rest
     if (bt >= NB) return;
     const int p0 = blockIdx.y * p_per_wave;
     const int col = bt * 16 + n;
+    // Section 5.3: the one-hot block of the series' category follows the window (rows I .. I+n_cat-1)
+    const int hot = (n_cat > 0 && col < B) ? I + categories[col] : -1;
     for (int p = p0; p < p0 + p_per_wave && p < P; ++p) {
         const size_t tile = (size_t)p * NB + bt;
         const int t = p + I - 1;
         const float ut = u[(size_t)t * Bp + col];
         float *xo = X + tile * xrows * 16 + lane;
-        for (int r = g; r < xrows; r += 4) xo[(r - g) * 16] = (r < I) ? v[(size_t)(p + r) * Bp + col] - ut : 0.0f;
+        for (int r = g; r < xrows; r += 4)
+            xo[(r - g) * 16] = (r < I) ? v[(size_t)(p + r) * Bp + col] - ut : (r == hot ? 1.0f : 0.0f);
         float *zo = Z + tile * zrows * 16 + lane;
         for (int r = g; r < zrows; r += 4) zo[(r - g) * 16] = (r < H) ? v[(size_t)(t + 1 + r) * Bp + col] - ut : 0.0f;
     }
@@ -778,13 +782,13 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
     return run(es_forward_kernel<2>);
 }
 
-hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st)
+hipError_t launch_window_forward(const Plan &pl, const int32_t *categories, float *ws, hipStream_t st)
 {
     // few positions per wave at small batches (enough waves), more at large ones (less per-wave overhead)
     const int p_per_wave = pl.NB >= 2048 ? 8 : (pl.NB >= 512 ? 4 : 1);
     window_forward_kernel<<<dim3((pl.NB + 3) / 4, (pl.P + p_per_wave - 1) / p_per_wave), 256, 0, st>>>(ws + pl.u, ws + pl.v, ws + pl.X, ws + pl.Z,
                                                                          pl.P, pl.NB, pl.Bp, pl.I, pl.H, 4 * pl.IT,
-                                                                         pl.OP, p_per_wave);
+                                                                         pl.OP, p_per_wave, categories, pl.C, pl.B);
     return hipGetLastError();
 }
 

@@ -27,6 +27,7 @@ struct esrnn_handle {
     // stage indices
     int st_setup, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head, st_loss;
     int st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce, st_tail;
+    const int32_t *categories;   // device array of the caller, or null
 };
 
 namespace {
@@ -78,6 +79,7 @@ esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
     }
     h->forward_done = false;
     h->profiling = false;
+    h->categories = nullptr;
     h->n_stages = 0;
     const Plan &pl = h->plan;
     h->st_setup = add_stage(h, "setup", 0);
@@ -103,6 +105,14 @@ esrnn_status esrnn_destroy(esrnn_handle *h)
         if (h->stage[i].stop) (void)hipEventDestroy(h->stage[i].stop);
     }
     delete h;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_set_categories(esrnn_handle *h, const int32_t *categories)
+{
+    if (!h) return ESRNN_ERR_NULL;
+    if (h->plan.C == 0 && categories) return ESRNN_ERR_CONFIG;
+    h->categories = categories;
     return ESRNN_OK;
 }
 
@@ -145,6 +155,7 @@ esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengt
                            float *loss, float *forecasts, void *stream)
 {
     if (!h || !y || !lengths || !es_params || !weights || !workspace || !loss) return ESRNN_ERR_NULL;
+    if (h->plan.C > 0 && !h->categories) return ESRNN_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
     const Plan &pl = h->plan;
     float *ws = static_cast<float *>(workspace);
@@ -152,7 +163,7 @@ esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengt
     h->forward_done = false;
     ESRNN_TRY(run_stage(h, h->st_setup, st, [&] { return launch_setup(pl, lengths, weights, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, lengths, es_params, ws, st); }));
-    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, h->categories, ws, st); }));
     for (int l = 0; l < pl.L; ++l)
         ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ws, st); }));
     // the output stage runs its reverse pass in the same launch: the loss gradient needs nothing beyond it
@@ -205,6 +216,7 @@ esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengt
                            const float *weights, void *workspace, float *forecasts, void *stream)
 {
     if (!h || !y || !lengths || !es_params || !weights || !workspace || !forecasts) return ESRNN_ERR_NULL;
+    if (h->plan.C > 0 && !h->categories) return ESRNN_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
     const Plan &pl = h->plan;
     float *ws = static_cast<float *>(workspace);
@@ -214,7 +226,7 @@ esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengt
     ESRNN_TRY(launch_extend_lengths(pl, lengths, ws, st));
     ESRNN_TRY(run_stage(h, h->st_setup, st, [&] { return launch_setup(pl, ext, weights, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, ext, es_params, ws, st); }));
-    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, h->categories, ws, st); }));
     for (int l = 0; l < pl.L; ++l)
         ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, ext, ws, nullptr, st); }));
@@ -243,13 +255,14 @@ esrnn_status esrnn_es_window_forward(esrnn_handle *h, const float *y, const int3
                                      const float *es_params, void *workspace, void *stream)
 {
     if (!h || !y || !lengths || !es_params || !workspace) return ESRNN_ERR_NULL;
+    if (h->plan.C > 0 && !h->categories) return ESRNN_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
     const Plan &pl = h->plan;
     float *ws = static_cast<float *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     ESRNN_TRY(run_stage(h, h->st_setup, st, [&] { return launch_setup(pl, lengths, nullptr, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, lengths, es_params, ws, st); }));
-    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, ws, st); }));
+    ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, h->categories, ws, st); }));
     return ESRNN_OK;
 }
 
@@ -340,8 +353,8 @@ esrnn_status esrnn_workspace_buffer(const esrnn_handle *h, int32_t which, int32_
     case ESRNN_BUF_V: off = pl.v; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
     case ESRNN_BUF_GRAD_U: off = pl.gu; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
     case ESRNN_BUF_GRAD_V: off = pl.gv; layout = ESRNN_LAYOUT_TIME_MAJOR; break;
-    case ESRNN_BUF_X: off = pl.X; rows = 4 * pl.IT; logical = pl.I; break;
-    case ESRNN_BUF_GRAD_X: off = pl.gX; rows = 4 * pl.IT; logical = pl.I; break;
+    case ESRNN_BUF_X: off = pl.X; rows = 4 * pl.IT; logical = pl.I + pl.C; break;
+    case ESRNN_BUF_GRAD_X: off = pl.gX; rows = 4 * pl.IT; logical = pl.I + pl.C; break;
     case ESRNN_BUF_Z: off = pl.Z; rows = pl.OP; logical = pl.H; break;
     case ESRNN_BUF_O: off = pl.O; rows = pl.OP; logical = pl.H; break;
     case ESRNN_BUF_GRAD_O: off = pl.gO; rows = pl.OP; logical = pl.H; break;

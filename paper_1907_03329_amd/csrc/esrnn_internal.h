@@ -46,9 +46,10 @@ struct LayerPlan {
 struct Plan {
     esrnn_config cfg;
     int B, T, I, H, h, P;
+    int C;               // entries of the category one-hot block that follows the input window (0: none)
     int NB, Bp;          // series tiles, padded batch
     int HT, HP;          // hidden unit tiles, padded hidden (4*HT)
-    int IT;              // unit tiles of the input window as used by layer 0
+    int IT;              // unit tiles of the network input (window + one-hot block) as used by layer 0
     int OT, MO, OP;      // horizon: unit tiles, 16-row MFMA tiles, rows of the Z / O / gO tiles (4*OT)
     int MA;              // 16-row tiles of the hidden dimension in "unit-tile" order: ceil(HT/4)
     int L;
@@ -100,7 +101,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl);
 hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *weights, float *ws, hipStream_t st);
 hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,
                              float *ws, hipStream_t st);
-hipError_t launch_window_forward(const Plan &pl, float *ws, hipStream_t st);
+hipError_t launch_window_forward(const Plan &pl, const int32_t *categories, float *ws, hipStream_t st);
 hipError_t launch_lstm_forward(const Plan &pl, int layer, float *ws, hipStream_t st);
 // output stage, forward and reverse in one launch (needs the loss normalisers of launch_setup)
 hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st);

@@ -453,7 +453,8 @@ hipError_t run_bwd(const LstmBwdArgs &a, int chains, hipStream_t st)
     return hipGetLastError();
 }
 
-#define ESRNN_LSTM_SHAPES(X) X(2, 1) X(2, 2) X(8, 2) X(8, 8) X(10, 1) X(10, 6) X(10, 10) X(13, 3) X(13, 13) X(16, 16)
+#define ESRNN_LSTM_SHAPES(X) \
+    X(2, 1) X(2, 2) X(8, 2) X(8, 3) X(8, 8) X(10, 1) X(10, 3) X(10, 6) X(10, 8) X(10, 10) X(13, 3) X(13, 5) X(13, 13) X(16, 16)
 
 }  // namespace
 

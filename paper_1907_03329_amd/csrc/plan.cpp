@@ -35,8 +35,8 @@ int pick_ht(int hidden)
 
 bool lstm_shape_supported(int HT, int KXT)
 {
-    static const int pairs[][2] = {{2, 1}, {2, 2}, {8, 2}, {8, 8}, {10, 1}, {10, 6}, {10, 10},
-                                   {13, 3}, {13, 13}, {16, 16}};
+    static const int pairs[][2] = {{2, 1}, {2, 2}, {8, 2}, {8, 3}, {8, 8}, {10, 1}, {10, 3}, {10, 6}, {10, 8}, {10, 10},
+                                   {13, 3}, {13, 5}, {13, 13}, {16, 16}};
     for (auto &p : pairs)
         if (p[0] == HT && p[1] == KXT) return true;
     return false;
@@ -73,8 +73,10 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     if (!(cfg.lambda_lv >= 0.0f)) return ESRNN_ERR_CONFIG;
     if (cfg.param_space != ESRNN_PARAMS_DIRECT && cfg.param_space != ESRNN_PARAMS_LOGIT) return ESRNN_ERR_CONFIG;
     if ((long long)cfg.B * cfg.T > (1LL << 30)) return ESRNN_ERR_CONFIG;
+    if (cfg.n_categories < 0 || cfg.n_categories > ESRNN_MAX_CATEGORIES) return ESRNN_ERR_CONFIG;
+    if (cfg.I + cfg.n_categories > ESRNN_MAX_WINDOW) return ESRNN_ERR_CONFIG;
 
-    pl.B = cfg.B; pl.T = cfg.T; pl.I = cfg.I; pl.H = cfg.H; pl.h = cfg.hidden;
+    pl.B = cfg.B; pl.T = cfg.T; pl.I = cfg.I; pl.H = cfg.H; pl.h = cfg.hidden; pl.C = cfg.n_categories;
     pl.P = cfg.T - cfg.I - cfg.H + 1;
     pl.NB = ceil_div(cfg.B, kTileN);
     pl.Bp = pl.NB * kTileN;
@@ -86,9 +88,9 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.OP = 4 * pl.OT;
     pl.MA = ceil_div(pl.HT, 4);
     // layer 0 input tiles: exact if that kernel shape is instantiated, else padded to HT
-    pl.IT = ceil_div(cfg.I, 4);
+    pl.IT = ceil_div(cfg.I + pl.C, 4);
     if (!lstm_shape_supported(pl.HT, pl.IT)) {
-        if (cfg.I > pl.HP) return ESRNN_ERR_CONFIG;
+        if (cfg.I + pl.C > pl.HP) return ESRNN_ERR_CONFIG;
         pl.IT = pl.HT;
     }
 
@@ -114,7 +116,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
             lp.block = k;
             lp.first_in_block = (j == 0);
             lp.last_in_block = (j == nl - 1);
-            lp.in_dim = (L == 0) ? cfg.I : h;
+            lp.in_dim = (L == 0) ? cfg.I + pl.C : h;
             lp.KXT = (L == 0) ? pl.IT : pl.HT;
             lp.w_off = off; off += (size_t)4 * h * (lp.in_dim + h);
             lp.b_off = off; off += (size_t)4 * h;

@@ -38,6 +38,8 @@ def run_gpu(cfg, inp, backward=True):
     import torch
     step = binding.TrainingStep(cfg)
     dev = to_device(inp)
+    if "categories" in dev:
+        step.set_categories(dev["categories"])
     step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
     if backward:
         step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
@@ -136,7 +138,8 @@ def run_and_check(cfg, seed=0, ragged=False, stages=True, mutate=None):
     inp = synth.make_inputs(cfg, seed=seed, ragged=ragged)
     if mutate is not None:
         mutate(inp)
-    f = oracle.forward(cfg, inp["y"], inp["lengths"], inp["es_params"], inp["weights"])
+    f = oracle.forward(cfg, inp["y"], inp["lengths"], inp["es_params"], inp["weights"],
+                       categories=inp.get("categories"))
     g = oracle.backward(cfg, f)
     step = run_gpu(cfg, inp)
     errs = check_forward(cfg, inp, step, f, stages)
