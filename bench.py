@@ -114,6 +114,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the number of series")
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="host threads of the oracle baseline (0 = all)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -248,6 +249,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import oracle
+        if args.cpu_threads > 0:
+            oracle.set_num_threads(args.cpu_threads)
         # the full workload if it is small enough, else a prefix of the series
         flops = 3.0 * sum(stage_model(cfg, f"lstm_forward_l{l}")[1] for l in range(cfg.n_layers))
         nb = cfg.B

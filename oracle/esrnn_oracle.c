@@ -89,6 +89,17 @@ int eso_max_threads(void)
 #endif
 }
 
+/* Limits the host threads of the later calls (timing runs only; results do not depend on it beyond the
+ * order in which per-thread weight-gradient sums are added). */
+void eso_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 static double sigmoid(double x) { return 1.0 / (1.0 + exp(-x)); }
 
 /* Normalisers of the two loss terms: the number of unmasked head outputs and

@@ -93,6 +93,7 @@ int eso_es_param_rows(const eso_config *cfg);
 int64_t eso_weight_count(const eso_config *cfg);
 int eso_num_layers(const eso_config *cfg);
 int eso_max_threads(void);
+void eso_set_num_threads(int n);   /* host threads used by later calls (timing only) */
 
 /* Returns 0 on success, nonzero on an invalid configuration. */
 int eso_forward(const eso_config *cfg, const double *y, const int32_t *lengths,

@@ -67,6 +67,11 @@ def max_threads() -> int:
     return int(lib().eso_max_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Host threads of later oracle calls (for timing the baseline on one core)."""
+    lib().eso_set_num_threads(C.c_int(int(n)))
+
+
 def _c_config(cfg, n_pin=0.0, n_lv=0.0, B=None, categories=None) -> _Config:
     c = _Config()
     c.n_cat = int(getattr(cfg, "n_cat", 0))
