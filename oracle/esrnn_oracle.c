@@ -311,6 +311,33 @@ static void loss_series(const eso_config *c, const plan_t *pl, int b, int len,
             }
 }
 
+/* Section 8.4, second kind of penalty: the average squared magnitude of the cell state of the first
+ * layer of every block ("stack").  Reading: one average over those layers, the valid window positions
+ * of all series and the hidden units; this returns one series' sum of squares. */
+static double cell_state_sumsq(const eso_config *c, const plan_t *pl, int b, int Pb, const eso_tape *tp)
+{
+    const int h = c->hidden, P = pl->P, B = c->B;
+    double s = 0.0;
+    for (int layer = 0; layer < pl->L; ++layer) {
+        if (!pl->first_in_block[layer]) continue;
+        const double *C = tp->c + ((int64_t)layer * B + b) * P * h;
+        for (int p = 0; p < Pb; ++p)
+            for (int j = 0; j < h; ++j) s += C[(int64_t)p * h + j] * C[(int64_t)p * h + j];
+    }
+    return s;
+}
+
+/* number of terms of that average */
+static double cell_state_count(const eso_config *c, const int32_t *lengths)
+{
+    double n = 0.0;
+    for (int b = 0; b < c->B; ++b) {
+        int Pb = lengths[b] - c->I - c->H + 1;
+        if (Pb > 0) n += (double)Pb;
+    }
+    return n * c->hidden * c->n_blocks;
+}
+
 int eso_forward(const eso_config *cfg, const double *y, const int32_t *lengths,
                 const double *es_params, const double *weights,
                 eso_tape *tape, double *loss, double *forecasts)
@@ -319,8 +346,8 @@ int eso_forward(const eso_config *cfg, const double *y, const int32_t *lengths,
     if (make_plan(cfg, &pl)) return 1;
     for (int b = 0; b < cfg->B; ++b)
         if (lengths[b] < cfg->I + cfg->H || lengths[b] > cfg->T) return 2;
-    double total_pin = 0.0, total_lv = 0.0;
-#pragma omp parallel for schedule(dynamic, 1) reduction(+ : total_pin, total_lv)
+    double total_pin = 0.0, total_lv = 0.0, total_cs = 0.0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : total_pin, total_lv, total_cs)
     for (int b = 0; b < cfg->B; ++b) {
         const int len = lengths[b];
         double sp, sl;
@@ -330,12 +357,16 @@ int eso_forward(const eso_config *cfg, const double *y, const int32_t *lengths,
         loss_series(cfg, &pl, b, len, tape, &sp, &sl, forecasts);
         total_pin += sp;
         total_lv += sl;
+        if (cfg->lambda_c != 0.0) total_cs += cell_state_sumsq(cfg, &pl, b, len - cfg->I - cfg->H + 1, tape);
     }
     loss_counts(cfg, lengths, &tape->n_pin, &tape->n_lv);
     tape->sum_pin = total_pin;
     tape->sum_lv = total_lv;
     double L = total_pin / tape->n_pin;
     if (cfg->lambda_lv != 0.0 && tape->n_lv > 0.0) L += cfg->lambda_lv * total_lv / tape->n_lv;
+    tape->sum_cs = total_cs;
+    tape->n_cs = cell_state_count(cfg, lengths);
+    if (cfg->lambda_c != 0.0 && tape->n_cs > 0.0) L += cfg->lambda_c * total_cs / tape->n_cs;
     *loss = L;
     return 0;
 }
@@ -348,7 +379,7 @@ int eso_forward(const eso_config *cfg, const double *y, const int32_t *lengths,
  * output, then linear layer, tanh layer, residual blocks and the LSTM layers
  * back through the window positions.  gw accumulates weight gradients. */
 static void network_backward_series(const eso_config *c, const plan_t *pl, int b, int Pb,
-                                    const double *w, const eso_tape *tp, double n_pin,
+                                    const double *w, const eso_tape *tp, double n_pin, double n_cs,
                                     double *gO, double *gR, double *gX, double *gw)
 {
     const int h = c->hidden, P = pl->P, H = c->H, B = c->B, Iw = c->I + c->n_cat;
@@ -429,6 +460,9 @@ static void network_backward_series(const eso_config *c, const plan_t *pl, int b
                 double dh = g_h[(int64_t)p * h + j] + dh_rec[(int64_t)p * h + j];
                 double tc = tanh(C[(int64_t)p * h + j]);
                 double dc = dc_rec[(int64_t)p * h + j] + dh * go * (1.0 - tc * tc);
+                /* cell-state penalty of a block's first layer: d/dc of lambda_c * c^2 / n_cs */
+                if (c->lambda_c != 0.0 && pl->first_in_block[layer] && n_cs > 0.0)
+                    dc += 2.0 * c->lambda_c * C[(int64_t)p * h + j] / n_cs;
                 double cp = cprev ? cprev[j] : 0.0;
                 dgate[0 * h + j] = dc * gg * gi * (1.0 - gi);
                 dgate[1 * h + j] = dc * cp * gf * (1.0 - gf);
@@ -585,6 +619,7 @@ int eso_backward(const eso_config *cfg, const double *y, const int32_t *lengths,
     const int P = pl.P, h = cfg->hidden, T = cfg->T, I = cfg->I, H = cfg->H, Iw = cfg->I + cfg->n_cat;
     double n_pin, n_lv;
     loss_counts(cfg, lengths, &n_pin, &n_lv);
+    const double n_cs = cell_state_count(cfg, lengths);
     memset(grad_weights, 0, sizeof(double) * pl.n_weights);
     int nthreads = eso_max_threads();
     double *gw_all = (double *)calloc((size_t)nthreads * pl.n_weights, sizeof(double));
@@ -605,7 +640,7 @@ int eso_backward(const eso_config *cfg, const double *y, const int32_t *lengths,
 #pragma omp for schedule(dynamic, 1)
         for (int b = 0; b < cfg->B; ++b) {
             const int len = lengths[b];
-            network_backward_series(cfg, &pl, b, len - I - H + 1, weights, tape, n_pin, gO, gR, gX, gw);
+            network_backward_series(cfg, &pl, b, len - I - H + 1, weights, tape, n_pin, n_cs, gO, gR, gX, gw);
             window_backward_series(cfg, &pl, b, len, tape, gX, gO, n_lv, gu, gv);
             es_backward_series(cfg, &pl, b, len, y, es_params, tape, gu, gv, grad_es_params);
             if (adj) {

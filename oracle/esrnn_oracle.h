@@ -17,7 +17,8 @@
  *   - Section 3.4: tanh layer followed by a linear layer.
  *   - Section 3.5: masking of padded outputs and the pinball loss.
  *   - Section 8.2 (multiple seasonality, no seasonality) and Section 8.4
- *     (penalty on changes of the level).
+ *     (penalty on changes of the level; penalty on the squared cell state of
+ *     the first layer of every block).
  *   - Section 3.3: per-series smoothing coefficients and initial seasonality
  *     are trained jointly with the network, hence the reverse sweep through
  *     the smoothing recursions.
@@ -63,6 +64,7 @@ typedef struct {
     int32_t n_cat;            /* 0: none; else the network input is the window followed by a one-hot block of
                                  this many entries for the series' category (Section 5.3) */
     const int32_t *categories; /* [B], values in [0, n_cat); NULL if n_cat == 0 */
+    double lambda_c;          /* weight of the cell-state penalty (Section 8.4, second kind); 0 disables it */
 } eso_config;
 
 /* Forward intermediates; every array is caller-allocated and series-major.
@@ -79,6 +81,7 @@ typedef struct {
     double *a;                        /* [B][P][h] tanh layer */
     double *o;                        /* [B][P][H] head output */
     double sum_pin, sum_lv, n_pin, n_lv;
+    double sum_cs, n_cs;              /* cell-state penalty: sum of squares and number of terms */
 } eso_tape;
 
 /* Reverse-mode intermediates (any pointer may be NULL). */

@@ -32,13 +32,14 @@ class _Config(C.Structure):
         ("tau", C.c_double), ("lambda_lv", C.c_double),
         ("n_pin", C.c_double), ("n_lv", C.c_double),
         ("n_cat", C.c_int32), ("categories", C.POINTER(C.c_int32)),
+        ("lambda_c", C.c_double),
     ]
 
 
 class _Tape(C.Structure):
     _fields_ = [(n, _dp) for n in ("alpha", "gamma1", "gamma2", "l", "S1", "S2", "u", "v",
                                    "X", "Z", "gates", "c", "h", "blk", "a", "o")] + \
-               [(n, C.c_double) for n in ("sum_pin", "sum_lv", "n_pin", "n_lv")]
+               [(n, C.c_double) for n in ("sum_pin", "sum_lv", "n_pin", "n_lv", "sum_cs", "n_cs")]
 
 
 class _Adjoint(C.Structure):
@@ -75,6 +76,7 @@ def set_num_threads(n: int) -> None:
 def _c_config(cfg, n_pin=0.0, n_lv=0.0, B=None, categories=None) -> _Config:
     c = _Config()
     c.n_cat = int(getattr(cfg, "n_cat", 0))
+    c.lambda_c = float(getattr(cfg, "lambda_c", 0.0))
     if c.n_cat > 0:
         if categories is None:
             raise ValueError("oracle: this configuration needs the categories of the series")
@@ -147,6 +149,7 @@ def forward(cfg, y, lengths, es_params, weights, n_pin=0.0, n_lv=0.0, want_forec
         raise ValueError(f"oracle forward failed with code {rc}")
     r.loss = loss.value
     r.sum_pin, r.sum_lv, r.n_pin, r.n_lv = tape.sum_pin, tape.sum_lv, tape.n_pin, tape.n_lv
+    r.sum_cs, r.n_cs = tape.sum_cs, tape.n_cs
     r._tape, r._cc = tape, cc
     r._inputs = (y, lengths, es_params, weights)
     r.P, r.K, r.n_layers = P, K, nl

@@ -39,6 +39,7 @@ class Config:
     tau: float = 0.48
     lambda_lv: float = 50.0
     param_space: int = PARAMS_DIRECT
+    lambda_c: float = 0.0   # weight of the cell-state penalty (Section 8.4); 0: none
     n_cat: int = 0     # series categories fed to the network as a one-hot block after the input window (Section 5.3); 0: none
     # generator knobs (standard deviations; see make_inputs)
     step_mu: float = 0.0
