@@ -78,6 +78,9 @@ typedef struct {
     int32_t n_categories;     /* 0: none; else the network input is the window followed by a one-hot block of this
                                  many entries for the series' category (Section 5.3; the paper's data has 6), and the
                                  first layer's W is [4*hidden][I + n_categories + hidden].  See esrnn_set_categories */
+    float lambda_cs;          /* weight of the cell-state penalty (Section 8.4: the average squared cell state of the
+                                 first layer of every block, over valid window positions, units and those layers);
+                                 0 disables it */
 } esrnn_config;
 
 typedef struct esrnn_handle esrnn_handle;
@@ -119,7 +122,8 @@ const char *esrnn_status_string(esrnn_status s);
  *   workspace  >= esrnn_workspace_bytes, 256-byte aligned; afterwards holds
  *              everything esrnn_backward needs.
  *   loss       one float: mean pinball loss over unmasked outputs + lambda_lv *
- *              mean squared second difference of the log level.
+ *              mean squared second difference of the log level + lambda_cs * mean
+ *              squared cell state of the first layer of every block.
  *   forecasts  [P][B][H] with P = T - I - H + 1, original scale, zero where the
  *              window does not fit into the series; may be NULL.
  */

@@ -34,6 +34,7 @@ class EsrnnConfig(C.Structure):
         ("tau", C.c_float), ("lambda_lv", C.c_float),
         ("param_space", C.c_int32),
         ("n_categories", C.c_int32),
+        ("lambda_cs", C.c_float),
     ]
 
 
@@ -125,6 +126,7 @@ def make_config(cfg) -> EsrnnConfig:
     c.tau, c.lambda_lv = float(cfg.tau), float(cfg.lambda_lv)
     c.param_space = int(cfg.param_space)
     c.n_categories = int(getattr(cfg, "n_cat", 0))
+    c.lambda_cs = float(getattr(cfg, "lambda_c", 0.0))
     return c
 
 

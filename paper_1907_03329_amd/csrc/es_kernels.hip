@@ -19,6 +19,7 @@ struct PrepArgs {
     const int32_t *lengths;
     Scalars *sc;
     int B, T, I, H;
+    int cs_per_window;   // cell-state values per valid window in the cell-state penalty: hidden * blocks
 };
 
 __device__ void prep_body(const PrepArgs &pa)
@@ -57,6 +58,8 @@ __device__ void prep_body(const PrepArgs &pa)
     if (threadIdx.x == 0) {
         sc->inv_n_pin = s_pin[0] > 0.0 ? (float)(1.0 / s_pin[0]) : 0.0f;
         sc->inv_n_lv = s_lv[0] > 0.0 ? (float)(1.0 / s_lv[0]) : 0.0f;
+        const double n_cs = s_pin[0] / (double)H * (double)pa.cs_per_window;   // valid windows x hidden x blocks
+        sc->inv_n_cs = n_cs > 0.0 ? (float)(1.0 / n_cs) : 0.0f;
     }
 }
 
@@ -360,24 +363,30 @@ __global__ void __launch_bounds__(256) window_forward_kernel(const float *__rest
 // loss = pinball_sum / n_pin + lambda * level_sum / n_lv.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) loss_finalize_kernel(const float *__restrict__ partial, int n_pin_parts, int n_lv_parts,
-                                                             const Scalars *__restrict__ sc, float lambda, float *__restrict__ loss)
+                                                             const float *__restrict__ cs_partial, int n_cs_parts,
+                                                             const Scalars *__restrict__ sc, float lambda, float lambda_cs,
+                                                             float *__restrict__ loss)
 {
-    __shared__ double s_a[256], s_b[256];
-    double a = 0.0, b = 0.0;
+    __shared__ double s_a[256], s_b[256], s_c[256];
+    double a = 0.0, b = 0.0, c = 0.0;
     for (int i = threadIdx.x; i < n_pin_parts; i += 256) a += (double)partial[i];
     for (int i = threadIdx.x; i < n_lv_parts; i += 256) b += (double)partial[n_pin_parts + i];
+    for (int i = threadIdx.x; i < n_cs_parts; i += 256) c += (double)cs_partial[i];
     s_a[threadIdx.x] = a;
     s_b[threadIdx.x] = b;
+    s_c[threadIdx.x] = c;
     __syncthreads();
     for (int off = 128; off >= 1; off >>= 1) {
         if ((int)threadIdx.x < off) {
             s_a[threadIdx.x] += s_a[threadIdx.x + off];
             s_b[threadIdx.x] += s_b[threadIdx.x + off];
+            s_c[threadIdx.x] += s_c[threadIdx.x + off];
         }
         __syncthreads();
     }
     if (threadIdx.x == 0)
-        *loss = (float)(s_a[0] * (double)sc->inv_n_pin + (double)lambda * s_b[0] * (double)sc->inv_n_lv);
+        *loss = (float)(s_a[0] * (double)sc->inv_n_pin + (double)lambda * s_b[0] * (double)sc->inv_n_lv +
+                        (double)lambda_cs * s_c[0] * (double)sc->inv_n_cs);
 }
 
 // ---------------------------------------------------------------------------
@@ -736,7 +745,8 @@ hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *wei
     SetupArgs a{};
     a.L = pl.L;
     a.pack = weights != nullptr;
-    a.prep = PrepArgs{lengths, reinterpret_cast<Scalars *>(ws + pl.scalars), pl.B, pl.T, pl.I, pl.H};
+    a.prep = PrepArgs{lengths, reinterpret_cast<Scalars *>(ws + pl.scalars), pl.B, pl.T, pl.I, pl.H,
+                      pl.h * pl.cfg.n_blocks};
     if (!a.pack) {
         setup_kernel<<<dim3(1, 1, 1), 256, 0, st>>>(a);
         return hipGetLastError();
@@ -795,7 +805,9 @@ hipError_t launch_window_forward(const Plan &pl, const int32_t *categories, floa
 hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStream_t st)
 {
     loss_finalize_kernel<<<1, 256, 0, st>>>(ws + pl.loss_partial, pl.n_loss_partial - pl.es_blocks, pl.es_blocks,
-                                            reinterpret_cast<const Scalars *>(ws + pl.scalars), pl.cfg.lambda_lv, loss);
+                                            ws + pl.cs_partial, pl.n_cs_partial,
+                                            reinterpret_cast<const Scalars *>(ws + pl.scalars), pl.cfg.lambda_lv,
+                                            pl.cfg.lambda_cs, loss);
     return hipGetLastError();
 }
 

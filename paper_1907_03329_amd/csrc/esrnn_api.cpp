@@ -165,7 +165,7 @@ esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengt
     ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, lengths, es_params, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, h->categories, ws, st); }));
     for (int l = 0; l < pl.L; ++l)
-        ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ws, st); }));
+        ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, lengths, ws, st); }));
     // the output stage runs its reverse pass in the same launch: the loss gradient needs nothing beyond it
     ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, lengths, ws, forecasts, st); }));
     ESRNN_TRY(run_stage(h, h->st_loss, st, [&] { return launch_loss_finalize(pl, ws, loss, st); }));
@@ -185,7 +185,7 @@ esrnn_status esrnn_backward(esrnn_handle *h, const float *y, const int32_t *leng
     float *ws = static_cast<float *>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     for (int l = pl.L - 1; l >= 0; --l)
-        ESRNN_TRY(run_stage(h, h->st_lstm_bwd[l], st, [&] { return launch_lstm_backward(pl, l, ws, st); }));
+        ESRNN_TRY(run_stage(h, h->st_lstm_bwd[l], st, [&] { return launch_lstm_backward(pl, l, lengths, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_win_bwd, st, [&] { return launch_window_backward(pl, lengths, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_es_bwd, st,
                         [&] { return launch_es_backward(pl, y, lengths, es_params, ws, grad_es_params, st); }));
@@ -228,7 +228,7 @@ esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengt
     ESRNN_TRY(run_stage(h, h->st_es_fwd, st, [&] { return launch_es_forward(pl, y, ext, es_params, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, h->categories, ws, st); }));
     for (int l = 0; l < pl.L; ++l)
-        ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ws, st); }));
+        ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ext, ws, st); }));
     ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, ext, ws, nullptr, st); }));
     ESRNN_TRY(run_stage(h, h->st_tail, st, [&] { return launch_forecast_tail(pl, lengths, ws, forecasts, st); }));
     return ESRNN_OK;

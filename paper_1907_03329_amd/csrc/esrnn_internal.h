@@ -41,6 +41,7 @@ struct LayerPlan {
     size_t dw_partial;   // [NB*chains][HT*MB][4][64] per-workgroup weight-gradient tiles
     size_t db_partial;   // [NB*chains][HT][4][4]
     size_t dw_reduced, db_reduced;   // [kReduceSplits][...] first reduction stage
+    size_t cs_partial;   // [NB*chains] sums of squared cell states (first layer of a block, penalty on)
 };
 
 struct Plan {
@@ -70,6 +71,7 @@ struct Plan {
     size_t gsum;                        // TL(HP) sum of gradient sources (three or more blocks only)
     size_t head_fwd_pack, head_bwd_pack; // packed head operands
     size_t loss_partial; int n_loss_partial;   // [head_blocks] pinball sums, then [es_blocks] level-penalty sums
+    size_t cs_partial; int n_cs_partial;       // sums of squared cell states of all penalised layers, contiguous
     int head_blocks;                           // workgroups of the output-stage kernel
     size_t head_dw_partial; int n_head_waves;  // [n_head_waves][head_dw_stride]; 4 waves per workgroup
     int head_dw_stride;
@@ -83,6 +85,7 @@ struct Plan {
 struct Scalars {
     float inv_n_pin;   // 1 / number of unmasked head outputs
     float inv_n_lv;    // 1 / number of second differences of the log level (0 if none)
+    float inv_n_cs;    // 1 / number of cell-state values in the cell-state penalty (0 if none)
 };
 
 // offsets inside the packed head operand blocks (floats), filled by plan.cpp
@@ -102,12 +105,12 @@ hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *wei
 hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,
                              float *ws, hipStream_t st);
 hipError_t launch_window_forward(const Plan &pl, const int32_t *categories, float *ws, hipStream_t st);
-hipError_t launch_lstm_forward(const Plan &pl, int layer, float *ws, hipStream_t st);
+hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
 // output stage, forward and reverse in one launch (needs the loss normalisers of launch_setup)
 hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st);
 hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStream_t st);
 
-hipError_t launch_lstm_backward(const Plan &pl, int layer, float *ws, hipStream_t st);
+hipError_t launch_lstm_backward(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
 hipError_t launch_window_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
 hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,
                               float *ws, float *grad_es, hipStream_t st);

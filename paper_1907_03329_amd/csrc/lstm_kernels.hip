@@ -31,9 +31,13 @@ struct LstmFwdArgs {
     const float *resid;   // TL(HP) or null
     float *out;           // TL(HP) or null: resid + hid
     int P, NB, d;
+    // cell-state penalty (Section 8.4) of a block's first layer, kernels instantiated with CP only
+    const int32_t *lengths;
+    float *cs_partial;    // [NB * gridDim.y] sums of squared cell states over valid window positions
+    int B, T, I, H;
 };
 
-template <int HT, int KXT>
+template <int HT, int KXT, bool CP>
 __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFwdArgs a)
 {
     constexpr int KT = KXT + HT;
@@ -56,6 +60,14 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         bias[j] = f32x4{bv.x, bv.y, bv.z, bv.w};
     }
     const size_t xtile = (size_t)KXT * 64;
+    // positions below this take part in the loss for this lane's series (CP only)
+    int n_valid = 0;
+    float csq = 0.0f;
+    if constexpr (CP) {
+        const int col = bt * kTileN + (lane & 15);
+        const int len = col < a.B ? min(max(a.lengths[col], 0), a.T) : 0;
+        n_valid = len - a.I - a.H + 1;
+    }
 
     for (int r = blockIdx.y; r < a.d && r < a.P; r += gridDim.y) {
         // start of a chain: zero state
@@ -117,6 +129,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                     const float cn = gf * creg[j] + gi * gg;
                     const float hn = go * tanh_f(cn);
                     creg[j] = cn;
+                    if constexpr (CP) csq += p < n_valid ? cn * cn : 0.0f;
                     hn_buf[mt * 64 + lane] = hn;
                     const size_t tile = (pb * HT + mt) * 64;   // wave-uniform: scalar address arithmetic
                     // gates are read again only by the reverse pass: streaming stores
@@ -146,6 +159,14 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
             }
             lds_barrier();
         }
+    }
+    if constexpr (CP) {
+        __shared__ float s_cs[kLstmWaves];
+        const float tot = wave_sum(csq);
+        if (lane == 0) s_cs[s] = tot;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            a.cs_partial[blockIdx.x * gridDim.y + blockIdx.y] = (s_cs[0] + s_cs[1]) + (s_cs[2] + s_cs[3]);
     }
 }
 
@@ -181,9 +202,14 @@ struct LstmBwdArgs {
     float *dw_partial;    // [NB*chains][HT*MB][4][64]
     float *db_partial;    // [NB*chains][HT][4][4]
     int P, NB, d;
+    // cell-state penalty (Section 8.4) of a block's first layer, kernels instantiated with CP only
+    const int32_t *lengths;
+    const Scalars *sc;
+    float two_lambda_cs;
+    int B, T, I, H;
 };
 
-template <int HT, int KXT>
+template <int HT, int KXT, bool CP>
 __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_backward_kernel(LstmBwdArgs a)
 {
     constexpr int W = kLstmWaves;
@@ -264,14 +290,24 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     };
 
     const float g2_scale = a.n_gsrc >= 2 ? 1.0f : 0.0f;
+    // d/dc of lambda * c^2 / n over the valid window positions of this lane's series (CP only)
+    int n_valid = 0;
+    float pen = 0.0f;
+    if constexpr (CP) {
+        const int col = bt * kTileN + n;
+        const int len = col < a.B ? min(max(a.lengths[col], 0), a.T) : 0;
+        n_valid = len - a.I - a.H + 1;
+        pen = a.two_lambda_cs * a.sc->inv_n_cs;
+    }
     float dcreg[MTW], dhreg[MTW];
     float da[MTW][4];
     // ---- step A, tile j of the fetched position: gate gradients to registers and LDS
-    auto step_a_tile = [&](int j, bool has_prev) {
+    auto step_a_tile = [&](int j, bool has_prev, int p_cur) {
         const float4 gt = pf_gt[j];
         const float dh = pf_g[j] + g2_scale * pf_g2[j] + dhreg[j];
         const float tc = tanh_f(pf_c[j]);
-        const float dc = dcreg[j] + dh * gt.w * (1.0f - tc * tc);
+        float dc = dcreg[j] + dh * gt.w * (1.0f - tc * tc);
+        if constexpr (CP) dc += p_cur < n_valid ? pen * pf_c[j] : 0.0f;
         const float cp = has_prev ? pf_cp[j] : 0.0f;
         da[j][0] = dc * gt.z * gt.x * (1.0f - gt.x);
         da[j][1] = dc * cp * gt.y * (1.0f - gt.y);
@@ -370,7 +406,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
         fetch(p_last);
         store_xh(p_last >= a.d);
 #pragma unroll
-        for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d);
+        for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d, p_last);
         fetch(max(p_last - a.d, r0));
         step_b();
 
@@ -382,10 +418,10 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             store_xh(has_prev);
 #pragma unroll
             for (int j = 0; j < MTW - 1; ++j) {
-                step_a_tile(j, has_prev);
+                step_a_tile(j, has_prev, p - a.d);
                 dw_row(j);
             }
-            step_a_tile(MTW - 1, has_prev);
+            step_a_tile(MTW - 1, has_prev, p - a.d);
             if (kDxLate) store_dx(p);
             fetch(max(p - 2 * a.d, r0));
             if (last_row_valid) dw_row(MTW - 1);
@@ -442,14 +478,16 @@ __global__ void __launch_bounds__(256) sum_sources_kernel(const float4 *__restri
 template <int HT, int KXT>
 hipError_t run_fwd(const LstmFwdArgs &a, int chains, hipStream_t st)
 {
-    lstm_forward_kernel<HT, KXT><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
+    if (a.cs_partial) lstm_forward_kernel<HT, KXT, true><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
+    else lstm_forward_kernel<HT, KXT, false><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
     return hipGetLastError();
 }
 
 template <int HT, int KXT>
 hipError_t run_bwd(const LstmBwdArgs &a, int chains, hipStream_t st)
 {
-    lstm_backward_kernel<HT, KXT><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
+    if (a.sc) lstm_backward_kernel<HT, KXT, true><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
+    else lstm_backward_kernel<HT, KXT, false><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -458,21 +496,28 @@ hipError_t run_bwd(const LstmBwdArgs &a, int chains, hipStream_t st)
 
 }  // namespace
 
-hipError_t launch_lstm_forward(const Plan &pl, int layer, float *ws, hipStream_t st)
+hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st)
 {
     const LayerPlan &lp = pl.layer[layer];
+    const bool cp = lp.first_in_block && pl.cfg.lambda_cs != 0.0f;
     LstmFwdArgs a{ws + lp.wpack_fwd, ws + lp.bias_pack, ws + lp.xsrc, ws + lp.gates, ws + lp.c, ws + lp.hid,
-                  lp.out ? ws + lp.resid : nullptr, lp.out ? ws + lp.out : nullptr, pl.P, pl.NB, lp.dil};
+                  lp.out ? ws + lp.resid : nullptr, lp.out ? ws + lp.out : nullptr, pl.P, pl.NB, lp.dil,
+                  lengths, cp ? ws + lp.cs_partial : nullptr, pl.B, pl.T, pl.I, pl.H};
 #define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_fwd<HT_, KXT_>(a, lp.chains, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_lstm_backward(const Plan &pl, int layer, float *ws, hipStream_t st)
+hipError_t launch_lstm_backward(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st)
 {
     const LayerPlan &lp = pl.layer[layer];
     LstmBwdArgs a{};
+    const bool cp = lp.first_in_block && pl.cfg.lambda_cs != 0.0f;
+    a.lengths = lengths;
+    a.sc = cp ? reinterpret_cast<const Scalars *>(ws + pl.scalars) : nullptr;
+    a.two_lambda_cs = 2.0f * pl.cfg.lambda_cs;
+    a.B = pl.B; a.T = pl.T; a.I = pl.I; a.H = pl.H;
     a.wpack = ws + lp.wpack_bwd; a.xsrc = ws + lp.xsrc; a.gates = ws + lp.gates; a.c = ws + lp.c; a.hid = ws + lp.hid;
     a.n_gsrc = lp.n_gsrc < 2 ? lp.n_gsrc : 2;
     a.gsrc[0] = ws + lp.gsrc[0];

@@ -71,6 +71,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     if (cfg.n_blocks < 1 || cfg.n_blocks > ESRNN_MAX_BLOCKS) return ESRNN_ERR_CONFIG;
     if (!(cfg.tau > 0.0f && cfg.tau < 1.0f)) return ESRNN_ERR_CONFIG;
     if (!(cfg.lambda_lv >= 0.0f)) return ESRNN_ERR_CONFIG;
+    if (!(cfg.lambda_cs >= 0.0f)) return ESRNN_ERR_CONFIG;
     if (cfg.param_space != ESRNN_PARAMS_DIRECT && cfg.param_space != ESRNN_PARAMS_LOGIT) return ESRNN_ERR_CONFIG;
     if ((long long)cfg.B * cfg.T > (1LL << 30)) return ESRNN_ERR_CONFIG;
     if (cfg.n_categories < 0 || cfg.n_categories > ESRNN_MAX_CATEGORIES) return ESRNN_ERR_CONFIG;
@@ -177,6 +178,17 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         lp.db_reduced = ws.take((size_t)kReduceSplits * pl.HT * 16);
         pl.dx[l] = l > 0 ? ws.take(PN * tileH) : pl.gX;
     }
+    // cell-state penalty: one partial sum per forward workgroup of every block's first layer, contiguous
+    pl.cs_partial = ws.at;
+    pl.n_cs_partial = 0;
+    if (cfg.lambda_cs != 0.0f)
+        for (int l = 0; l < L; ++l) {
+            LayerPlan &lp = pl.layer[l];
+            if (!lp.first_in_block) continue;
+            lp.cs_partial = pl.cs_partial + pl.n_cs_partial;
+            pl.n_cs_partial += pl.NB * lp.chains;
+        }
+    ws.take((size_t)pl.n_cs_partial);
     // block outputs: block 0's is the hidden state of its last layer
     for (int l = 0; l < L; ++l) {
         LayerPlan &lp = pl.layer[l];

@@ -39,7 +39,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_config_struct_matches_header_size(lib):
     # 9 int32 + 4 + 16 int32 + 2 float + 1 int32
-    assert C.sizeof(binding.EsrnnConfig) == 4 * (9 + 4 + 16 + 2 + 1 + 1)
+    assert C.sizeof(binding.EsrnnConfig) == 4 * (9 + 4 + 16 + 2 + 1 + 1 + 1)
 
 
 @pytest.mark.parametrize("name", synth.CONFIG_ORDER)
