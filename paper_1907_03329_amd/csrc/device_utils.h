@@ -24,6 +24,10 @@ __device__ __forceinline__ void lds_barrier()
 
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 
+// Natural logarithm of a normal positive number (series values, levels and seasonal factors are far from
+// the denormal range): the hardware log2 without the rescaling path for denormals.
+__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * 0.69314718055994531f; }
+
 __device__ __forceinline__ float sigmoid_f(float x)
 {
     return fast_rcp(1.0f + __expf(-x));

@@ -279,8 +279,8 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
             }
         }
         s1_cur = s1_nxt; s2_cur = s2_nxt;
-        const float ut = live ? __logf(lt) : 0.0f;
-        const float vt = live ? __logf(q) : 0.0f;      // ln y - ln(S1 S2)
+        const float ut = live ? fast_log(lt) : 0.0f;
+        const float vt = live ? fast_log(q) : 0.0f;      // ln y - ln(S1 S2)
         const int o = t * row_stride;
         lvl_b[o] = live ? lt : 1.0f;
         u_b[o] = ut;

@@ -248,7 +248,7 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int q = 4 * ma + r;
-                const float rv = q < HT ? cur.br[q < HT ? q : 0] : 0.0f;   // rows past HT are padding
+                const float rv = q < HT ? cur.br[q < HT ? q : HT - 1] : 0.0f;   // unit tiles past HT are padding (the index stays in range)
                 dp[q] = acc[ma][r] * (1.0f - av[q] * av[q]);
                 dba[q] += dp[q];
                 const int row = 4 * q + g;
