@@ -115,29 +115,42 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
 #pragma unroll
             for (int ks = 0; ks < HT; ++ks) bh[ks] = hb[ks * 64 + lane];
             float *hn_buf = hbuf[(it + 1) & 1];
-            // tile by tile: the activations of one tile overlap the MFMAs of the next
+            // Tile by tile, one tile ahead on the matrix pipe: the MFMAs of tile j+1 are issued before the
+            // activations of tile j, whose accumulator is complete by then (no drain of the pipe per tile).
+            auto tile_mfma = [&](int j) {
+#pragma unroll
+                for (int ks = 0; ks < HT; ++ks) acc[j] = mfma16(wreg[j][KXT + ks], bh[ks], acc[j]);
+            };
+            auto tile_act = [&](int j) {
+                const int mt = s + kLstmWaves * j;
+                const float gi = sigmoid_f(acc[j][0]);
+                const float gf = sigmoid_f(acc[j][1]);
+                const float gg = tanh_f(acc[j][2]);
+                const float go = sigmoid_f(acc[j][3]);
+                const float cn = gf * creg[j] + gi * gg;
+                const float hn = go * tanh_f(cn);
+                creg[j] = cn;
+                if constexpr (CP) csq += p < n_valid ? cn * cn : 0.0f;
+                hn_buf[mt * 64 + lane] = hn;
+                const size_t tile = (pb * HT + mt) * 64;   // wave-uniform: scalar address arithmetic
+                // gates are read again only by the reverse pass: streaming stores
+                __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + tile + lane);
+                __builtin_nontemporal_store(cn, a.c + tile + lane);
+                (a.hid + tile)[lane] = hn;
+                if (a.out) (a.out + tile)[lane] = res[j] + hn;
+            };
+            const bool last_tile = s + kLstmWaves * (MTW - 1) < HT;   // this wave's last tile exists
+            // (with a one-tile input, KXT = 1, the plain order measured faster and is kept)
+            constexpr bool kAhead = KXT >= 2;
+            if (kAhead) tile_mfma(0);
 #pragma unroll
             for (int j = 0; j < MTW; ++j) {
-                const int mt = s + kLstmWaves * j;
-                if (j < MTW - 1 || mt < HT) {
-#pragma unroll
-                    for (int ks = 0; ks < HT; ++ks) acc[j] = mfma16(wreg[j][KXT + ks], bh[ks], acc[j]);
-                    const float gi = sigmoid_f(acc[j][0]);
-                    const float gf = sigmoid_f(acc[j][1]);
-                    const float gg = tanh_f(acc[j][2]);
-                    const float go = sigmoid_f(acc[j][3]);
-                    const float cn = gf * creg[j] + gi * gg;
-                    const float hn = go * tanh_f(cn);
-                    creg[j] = cn;
-                    if constexpr (CP) csq += p < n_valid ? cn * cn : 0.0f;
-                    hn_buf[mt * 64 + lane] = hn;
-                    const size_t tile = (pb * HT + mt) * 64;   // wave-uniform: scalar address arithmetic
-                    // gates are read again only by the reverse pass: streaming stores
-                    __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + tile + lane);
-                    __builtin_nontemporal_store(cn, a.c + tile + lane);
-                    (a.hid + tile)[lane] = hn;
-                    if (a.out) (a.out + tile)[lane] = res[j] + hn;
+                if (kAhead) {
+                    if (j + 1 < MTW - 1 || (j + 1 == MTW - 1 && last_tile)) tile_mfma(j + 1);
+                } else {
+                    if (j < MTW - 1 || last_tile) tile_mfma(j);
                 }
+                if (j < MTW - 1 || last_tile) tile_act(j);
             }
             // input part of the next position of the chain: independent of the
             // recurrence, so it runs on the matrix pipe while the waves meet at
