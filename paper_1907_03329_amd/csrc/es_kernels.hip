@@ -351,10 +351,13 @@ __global__ void __launch_bounds__(256) window_forward_kernel(const float *__rest
         const int t = p + I - 1;
         const float ut = u[(size_t)t * Bp + col];
         float *xo = X + tile * xrows * 16 + lane;
+        // streaming stores: the tiles are consumed by later kernels, not by this one
         for (int r = g; r < xrows; r += 4)
-            xo[(r - g) * 16] = (r < I) ? v[(size_t)(p + r) * Bp + col] - ut : (r == hot ? 1.0f : 0.0f);
+            __builtin_nontemporal_store((r < I) ? v[(size_t)(p + r) * Bp + col] - ut : (r == hot ? 1.0f : 0.0f),
+                                        xo + (r - g) * 16);
         float *zo = Z + tile * zrows * 16 + lane;
-        for (int r = g; r < zrows; r += 4) zo[(r - g) * 16] = (r < H) ? v[(size_t)(t + 1 + r) * Bp + col] - ut : 0.0f;
+        for (int r = g; r < zrows; r += 4)
+            __builtin_nontemporal_store((r < H) ? v[(size_t)(t + 1 + r) * Bp + col] - ut : 0.0f, zo + (r - g) * 16);
     }
 }
 
