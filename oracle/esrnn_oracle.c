@@ -397,7 +397,14 @@ static void network_backward_series(const eso_config *c, const plan_t *pl, int b
         for (int j = 0; j < H; ++j) {
             double d = Z[p * H + j] - O[p * H + j];
             /* rho = tau*d (d >= 0) or (tau-1)*d; d = z - o */
-            gO[p * H + j] = ((d >= 0.0) ? -c->tau : (1.0 - c->tau)) / n_pin;
+            int right = (d >= 0.0);
+            /* kink of the loss: the caller may name the one-sided derivative to take (see eso_config) */
+            if (c->pin_side) {
+                const int8_t side = c->pin_side[((int64_t)b * P + p) * H + j];
+                if (side > 0) right = 1;
+                if (side < 0) right = 0;
+            }
+            gO[p * H + j] = (right ? -c->tau : (1.0 - c->tau)) / n_pin;
         }
         for (int q = 0; q < h; ++q) da[q] = 0.0;
         for (int j = 0; j < H; ++j) {

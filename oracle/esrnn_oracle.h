@@ -65,6 +65,13 @@ typedef struct {
                                  this many entries for the series' category (Section 5.3) */
     const int32_t *categories; /* [B], values in [0, n_cat); NULL if n_cat == 0 */
     double lambda_c;          /* weight of the cell-state penalty (Section 8.4, second kind); 0 disables it */
+    const int8_t *pin_side;   /* NULL, or [B][P][H]: which one-sided derivative of the pinball loss (Section 3.5)
+                                 eso_backward takes at an output.  0: the side the sign of target - output
+                                 gives (target == output counts as the target >= output side); +1: the
+                                 target >= output side; -1: the other side.  The loss is not differentiable
+                                 where target == output, and both one-sided values are valid results there:
+                                 a checker sets +-1 only at outputs that are equal to their targets up to the
+                                 rounding of the implementation under test.  eso_forward ignores it. */
 } eso_config;
 
 /* Forward intermediates; every array is caller-allocated and series-major.

@@ -33,6 +33,7 @@ class _Config(C.Structure):
         ("n_pin", C.c_double), ("n_lv", C.c_double),
         ("n_cat", C.c_int32), ("categories", C.POINTER(C.c_int32)),
         ("lambda_c", C.c_double),
+        ("pin_side", C.POINTER(C.c_int8)),
     ]
 
 
@@ -156,11 +157,21 @@ def forward(cfg, y, lengths, es_params, weights, n_pin=0.0, n_lv=0.0, want_forec
     return r
 
 
-def backward(cfg, fwd, want_adjoints=True):
+def backward(cfg, fwd, want_adjoints=True, pin_side=None):
     """Reverse mode for the forward result ``fwd``; returns grad_es_params
-    [K,B], grad_weights (flat) and, optionally, the adjoint intermediates."""
+    [K,B], grad_weights (flat) and, optionally, the adjoint intermediates.
+
+    ``pin_side`` (int8 [B,P,H], optional) names the one-sided derivative of the
+    pinball loss to take at outputs that sit on its kink (+1: the target >=
+    output side, -1: the other, 0: decided by the sign as usual)."""
     L_ = lib()
     y, lengths, es_params, weights = fwd._inputs
+    if pin_side is not None:
+        side = np.ascontiguousarray(pin_side, dtype=np.int8)
+        assert side.shape == (y.shape[1], fwd.P, cfg.H), side.shape
+        fwd._cc.pin_side = side.ctypes.data_as(C.POINTER(C.c_int8))
+    else:
+        fwd._cc.pin_side = None
     T, B = y.shape
     h, I, H, P = cfg.hidden, cfg.I, cfg.H, fwd.P
     g = SimpleNamespace()
@@ -179,6 +190,7 @@ def backward(cfg, fwd, want_adjoints=True):
                          _ptr(es_params), _ptr(weights), C.byref(fwd._tape),
                          C.byref(adj) if want_adjoints else None,
                          _ptr(g.grad_es_params), _ptr(g.grad_weights))
+    fwd._cc.pin_side = None      # the array above goes out of scope with this call
     if rc != 0:
         raise ValueError(f"oracle backward failed with code {rc}")
     return g

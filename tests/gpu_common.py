@@ -4,6 +4,8 @@ CPU oracle on the same seeded inputs and compare tensor by tensor.
 Tolerance convention (per tensor): max |gpu - oracle| / max |oracle|.
 Forecasts and loss must be within 1e-4, every gradient tensor within 1e-3; the
 intermediates are held to the same bounds so that a failure names its stage.
+On top of that: every forecast element by element within 1e-3, and forecasts
+(1e-4) and smoothing gradients (1e-3) normalised series by series.
 """
 from __future__ import annotations
 
@@ -90,43 +92,106 @@ def check_forward(cfg, inp, step, f, stages=True):
     fc = step.forecasts.cpu().numpy()
     chk("forecasts", fc, f.forecasts, None, TOL_FWD)
     assert np.all(fc[~wm] == 0.0), "forecasts of masked windows must be zero"
+    # element by element (forecasts are positive), and normalised by each series' own largest forecast
+    wmf = np.broadcast_to(wm[:, :, None], fc.shape)
+    e = float((np.abs(fc - f.forecasts)[wmf] / np.abs(f.forecasts)[wmf]).max()) if wmf.any() else 0.0
+    errs["forecasts_elementwise"] = e
+    assert e <= TOL_FC_ELEMENT, f"forecasts, element by element: {e:.3e} > {TOL_FC_ELEMENT:g} ({cfg.name})"
+    e = per_series_err(fc, f.forecasts, series_axis=1)
+    errs["forecasts_per_series"] = e
+    assert e <= TOL_FC_SERIES, f"forecasts, series by series: {e:.3e} > {TOL_FC_SERIES:g} ({cfg.name})"
     return errs
 
 
-def check_backward(cfg, inp, step, f, g, stages=True):
+def per_series_err(got, want, series_axis, floor_frac=0.0):
+    """Worst over the series of max |gpu - oracle| / max |oracle| taken over that series' own elements:
+    a small-scale series is held to the same relative bound as a large one.
+
+    floor_frac > 0 (gradients): a series' gradient is a sum of signed terms and its rounding error scales
+    with the terms, not with the sum, so a series whose gradient cancels to almost nothing is normalised by
+    floor_frac x the median series' scale instead of its own."""
+    got = np.moveaxis(np.asarray(got, dtype=np.float64), series_axis, 0)
+    want = np.moveaxis(np.asarray(want, dtype=np.float64), series_axis, 0)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    n = got.shape[0]
+    diff = np.abs(got - want).reshape(n, -1).max(axis=1)
+    scale = np.abs(want).reshape(n, -1).max(axis=1)
+    if floor_frac > 0.0:
+        scale = np.maximum(scale, floor_frac * np.median(scale))
+    ok = scale > 0
+    return float((diff[ok] / scale[ok]).max()) if ok.any() else 0.0
+
+
+# Bounds added to the per-tensor ones: every forecast element by element, and forecasts and smoothing
+# gradients normalised series by series (levels span an order of magnitude across the series).
+TOL_FC_ELEMENT = 1e-3
+TOL_FC_SERIES = 1e-4
+TOL_GES_SERIES = 1e-3
+
+
+def kink_sides(cfg, f, wm, gO_gpu):
+    """Outputs on the kink of the pinball loss (Section 3.5): target == output up to float32 rounding.
+
+    There the loss has two one-sided derivatives and either is a correct result.  Returns
+    (near [B,P,H] bool, side [B,P,H] int8): at a near element the GPU value must be one of the two
+    admissible values, and `side` records which (+1: the target >= output side, -1: the other), so that
+    the oracle can be asked for the gradient with the same choice; 0 elsewhere."""
+    near = np.abs(f.Z - f.o) <= 2e-6 * np.maximum(1.0, np.abs(f.Z))             # [B, P, H]
+    near &= wm.T[:, :, None]
+    side = np.zeros(near.shape, dtype=np.int8)
+    if near.any():
+        right, left = -cfg.tau / f.n_pin, (1.0 - cfg.tau) / f.n_pin
+        got = np.asarray(gO_gpu, dtype=np.float64).transpose(1, 0, 2)[near]
+        d_right, d_left = np.abs(got - right), np.abs(got - left)
+        best = np.minimum(d_right, d_left)
+        assert best.max() <= TOL_GRAD * max(abs(right), abs(left)), \
+            "loss gradient at the pinball kink is neither of the two one-sided derivatives"
+        side[near] = np.where(d_right <= d_left, 1, -1)
+    return near, side
+
+
+def check_backward(cfg, inp, step, f, g=None, stages=True, want_adjoints=None):
+    """Compare the GPU reverse pass with the oracle's, every tensor on every series.
+
+    Outputs that sit on the kink of the pinball loss are first checked against the two admissible
+    one-sided derivatives; the oracle's reverse sweep is then run with the side the GPU took at exactly
+    those outputs (its own choice everywhere else), so that nothing is left out of the comparison."""
     errs = {}
     T = cfg.T
     lengths = inp["lengths"]
     live = (np.arange(T)[:, None] < lengths[None, :])
     wm = valid_window_mask(cfg, lengths)
+    if want_adjoints is None:
+        want_adjoints = stages
 
     def chk(name, got, want, mask, tol):
         e = rel_err(got, want, mask)
         errs[name] = e
         assert e <= tol, f"{name}: relative error {e:.3e} > {tol:g} ({cfg.name})"
 
-    # At the kink of the pinball loss (target == output up to float32 rounding) either one-sided
-    # derivative is a valid result, and the choice changes that series' gradients by a visible amount.
-    # One such element moves the pinball part of its series' gradients by about 2 / (valid outputs of the
-    # series).  Series where that could exceed a fifth of the gradient tolerance are compared through the
-    # shared-weight gradients only (where one element weighs 1 / n_pin); everything per series is
-    # compared on the other series.
-    near = np.abs(f.Z - f.o) <= 2e-6 * np.maximum(1.0, np.abs(f.Z))            # [B, P, H]
-    near &= wm.T[:, :, None]
-    n_out = np.maximum(wm.sum(axis=0) * cfg.H, 1)                                # [B]
-    clean = 2.0 * near.sum(axis=(1, 2)) / n_out <= 0.2 * TOL_GRAD               # [B]
-    errs["series_at_kink"] = float((~clean).sum())
-    assert (~clean).sum() <= max(3, 0.05 * cfg.B), "implausibly many outputs at the kink of the pinball loss"
+    gO_gpu = step.buffer("grad_O").cpu().numpy()                                # [P, B, H]
+    near, side = kink_sides(cfg, f, wm, gO_gpu)
+    errs["series_at_kink"] = float(near.any(axis=(1, 2)).sum())
+    # No series is left out of any comparison below.  Plausibility only: the band is 4e-6 wide and the
+    # targets and outputs differ by about 0.1, so a few outputs in 1e5 land in it.
+    n_valid = int(wm.sum()) * cfg.H
+    assert near.sum() <= max(3, 2e-4 * n_valid), f"implausibly many outputs at the kink: {int(near.sum())} of {n_valid}"
+    own = np.where(f.Z - f.o >= 0.0, 1, -1).astype(np.int8)
+    if g is None or np.any(side[near] != own[near]) or (want_adjoints and not hasattr(g, "gO")):
+        g = oracle.backward(cfg, f, want_adjoints=want_adjoints, pin_side=side if near.any() else None)
     if stages:
-        chk("grad_O", step.buffer("grad_O").cpu().numpy(), g.gO.transpose(1, 0, 2),
-            np.broadcast_to(clean[None, :, None], (wm.shape[0], cfg.B, cfg.H)), TOL_GRAD)
-        chk("grad_top", step.buffer("grad_top").cpu().numpy(), g.gR.transpose(1, 0, 2), wm & clean[None, :], TOL_GRAD)
-        chk("grad_X", step.buffer("grad_X").cpu().numpy(), g.gX.transpose(1, 0, 2), wm & clean[None, :], TOL_GRAD)
-        chk("grad_u", step.buffer("grad_u").cpu().numpy(), g.gu.T, live & clean[None, :], TOL_GRAD)
-        chk("grad_v", step.buffer("grad_v").cpu().numpy(), g.gv.T, live & clean[None, :], TOL_GRAD)
+        full = np.ones((wm.shape[0], cfg.B, cfg.H), dtype=bool)
+        chk("grad_O", gO_gpu, g.gO.transpose(1, 0, 2), full, TOL_GRAD)
+        chk("grad_top", step.buffer("grad_top").cpu().numpy(), g.gR.transpose(1, 0, 2), wm, TOL_GRAD)
+        chk("grad_X", step.buffer("grad_X").cpu().numpy(), g.gX.transpose(1, 0, 2), wm, TOL_GRAD)
+        chk("grad_u", step.buffer("grad_u").cpu().numpy(), g.gu.T, live, TOL_GRAD)
+        chk("grad_v", step.buffer("grad_v").cpu().numpy(), g.gv.T, live, TOL_GRAD)
     ges = step.grad_es_params.cpu().numpy()
     for name, sl in synth.es_param_rows(cfg).items():
-        chk(f"grad_{name}", ges[sl][:, clean], g.grad_es_params[sl][:, clean], None, TOL_GRAD)
+        chk(f"grad_{name}", ges[sl], g.grad_es_params[sl], None, TOL_GRAD)
+    e = per_series_err(ges, g.grad_es_params, series_axis=1, floor_frac=0.1)
+    errs["grad_es_per_series"] = e
+    assert e <= TOL_GES_SERIES, f"smoothing gradients, series by series: {e:.3e} > {TOL_GES_SERIES:g} ({cfg.name})"
     gw = step.grad_weights.cpu().numpy()
     for name, off, shape in synth.weight_layout(cfg):
         n = int(np.prod(shape))
@@ -140,9 +205,8 @@ def run_and_check(cfg, seed=0, ragged=False, stages=True, mutate=None):
         mutate(inp)
     f = oracle.forward(cfg, inp["y"], inp["lengths"], inp["es_params"], inp["weights"],
                        categories=inp.get("categories"))
-    g = oracle.backward(cfg, f)
     step = run_gpu(cfg, inp)
     errs = check_forward(cfg, inp, step, f, stages)
-    errs.update(check_backward(cfg, inp, step, f, g, stages))
+    errs.update(check_backward(cfg, inp, step, f, None, stages))
     step.close()
     return errs

@@ -36,9 +36,7 @@ def test_full_size_workload(name):
     gauge_invariant(cfg, inp, step)
     f = oracle.forward(cfg, inp["y"], inp["lengths"], inp["es_params"], inp["weights"])
     errs = gc.check_forward(cfg, inp, step, f, stages=False)
-    g = oracle.backward(cfg, f, want_adjoints=False)
-    del f.gates, f.c, f.h
-    errs.update(gc.check_backward(cfg, inp, step, f, g, stages=False))
+    errs.update(gc.check_backward(cfg, inp, step, f, None, stages=False))
     kink = errs.pop("series_at_kink")
     worst = sorted(errs.items(), key=lambda kv: -kv[1])[:4]
     print(f"  {name}: {int(kink)} series with an output at the pinball kink; worst " + ", ".join(f"{k}={v:.2e}" for k, v in worst), flush=True)
