@@ -53,7 +53,8 @@ typedef enum {
     ESRNN_OK = 0,
     ESRNN_ERR_NULL = 1,       /* a required pointer is NULL */
     ESRNN_ERR_CONFIG = 2,     /* configuration outside the supported range */
-    ESRNN_ERR_WORKSPACE = 3,  /* workspace pointer misaligned (256 bytes required) */
+    ESRNN_ERR_WORKSPACE = 3,  /* workspace pointer misaligned (256 bytes required), or the built-in workspace of
+                                 esrnn_predict_static too small for this configuration */
     ESRNN_ERR_ORDER = 4,      /* esrnn_backward without a preceding esrnn_forward on the handle */
     ESRNN_ERR_HIP = 5         /* a HIP runtime call or kernel launch failed */
 } esrnn_status;
@@ -181,6 +182,22 @@ esrnn_status esrnn_adam_update(esrnn_handle *h, const esrnn_adam_config *opt, in
  */
 esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengths, const float *es_params,
                            const float *weights, void *workspace, float *forecasts, void *stream);
+
+/*
+ * esrnn_predict for callers that cannot allocate device memory and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same kernels and
+ * same results as esrnn_predict, but the workspace is an array inside the library (device memory of
+ * ESRNN_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends).  The call
+ * allocates nothing and frees nothing; its first call on a device looks the array's address up.
+ * Returns ESRNN_ERR_WORKSPACE if esrnn_workspace_bytes of this handle exceeds ESRNN_STATIC_SCRATCH_BYTES
+ * (batch too large for the built-in array: use esrnn_predict with a workspace of your own).
+ * All calls on one GPU, from every handle, share the one array, which keeps the contents of the last
+ * call (no part of it needs clearing: every kernel writes what it later reads): calls that overlap on
+ * one GPU race, and esrnn_backward must not follow.
+ */
+#define ESRNN_STATIC_SCRATCH_BYTES (32u << 20)
+esrnn_status esrnn_predict_static(esrnn_handle *h, const float *y, const int32_t *lengths, const float *es_params,
+                                  const float *weights, float *forecasts, void *stream);
 
 /*
  * Accuracy per series of forecasts [B][H] against actual values [B][H], with the

@@ -87,8 +87,9 @@ def load_library():
     lib.esrnn_adam_update.argtypes = [vp, C.POINTER(AdamConfig), C.c_int32, fp, fp, fp, fp, fp, fp, fp, fp, vp, vp]
     lib.esrnn_adam_update.restype = C.c_int
     lib.esrnn_predict.argtypes = [vp, fp, i32p, fp, fp, vp, fp, vp]
+    lib.esrnn_predict_static.argtypes = [vp, fp, i32p, fp, fp, fp, vp]
     lib.esrnn_forecast_metrics.argtypes = [vp, fp, fp, fp, i32p, C.c_int32, fp, fp, vp]
-    for fn in ("esrnn_predict", "esrnn_forecast_metrics"):
+    for fn in ("esrnn_predict", "esrnn_predict_static", "esrnn_forecast_metrics"):
         getattr(lib, fn).restype = C.c_int
     lib.esrnn_profile_enable.argtypes = [vp, C.c_int32]
     lib.esrnn_profile_stage_count.argtypes = [vp, C.POINTER(C.c_int32)]
@@ -305,6 +306,15 @@ def esrnn_predict(handle, y, lengths, es_params, weights, workspace, forecasts, 
                                       _ptr(forecasts, torch.float32), _stream(stream))
     if st != ESRNN_OK:
         raise EsrnnError(st, "esrnn_predict")
+
+
+def esrnn_predict_static(handle, y, lengths, es_params, weights, forecasts, stream=None) -> None:
+    import torch
+    st = load_library().esrnn_predict_static(handle, _ptr(y, torch.float32), _ptr(lengths, torch.int32),
+                                             _ptr(es_params, torch.float32), _ptr(weights, torch.float32),
+                                             _ptr(forecasts, torch.float32), _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_predict_static")
 
 
 def esrnn_forecast_metrics(handle, forecasts, actuals, y, lengths, m, smape, mase, stream=None) -> None:

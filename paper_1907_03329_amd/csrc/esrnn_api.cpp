@@ -143,7 +143,7 @@ const char *esrnn_status_string(esrnn_status s)
     case ESRNN_OK: return "ok";
     case ESRNN_ERR_NULL: return "null pointer argument";
     case ESRNN_ERR_CONFIG: return "unsupported configuration";
-    case ESRNN_ERR_WORKSPACE: return "workspace pointer not 256-byte aligned";
+    case ESRNN_ERR_WORKSPACE: return "workspace pointer not 256-byte aligned, or built-in workspace too small";
     case ESRNN_ERR_ORDER: return "backward called without a preceding forward";
     case ESRNN_ERR_HIP: return "HIP runtime error";
     }
@@ -232,6 +232,18 @@ esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengt
     ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, ext, ws, nullptr, st); }));
     ESRNN_TRY(run_stage(h, h->st_tail, st, [&] { return launch_forecast_tail(pl, lengths, ws, forecasts, st); }));
     return ESRNN_OK;
+}
+
+esrnn_status esrnn_predict_static(esrnn_handle *h, const float *y, const int32_t *lengths, const float *es_params,
+                                  const float *weights, float *forecasts, void *stream)
+{
+    if (!h || !y || !lengths || !es_params || !weights || !forecasts) return ESRNN_ERR_NULL;
+    if (h->plan.total_floats * sizeof(float) > (size_t)ESRNN_STATIC_SCRATCH_BYTES) return ESRNN_ERR_WORKSPACE;
+    void *ws = nullptr;
+    size_t bytes = 0;
+    ESRNN_TRY(static_scratch(&ws, &bytes));
+    if (h->plan.total_floats * sizeof(float) > bytes) return ESRNN_ERR_WORKSPACE;
+    return esrnn_predict(h, y, lengths, es_params, weights, ws, forecasts, stream);
 }
 
 esrnn_status esrnn_forecast_metrics(esrnn_handle *h, const float *forecasts, const float *actuals, const float *y,

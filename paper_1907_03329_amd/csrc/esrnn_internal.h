@@ -124,6 +124,9 @@ hipError_t launch_forecast_tail(const Plan &pl, const int32_t *lengths, float *w
 hipError_t launch_forecast_metrics(const Plan &pl, const float *forecasts, const float *actuals, const float *y,
                                    const int32_t *lengths, int m, float *smape, float *mase, hipStream_t st);
 
+// Device address and size of the library's own scratch array on the current device (static_scratch.hip).
+hipError_t static_scratch(void **ptr, size_t *bytes);
+
 // Supported (HT, KXT) instantiations of the LSTM kernels.
 bool lstm_shape_supported(int HT, int KXT);
 

@@ -1,0 +1,53 @@
+"""esrnn_predict_static: out-of-sample forecasts with the workspace inside the library (no allocation),
+through the C ABI, against esrnn_predict on a caller-owned workspace: two calls in a row, the second on a
+smaller batch that reuses the same built-in array, then the first again; and the size limit."""
+import numpy as np
+import pytest
+
+from paper_1907_03329_amd import binding, synth
+from paper_1907_03329_amd.synth import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+
+def predict_both(cfg, seed):
+    import torch
+    inp = synth.make_inputs(cfg, seed=seed, ragged=True)
+    inp["lengths"] = np.minimum(inp["lengths"], cfg.T - cfg.H).astype(np.int32)   # room for the horizon
+    dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
+    step = binding.TrainingStep(cfg, want_forecasts=False)
+    assert step.workspace_bytes <= 32 << 20
+    want = step.predict(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    got = torch.full((cfg.B, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
+    binding.esrnn_predict_static(step.handle, dev["y"], dev["lengths"], dev["es_params"], dev["weights"], got)
+    torch.cuda.synchronize()
+    return step, inp, want.cpu().numpy(), got.cpu().numpy()
+
+
+def test_static_workspace_matches_caller_workspace_twice_in_a_row():
+    from oracle import oracle
+    big = CONFIGS["quarterly"].with_(B=50)
+    small = CONFIGS["quarterly"].with_(B=9, T=40)
+    for cfg, seed in ((big, 31), (small, 32), (big, 33)):
+        step, inp, want, got = predict_both(cfg, seed)
+        assert np.all(np.isfinite(got)) and np.all(got > 0)
+        assert np.array_equal(got, want), f"{cfg.B} series: built-in workspace differs from caller's workspace"
+        ref = oracle.predict(cfg, inp["y"], inp["lengths"], inp["es_params"], inp["weights"])
+        rel = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+        assert rel.max() <= 1e-4, rel.max()
+        step.close()
+
+
+def test_static_workspace_refuses_a_batch_that_does_not_fit():
+    import torch
+    cfg = CONFIGS["quarterly"].with_(B=512)
+    h = binding.esrnn_create(cfg)
+    assert binding.esrnn_workspace_bytes(h) > 32 << 20
+    inp = synth.make_inputs(cfg, seed=1)
+    dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
+    out = torch.zeros((cfg.B, cfg.H), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.EsrnnError) as ei:
+        binding.esrnn_predict_static(h, dev["y"], dev["lengths"], dev["es_params"], dev["weights"], out)
+    assert ei.value.status == 3
+    assert "too small" in binding.status_string(3)
+    binding.esrnn_destroy(h)
