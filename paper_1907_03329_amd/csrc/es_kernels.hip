@@ -72,10 +72,42 @@ struct PackLstmArgs {
     const float *W, *b;
     float *fwd, *bias, *bwd;
     int h, in_dim, HT, KXT;
+    int narrow;          // operand order of the 4-series kernels (4x4x1 MFMA) instead
 };
+
+// Operands of the 4-series kernels.  v_mfma_f32_4x4x1: lane l supplies A[l%4] of block l/4.
+//   forward  [wave][column k of x ; h][lane]: gate l%4 of unit wave*HT + min(l/4, HT-1) (the blocks past HT
+//            repeat the last unit, so that all lanes do the same work on the same addresses)
+//   reverse  [wave][group g][k-step 4*u + gate][lane]: W[gate, unit wave*HT + u][column 64*g + l]
+__device__ void pack_lstm_narrow_body(const PackLstmArgs &a)
+{
+    const int KX = 4 * a.KXT, KT4 = KX + 4 * a.HT, NG = (KT4 + 63) / 64, ld = a.in_dim + a.h;
+    const int n_fwd = 4 * KT4 * 64, n_bwd = 4 * NG * 4 * a.HT * 64;
+    auto user_col = [&](int k) {
+        if (k < KX) return k < a.in_dim ? k : -1;
+        if (k < KT4) return k - KX < a.h ? a.in_dim + k - KX : -1;
+        return -1;
+    };
+    for (int idx = blockIdx.x * 256 + threadIdx.x; idx < n_fwd + n_bwd; idx += gridDim.x * 256) {
+        if (idx < n_fwd) {
+            const int lane = idx & 63, k = (idx >> 6) % KT4, w = (idx >> 6) / KT4;
+            const int blk = min(lane >> 2, a.HT - 1), gate = lane & 3, unit = w * a.HT + blk, col = user_col(k);
+            a.fwd[idx] = (unit < a.h && col >= 0) ? a.W[(size_t)(gate * a.h + unit) * ld + col] : 0.0f;
+        } else {
+            const int j = idx - n_fwd;
+            const int lane = j & 63, ks = (j >> 6) % (4 * a.HT), g = ((j >> 6) / (4 * a.HT)) % NG, w = (j >> 6) / (4 * a.HT * NG);
+            const int unit = w * a.HT + (ks >> 2), gate = ks & 3, col = user_col(64 * g + lane);
+            a.bwd[j] = (unit < a.h && col >= 0) ? a.W[(size_t)(gate * a.h + unit) * ld + col] : 0.0f;
+        }
+    }
+}
 
 __device__ void pack_lstm_body(const PackLstmArgs &a)
 {
+    if (a.narrow) {
+        pack_lstm_narrow_body(a);
+        return;
+    }
     const int KT = a.KXT + a.HT, MB = (KT + 3) / 4, ld = a.in_dim + a.h;
     const int n_fwd = a.HT * KT * 64, n_bias = a.HT * 16, n_bwd = MB * 4 * a.HT * 64;
     for (int idx = blockIdx.x * 256 + threadIdx.x; idx < n_fwd + n_bias + n_bwd; idx += gridDim.x * 256) {
@@ -758,9 +790,10 @@ hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *wei
     for (int l = 0; l < pl.L; ++l) {
         const LayerPlan &lp = pl.layer[l];
         a.lstm[l] = PackLstmArgs{weights + lp.w_off, weights + lp.b_off, ws + lp.wpack_fwd, ws + lp.bias_pack,
-                                 ws + lp.wpack_bwd, pl.h, lp.in_dim, pl.HT, lp.KXT};
+                                 ws + lp.wpack_bwd, pl.h, lp.in_dim, pl.HT, lp.KXT, lp.narrow};
         const int KT = lp.KXT + pl.HT, MB = (KT + 3) / 4;
-        max_total = std::max(max_total, pl.HT * KT * 64 + pl.HT * 16 + MB * 4 * pl.HT * 64);
+        max_total = std::max(max_total, lp.narrow ? 4 * 4 * KT * 64 + 4 * ((4 * KT + 63) / 64) * 4 * pl.HT * 64
+                                                  : pl.HT * KT * 64 + pl.HT * 16 + MB * 4 * pl.HT * 64);
     }
     const HeadPack hp = head_pack_layout(pl);
     float *f = ws + pl.head_fwd_pack, *b = ws + pl.head_bwd_pack;
@@ -950,8 +983,8 @@ hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_wei
         const LayerPlan &lp = pl.layer[l];
         const int MB = (lp.KXT + pl.HT + 3) / 4;
         const int n_dw = pl.HT * MB * 256, n_db = pl.HT * 16;
-        lstm_splits[l] = add(lp.dw_partial, lp.dw_reduced, n_dw, pl.NB * lp.chains, n_dw);
-        add(lp.db_partial, lp.db_reduced, n_db, pl.NB * lp.chains, n_db);
+        lstm_splits[l] = add(lp.dw_partial, lp.dw_reduced, n_dw, pl.partial_groups(lp), n_dw);
+        add(lp.db_partial, lp.db_reduced, n_db, pl.partial_groups(lp), n_db);
     }
     const int n_head = (pl.MO * pl.MA + pl.MA * pl.MA) * 256 + 4 * pl.OT + 4 * pl.HT;
     const int head_splits = add(pl.head_dw_partial, pl.head_dw_reduced, pl.head_dw_stride, pl.n_head_waves, n_head);

@@ -17,6 +17,7 @@ constexpr int kMaxLayers = ESRNN_MAX_BLOCKS * ESRNN_MAX_LAYERS_PER_BLOCK;
 constexpr int kLstmWaves = 4;    // waves per workgroup in the LSTM kernels
 constexpr int kReduceSplits = 16; // subsets of producers in the first stage of the weight-gradient reduction
 constexpr int kLdsPad = 17;      // row stride of LDS arrays that are read transposed
+constexpr int kNarrowSeries = 4; // series per workgroup in the small-batch LSTM kernels
 
 // Tile layout TL(R): [P][NB][R][16]; element (p, b, r) at ((p*NB + b/16)*R + r)*16 + b%16.
 // A "unit tile" is 4 consecutive rows (64 floats = one float per lane).
@@ -37,7 +38,10 @@ struct LayerPlan {
     size_t gsrc[4];      // TL(HP): the gradient arriving at this layer's hidden output is the sum of these
     int n_gsrc;
     size_t gdst;         // TL(4*KXT) gradient with respect to the layer input
-    int chains;          // workgroups per series tile; each walks the residue classes r, r+chains, ... (mod dil)
+    int chains;          // workgroups per series tile (per 4 series if narrow); each walks the residue classes r, r+chains, ... (mod dil)
+    int narrow;          // 1: the layer runs on the 4-series kernels (lstm_narrow_kernels.hip): wpack_fwd is
+                         // [4][4*(KXT+HT)][64], wpack_bwd [4][NG][4*HT][64], bias_pack unused, and the
+                         // weight-gradient partials are indexed by 4*NB*chains workgroups
     size_t dw_partial;   // [NB*chains][HT*MB][4][64] per-workgroup weight-gradient tiles
     size_t db_partial;   // [NB*chains][HT][4][4]
     size_t dw_reduced, db_reduced;   // [kReduceSplits][...] first reduction stage
@@ -77,6 +81,7 @@ struct Plan {
     int head_dw_stride;
     size_t head_dw_reduced;
     int es_blocks;
+    int partial_groups(const LayerPlan &lp) const { return (lp.narrow ? 4 * NB : NB) * lp.chains; }   // producers of weight-gradient partials
     size_t es_window_floats;   // prefix of the workspace used by the smoothing and window stages alone
     size_t total_floats;
 };
@@ -105,7 +110,12 @@ hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *wei
 hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *lengths, const float *es,
                              float *ws, hipStream_t st);
 hipError_t launch_window_forward(const Plan &pl, const int32_t *categories, float *ws, hipStream_t st);
-hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
+hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths, const float *weights, float *ws,
+                               hipStream_t st);
+// 4-series kernels for layers with few workgroups (called by the two launchers above and below)
+hipError_t launch_lstm_forward_narrow(const Plan &pl, int layer, const int32_t *lengths, const float *weights,
+                                      float *ws, hipStream_t st);
+hipError_t launch_lstm_backward_narrow(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
 // output stage, forward and reverse in one launch (needs the loss normalisers of launch_setup)
 hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st);
 hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStream_t st);

@@ -509,9 +509,11 @@ hipError_t run_bwd(const LstmBwdArgs &a, int chains, hipStream_t st)
 
 }  // namespace
 
-hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st)
+hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths, const float *weights, float *ws,
+                               hipStream_t st)
 {
     const LayerPlan &lp = pl.layer[layer];
+    if (lp.narrow) return launch_lstm_forward_narrow(pl, layer, lengths, weights, ws, st);
     const bool cp = lp.first_in_block && pl.cfg.lambda_cs != 0.0f;
     LstmFwdArgs a{ws + lp.wpack_fwd, ws + lp.bias_pack, ws + lp.xsrc, ws + lp.gates, ws + lp.c, ws + lp.hid,
                   lp.out ? ws + lp.resid : nullptr, lp.out ? ws + lp.out : nullptr, pl.P, pl.NB, lp.dil,
@@ -547,6 +549,7 @@ hipError_t launch_lstm_backward(const Plan &pl, int layer, const int32_t *length
         if (e != hipSuccess) return e;
         a.gsrc[1] = ws + pl.gsum;
     }
+    if (lp.narrow) return launch_lstm_backward_narrow(pl, layer, lengths, ws, st);
     a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
     a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
 #define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains, st);

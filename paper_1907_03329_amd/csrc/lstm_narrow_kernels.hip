@@ -1,0 +1,542 @@
+// Dilated LSTM layer for small batches (Section 3.2, Table 1; Section 8.3 notes
+// how little of a GPU such small cells use): forward and reverse kernels that
+// give a workgroup FOUR series instead of sixteen.
+//
+// When series tiles x chains of a layer is far below the number of compute
+// units, the 16-series kernels of lstm_kernels.hip leave most of the chip idle
+// and the layer costs (positions of the longest chain) x (time of one position
+// on one compute unit).  Both factors are attacked here: four times as many
+// workgroups, and a position costs a quarter of the matrix work.
+//
+// Arithmetic.  v_mfma_f32_4x4x1_16B_f32: sixteen independent 4x4 outer products
+// ("blocks") per instruction, one k-step.  Lane l belongs to block l/4; it
+// supplies A[l%4] and B[l%4] of its block and holds D[0..3][l%4].  With its
+// broadcast control (cbsz = 4, abid = b) all sixteen blocks take the A values
+// of block b.  Here A carries the ACTIVATIONS of the four series for one input
+// column, broadcast from the block whose four lanes hold them, and B carries
+// the weights: block u, lane g of a wave holds gate g of hidden unit u.  One
+// instruction advances 16 units x 4 gates x 4 series by one input column, and no
+// operand has to be replicated over the blocks: a wave reads [x_p ; h_{p-d}] of
+// the four series from LDS with one 4-byte load per 16 columns.  A workgroup has
+// four waves; wave w owns the units w*HT .. w*HT+HT-1 (HT <= 16; the padded
+// hidden size is 4*HT).  A lane ends up with one gate of one unit for the four
+// series; a 4x4 transpose inside each quad of lanes (DPP) turns that into the
+// four gates of one unit for ONE series, and the cell update is lane-local as
+// in the 16-series kernels.
+//
+// The reverse kernel follows the 16-series one step by step (gate gradients,
+// transposed contraction split over the waves along the contraction, weight
+// gradient in accumulators for the whole launch) with these differences: the
+// transposed contraction runs on the 4x4x1 instruction with the gate gradients
+// broadcast straight from the registers of the lanes that computed them; the
+// weight gradient contracts over the four series, which is exactly the k = 4 of
+// ONE 16x16x4 instruction per 16x16 tile of dW; the LDS arrays a position writes
+// are double-buffered by position parity, which leaves one barrier per
+// position.  Every LDS array is laid out [row][4 series], so that each access
+// of a wave covers consecutive addresses.
+//
+// Global operands.  A position takes a fraction of a microsecond here, less
+// than the latency of HBM, so operands are requested a whole chunk of positions
+// ahead: at the last position of a chunk the registers that hold the next chunk
+// go to LDS and the requests for the chunk after it are issued.  Inside a chunk
+// the position loop issues no load at all, only stores, which nothing waits
+// for.  (A ring of registers with one request per position was slower: memory
+// operations complete in order, and where the paths into a loop differ the
+// compiler's wait for the oldest request also waits for the stores issued
+// since.)  Blocks past HT repeat the last unit of the wave, operands and
+// addresses alike, so no memory operation sits behind a divergent branch.
+//
+// All tensors keep the layouts of the 16-series kernels (TL(R) tiles of 16
+// series), so layers of both kinds mix freely and the weight-gradient
+// reduction is unchanged; a workgroup touches 16-byte pieces of each row.
+#include <type_traits>
+
+#include "device_utils.h"
+#include "esrnn_internal.h"
+
+namespace esrnn {
+
+namespace {
+
+constexpr int kNW = 4;          // waves per workgroup
+constexpr int kNT = 64 * kNW;   // threads per workgroup
+
+// D_blk[i][j] += A_ABID[i] * B_blk[j] for all 16 blocks: the A values of block ABID serve every block.
+template <int ABID>
+__device__ __forceinline__ f32x4 mfma4_bcast(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 4, ABID, 0);
+}
+
+// compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1 (the broadcast block is an immediate)
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// value of the same register in another lane of the quad: quad_perm control [a, b, c, d]
+template <int CTRL>
+__device__ __forceinline__ float quad_perm(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// 4x4 transpose inside each quad of lanes: lane j, component c  <->  lane c, component j
+__device__ __forceinline__ void quad_transpose(f32x4 &v, int j)
+{
+    const bool lo = j & 1, hi = j & 2;
+    {   // lanes j ^ 1, component pairs (0,1) and (2,3)
+        const float r01 = quad_perm<0xB1>(lo ? v[0] : v[1]);
+        const float r23 = quad_perm<0xB1>(lo ? v[2] : v[3]);
+        if (lo) { v[0] = r01; v[2] = r23; } else { v[1] = r01; v[3] = r23; }
+    }
+    {   // lanes j ^ 2, component pairs (0,2) and (1,3)
+        const float r02 = quad_perm<0x4E>(hi ? v[0] : v[2]);
+        const float r13 = quad_perm<0x4E>(hi ? v[1] : v[3]);
+        if (hi) { v[0] = r02; v[1] = r13; } else { v[2] = r02; v[3] = r13; }
+    }
+}
+
+struct NarrowFwdArgs {
+    const float *wpack;   // [4][KT4][64]  weight operands: wave, input column, lane (gate l%4 of unit l/4 of the wave)
+    const float *bias;    // caller's bias vector [4h]
+    const float *xsrc;    // TL(4*KXT)
+    float *gates;         // TL(HP) x [4]
+    float *c, *hid;       // TL(HP)
+    const float *resid;   // TL(HP) or null
+    float *out;           // TL(HP) or null: resid + hid
+    int P, NB, d, h;
+    const int32_t *lengths;
+    float *cs_partial;    // [4*NB * gridDim.y] (cell-state penalty, CP instantiations only)
+    int B, T, I, H;
+};
+
+template <int HT, int KXT, bool CP>
+__global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs a)
+{
+    constexpr int KX = 4 * KXT, HP = 4 * HT;
+    constexpr int CH = 8;                       // positions per chunk of staged inputs
+    constexpr int XG = (KX + 15) / 16, HG = (HP + 15) / 16;   // groups of 16 columns (one register each)
+    __shared__ float xc[2][CH][XG * 64];        // inputs x_p of a chunk of positions [column][series], by chunk parity
+    __shared__ float rc[CH][kNT];               // residual input of this thread's (unit, series)
+    __shared__ float hb[2][HG * 64];            // h_{p-d} [unit][series], by position parity
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int blk = lane >> 2, j = lane & 3;
+    const int bt = blockIdx.x >> 2, q = blockIdx.x & 3;
+    const bool valid = blk < HT;
+    const int unit = w * HT + min(blk, HT - 1);     // blocks past HT repeat the last unit
+
+    float wx[KX], wh[HP];
+#pragma unroll
+    for (int k = 0; k < KX; ++k) wx[k] = a.wpack[((size_t)w * (KX + HP) + k) * 64 + lane];
+#pragma unroll
+    for (int k = 0; k < HP; ++k) wh[k] = a.wpack[((size_t)w * (KX + HP) + KX + k) * 64 + lane];
+    // before the transpose a lane holds gate j of its unit for the four series
+    const float bias = unit < a.h ? a.bias[j * a.h + unit] : 0.0f;
+
+    // element of this lane inside the TL(HP) block of one (position, series tile)
+    const int lane_off = unit * 16 + 4 * q + j;
+    // cooperative input load: thread t < 4*KX brings row t/4 of series t%4 (the others repeat row 0)
+    const bool x_thread = (int)threadIdx.x < 4 * KX;
+    const int x_off = (x_thread ? (int)threadIdx.x >> 2 : 0) * 16 + 4 * q + (threadIdx.x & 3);
+    const bool has_out = a.out != nullptr;
+
+    int n_valid = 0;
+    float csq = 0.0f;
+    if constexpr (CP) {
+        const int col = bt * kTileN + 4 * q + j;
+        const int len = col < a.B ? min(max(a.lengths[col], 0), a.T) : 0;
+        n_valid = len - a.I - a.H + 1;
+    }
+    // columns past KX / HP in the last group of 16 are never written: zero once (their weights do not exist)
+    for (int e = threadIdx.x; e < 2 * CH * XG * 64; e += kNT) (&xc[0][0][0])[e] = 0.0f;
+    for (int e = threadIdx.x; e < 2 * HG * 64; e += kNT) (&hb[0][0])[e] = 0.0f;
+
+    for (int r = blockIdx.y; r < a.d && r < a.P; r += gridDim.y) {
+        const int n = (a.P - r + a.d - 1) / a.d;            // positions of this chain: r, r+d, ...
+        float xs[CH], rs[CH];
+        auto load_chunk = [&](int c) {
+#pragma unroll
+            for (int ii = 0; ii < CH; ++ii) {
+                const size_t tile = (size_t)(r + min(c * CH + ii, n - 1) * a.d) * a.NB + bt;
+                xs[ii] = (a.xsrc + tile * (KX * 16))[x_off];
+                rs[ii] = has_out ? (a.resid + tile * (HP * 16))[lane_off] : 0.0f;
+            }
+        };
+        auto flush_chunk = [&](int c) {
+#pragma unroll
+            for (int ii = 0; ii < CH; ++ii) {
+                if (x_thread) xc[c & 1][ii][threadIdx.x] = xs[ii];
+                rc[ii][threadIdx.x] = rs[ii];
+            }
+        };
+        // start of a chain: zero state, inputs of the first chunk staged, those of the second requested
+        load_chunk(0);
+        float creg = 0.0f;
+        __syncthreads();            // LDS free: initial clearing, or the last position of the previous chain
+        for (int e = threadIdx.x; e < 4 * HP; e += kNT) hb[0][e] = 0.0f;
+        flush_chunk(0);
+        load_chunk(1);
+        lds_barrier();
+
+        for (int i = 0; i < n; ++i) {
+            const int c = i / CH, ii = i % CH;
+            const int p = r + i * a.d;
+            const size_t pb = (size_t)p * a.NB + bt;
+            const float res = rc[ii][threadIdx.x];
+            // [x_p ; h_{p-d}] of the four series: lane (b, s) of register m holds column 16m + b of series s
+            float vh[HG], vx[XG];
+#pragma unroll
+            for (int m = 0; m < HG; ++m) vh[m] = hb[i & 1][64 * m + lane];
+#pragma unroll
+            for (int m = 0; m < XG; ++m) vx[m] = xc[c & 1][ii][64 * m + lane];
+            // two accumulators: consecutive instructions never depend on each other
+            f32x4 acc0 = f32x4{bias, bias, bias, bias}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+            static_for<0, KX / 2>([&](auto ic) {
+                constexpr int k = 2 * decltype(ic)::value;
+                acc0 = mfma4_bcast<k % 16>(vx[k / 16], wx[k], acc0);
+                acc1 = mfma4_bcast<(k + 1) % 16>(vx[(k + 1) / 16], wx[k + 1], acc1);
+            });
+            static_for<0, HP / 2>([&](auto ic) {
+                constexpr int k = 2 * decltype(ic)::value;
+                acc0 = mfma4_bcast<k % 16>(vh[k / 16], wh[k], acc0);
+                acc1 = mfma4_bcast<(k + 1) % 16>(vh[(k + 1) / 16], wh[k + 1], acc1);
+            });
+            f32x4 pre = acc0 + acc1;        // gate j of the unit, series 0..3
+            quad_transpose(pre, j);         // gates 0..3 of the unit, series j
+            const float gi = sigmoid_f(pre[0]);
+            const float gf = sigmoid_f(pre[1]);
+            const float gg = tanh_f(pre[2]);
+            const float go = sigmoid_f(pre[3]);
+            const float cn = gf * creg + gi * gg;
+            const float hn = go * tanh_f(cn);
+            creg = cn;
+            if constexpr (CP) csq += (valid && p < n_valid) ? cn * cn : 0.0f;
+            hb[(i + 1) & 1][4 * unit + j] = hn;
+            // last position of a chunk: stage the next chunk, request the one after it.  Placed ahead of
+            // this position's stores: the wait for the staged registers then only meets stores that are
+            // a whole position old.
+            if (ii == CH - 1 && i + 1 < n) {
+                flush_chunk(c + 1);
+                load_chunk(c + 2);
+            }
+            const size_t e = pb * (HP * 16) + lane_off;
+            __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + e);
+            __builtin_nontemporal_store(cn, a.c + e);
+            a.hid[e] = hn;
+            if (has_out) a.out[e] = res + hn;
+            lds_barrier();
+        }
+    }
+    if constexpr (CP) {
+        __shared__ float s_cs[kNW];
+        const float tot = wave_sum(csq);
+        if (lane == 0) s_cs[w] = tot;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            a.cs_partial[blockIdx.x * gridDim.y + blockIdx.y] = (s_cs[0] + s_cs[1]) + (s_cs[2] + s_cs[3]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Reverse pass.  Per position p of a chain, descending:
+//   A. every lane turns (dh, dc) of its (unit, series) into the four gate
+//      pre-activation gradients da (registers; a copy goes to LDS for step C);
+//   B. a wave multiplies W^T by the da of the units it owns: 4x4x1 MFMA with da
+//      as the broadcast A operand, taken from the registers of the four lanes
+//      that hold unit u, and the weights as B (a block is four consecutive
+//      columns of [x ; h]); the four partial results meet in LDS (part);
+//   -- barrier --
+//   every lane sums the four partials of its own (unit, series): the recurrent
+//      dh of the next position; the threads sum and store the input gradient;
+//   C. dW += da (x) [x_p ; h_{p-d}]: one 16x16x4 MFMA per 16x16 tile of dW, k =
+//      the four series; row tiles dealt to the waves round-robin.
+// da_all and part alternate between two copies by position parity: what a
+// position writes was last read two positions earlier, one barrier ago.  The
+// staged operands of a chunk of positions: per-thread values (gates, cell
+// states, arriving gradient) in a buffer every thread reads only where it wrote;
+// [x ; h] rows, which the whole workgroup reads, in two buffers by chunk parity.
+// ---------------------------------------------------------------------------
+struct NarrowBwdArgs {
+    const float *wpack;   // [4][NG][4*HT][64]  operands of W^T: wave, column group, k-step (unit, gate), lane = column
+    const float *xsrc;    // TL(4*KXT)
+    const float *gates, *c;
+    ptrdiff_t hid_minus_xsrc;   // hidden states TL(HP), as an offset in floats from xsrc (both lie in the workspace)
+    const float *gsrc[2];
+    int n_gsrc;
+    float *gdst;          // TL(4*KXT)
+    float *dw_partial;    // [4*NB*chains][HT*CT][4][64]
+    float *db_partial;    // [4*NB*chains][HT][4][4]
+    int P, NB, d;
+    const int32_t *lengths;
+    const Scalars *sc;
+    float two_lambda_cs;
+    int B, T, I, H;
+};
+
+template <int HT, int KXT, bool CP>
+__global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs a)
+{
+    constexpr int KX = 4 * KXT, HP = 4 * HT, KT4 = KX + HP;
+    constexpr int CH = 4;                        // positions per chunk of staged operands
+    constexpr int NG = (KT4 + 63) / 64;          // groups of 64 columns of [x ; h]
+    constexpr int CT = (KT4 + 15) / 16;          // 16-column tiles of dW
+    constexpr int MTW = (HT + kNW - 1) / kNW;    // 16-row tiles of dW per wave (a row tile = 4 units x 4 gates)
+    constexpr int XH_PER = (4 * KT4 + kNT - 1) / kNT;
+    __shared__ __align__(16) float da_all[2][HP * 16];           // [unit][series][gate]
+    __shared__ __align__(16) float part[2][kNW][NG * 64 * 4];    // partial W^T da of every wave [column][series]
+    __shared__ __align__(16) f32x4 lc[CH][2][kNT];               // per thread: activated gates; c, c_{p-d}, two gradient sources
+    __shared__ float xhc[2][CH][CT * 64];                        // [column of x_p ; h_{p-d}][series]
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int blk = lane >> 2, j = lane & 3;
+    const int bt = blockIdx.x >> 2, q = blockIdx.x & 3;
+    const bool valid = blk < HT;
+    const int unit = w * HT + min(blk, HT - 1);     // blocks past HT repeat the last unit
+    const int lane_off = unit * 16 + 4 * q + j;
+    // input gradient: thread t sums and stores element t mod 4*KX (threads past 4*KX repeat earlier ones)
+    const int dx_el = (int)threadIdx.x % (4 * KX);
+    // operands of the weight-gradient tiles inside 64 consecutive floats of da_all / xhc
+    const int ar_off = 16 * (lane & 3) + 4 * (lane >> 4) + ((lane & 15) >> 2);   // unit l%4, series l/16, gate (l%16)/4
+    const int xb_off = 4 * (lane & 15) + (lane >> 4);                            // column l%16, series l/16
+
+    float wreg[NG][4 * HT];
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int k = 0; k < 4 * HT; ++k) wreg[g][k] = a.wpack[(((size_t)w * NG + g) * (4 * HT) + k) * 64 + lane];
+    f32x4 dw[MTW][CT];
+#pragma unroll
+    for (int t = 0; t < MTW; ++t)
+#pragma unroll
+        for (int nb = 0; nb < CT; ++nb) dw[t][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 dbacc = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int e = threadIdx.x; e < 2 * CH * CT * 64; e += kNT) (&xhc[0][0][0])[e] = 0.0f;   // columns past KT4 stay zero
+
+    const float g2_scale = a.n_gsrc >= 2 ? 1.0f : 0.0f;
+    int n_valid = 0;
+    float pen = 0.0f;
+    if constexpr (CP) {
+        const int col = bt * kTileN + 4 * q + j;
+        const int len = col < a.B ? min(max(a.lengths[col], 0), a.T) : 0;
+        n_valid = len - a.I - a.H + 1;
+        pen = a.two_lambda_cs * a.sc->inv_n_cs;
+    }
+
+    for (int r0 = blockIdx.y; r0 < a.d && r0 < a.P; r0 += gridDim.y) {
+        const int n = (a.P - r0 + a.d - 1) / a.d;
+        const int p_last = r0 + (n - 1) * a.d;
+        // operands of the i-th position from the end of the chain (requests past the chain repeat the last)
+        f32x4 s_gt[CH], s_o[CH];     // (native vectors: arrays of the HIP float4 class do not stay in registers)
+        float s_xh[CH][XH_PER];
+        auto load_chunk = [&](int c) {
+#pragma unroll
+            for (int ii = 0; ii < CH; ++ii) {
+                const int p = p_last - min(c * CH + ii, n - 1) * a.d;
+                const size_t pb = (size_t)p * a.NB + bt;
+                const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
+                const size_t e = pb * (HP * 16) + lane_off;
+                s_gt[ii] = reinterpret_cast<const f32x4 *>(a.gates)[e];
+                s_o[ii] = f32x4{a.c[e], a.c[pbd * (HP * 16) + lane_off], a.gsrc[0][e], a.gsrc[1][e]};
+#pragma unroll
+                for (int k = 0; k < XH_PER; ++k) {
+                    const int el = min((int)threadIdx.x + k * kNT, 4 * KT4 - 1);
+                    const int col = el >> 2, jj = el & 3;
+                    // one base pointer and a per-lane offset (a per-lane choice between two pointers would be
+                    // fetched from the argument block in memory, with a wait, before every request)
+                    const ptrdiff_t off = col < KX ? (ptrdiff_t)((pb * KX + col) * 16)
+                                                   : a.hid_minus_xsrc + (ptrdiff_t)((pbd * HP + (col - KX)) * 16);
+                    s_xh[ii][k] = a.xsrc[off + 4 * q + jj];
+                }
+            }
+        };
+        auto flush_chunk = [&](int c) {
+#pragma unroll
+            for (int ii = 0; ii < CH; ++ii) {
+                const bool has_prev = p_last - min(c * CH + ii, n - 1) * a.d >= a.d;
+                lc[ii][0][threadIdx.x] = s_gt[ii];
+                lc[ii][1][threadIdx.x] = s_o[ii];
+#pragma unroll
+                for (int k = 0; k < XH_PER; ++k) {
+                    const int el = (int)threadIdx.x + k * kNT;
+                    if (el < 4 * KT4) xhc[c & 1][ii][el] = (el < 4 * KX || has_prev) ? s_xh[ii][k] : 0.0f;
+                }
+            }
+        };
+        load_chunk(0);
+        float dcreg = 0.0f, dhreg = 0.0f;
+        __syncthreads();            // LDS free: initial clearing, or the last position of the previous chain
+        flush_chunk(0);
+        load_chunk(1);
+        lds_barrier();
+
+        for (int i = 0; i < n; ++i) {
+            const int c = i / CH, ii = i % CH, par = i & 1;
+            const int p = p_last - i * a.d;
+            const size_t pb = (size_t)p * a.NB + bt;
+            const bool has_prev = p >= a.d;
+            // ---- A: gate gradients of (unit, series)
+            const f32x4 gt = lc[ii][0][threadIdx.x];      // activated input, forget, candidate, output gate
+            const f32x4 o = lc[ii][1][threadIdx.x];       // c, c_{p-d}, gradient sources
+            const float dh = o[2] + g2_scale * o[3] + dhreg;
+            const float tc = tanh_f(o[0]);
+            float dc = dcreg + dh * gt[3] * (1.0f - tc * tc);
+            if constexpr (CP) dc += p < n_valid ? pen * o[0] : 0.0f;
+            const float cp = has_prev ? o[1] : 0.0f;
+            f32x4 da;
+            da[0] = dc * gt[2] * gt[0] * (1.0f - gt[0]);
+            da[1] = dc * cp * gt[1] * (1.0f - gt[1]);
+            da[2] = dc * gt[0] * (1.0f - gt[2] * gt[2]);
+            da[3] = dh * tc * gt[3] * (1.0f - gt[3]);
+            dcreg = dc * gt[1];
+            if (valid) dbacc += da;
+            *reinterpret_cast<f32x4 *>(&da_all[par][16 * unit + 4 * j]) = da;    // for step C
+            // ---- B: partial W^T da over the k-steps (unit, gate) of this wave; da of unit u is
+            // broadcast from the registers of block u.  Two accumulators per column group:
+            // consecutive instructions never depend on each other.
+            f32x4 acc[NG][2];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g][0] = acc[g][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            static_for<0, HT>([&](auto ic) {
+                constexpr int ul = decltype(ic)::value;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    acc[g][0] = mfma4_bcast<ul>(da[0], wreg[g][4 * ul + 0], acc[g][0]);
+                    acc[g][1] = mfma4_bcast<ul>(da[1], wreg[g][4 * ul + 1], acc[g][1]);
+                }
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    acc[g][0] = mfma4_bcast<ul>(da[2], wreg[g][4 * ul + 2], acc[g][0]);
+                    acc[g][1] = mfma4_bcast<ul>(da[3], wreg[g][4 * ul + 3], acc[g][1]);
+                }
+            });
+            // lane l of group g holds column 64g + l for the four series
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+                *reinterpret_cast<f32x4 *>(&part[par][w][(64 * g + lane) * 4]) = acc[g][0] + acc[g][1];
+            lds_barrier();
+            // ---- sums of the four partials: recurrent dh of this lane; input gradient
+            {
+                const int e = 4 * (KX + unit) + j;
+                dhreg = (part[par][0][e] + part[par][1][e]) + (part[par][2][e] + part[par][3][e]);
+            }
+            const float dxv = (part[par][0][dx_el] + part[par][1][dx_el]) + (part[par][2][dx_el] + part[par][3][dx_el]);
+            // last position of a chunk: stage the next chunk, request the one after it (ahead of this
+            // position's store: the wait for the staged registers only meets stores a position old)
+            if (ii == CH - 1 && i + 1 < n) {
+                flush_chunk(c + 1);
+                load_chunk(c + 2);
+            }
+            a.gdst[(pb * KX + (dx_el >> 2)) * 16 + 4 * q + (dx_el & 3)] = dxv;
+            // ---- C: weight gradient, k = the four series
+            {
+                float xb[CT];
+#pragma unroll
+                for (int nb = 0; nb < CT; ++nb) xb[nb] = xhc[c & 1][ii][64 * nb + xb_off];
+#pragma unroll
+                for (int t = 0; t < MTW; ++t) {
+                    const int mt = w + kNW * t;
+                    if (mt < HT) {
+                        // row 4*gate + u of the tile is gate `gate` of unit 4*mt + u
+                        const float ar = da_all[par][64 * mt + ar_off];
+#pragma unroll
+                        for (int nb = 0; nb < CT; ++nb) dw[t][nb] = mfma16(ar, xb[nb], dw[t][nb]);
+                    }
+                }
+            }
+        }
+    }
+
+    const size_t partix = (size_t)blockIdx.x * gridDim.y + blockIdx.y;
+#pragma unroll
+    for (int t = 0; t < MTW; ++t) {
+        const int mt = w + kNW * t;
+        if (mt < HT) {
+#pragma unroll
+            for (int nb = 0; nb < CT; ++nb) {
+                float *dst = a.dw_partial + (partix * (HT * CT) + mt * CT + nb) * 256 + lane;
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) dst[rr * 64] = dw[t][nb][rr];
+            }
+        }
+    }
+    // bias gradient: sum over the four series (the lanes of a quad)
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        float v = dbacc[rr];
+        v += quad_perm<0xB1>(v);
+        v += quad_perm<0x4E>(v);
+        dbacc[rr] = v;
+    }
+    if (valid && j == 0) {
+        float *dst = a.db_partial + partix * (HT * 16) + (size_t)unit * 4;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) dst[rr] = dbacc[rr];
+    }
+}
+
+template <int HT, int KXT>
+hipError_t run_nfwd(const NarrowFwdArgs &a, int chains, hipStream_t st)
+{
+    if (a.cs_partial) lstm_forward_narrow_kernel<HT, KXT, true><<<dim3(4 * a.NB, chains), 64 * kNW, 0, st>>>(a);
+    else lstm_forward_narrow_kernel<HT, KXT, false><<<dim3(4 * a.NB, chains), 64 * kNW, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+template <int HT, int KXT>
+hipError_t run_nbwd(const NarrowBwdArgs &a, int chains, hipStream_t st)
+{
+    if (a.sc) lstm_backward_narrow_kernel<HT, KXT, true><<<dim3(4 * a.NB, chains), 64 * kNW, 0, st>>>(a);
+    else lstm_backward_narrow_kernel<HT, KXT, false><<<dim3(4 * a.NB, chains), 64 * kNW, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+#define ESRNN_LSTM_SHAPES(X) \
+    X(2, 1) X(2, 2) X(8, 2) X(8, 3) X(8, 8) X(10, 1) X(10, 3) X(10, 6) X(10, 8) X(10, 10) X(13, 3) X(13, 5) X(13, 13) X(16, 16)
+
+}  // namespace
+
+hipError_t launch_lstm_forward_narrow(const Plan &pl, int layer, const int32_t *lengths, const float *weights,
+                                      float *ws, hipStream_t st)
+{
+    const LayerPlan &lp = pl.layer[layer];
+    const bool cp = lp.first_in_block && pl.cfg.lambda_cs != 0.0f;
+    NarrowFwdArgs a{ws + lp.wpack_fwd, weights + lp.b_off, ws + lp.xsrc, ws + lp.gates, ws + lp.c, ws + lp.hid,
+                    lp.out ? ws + lp.resid : nullptr, lp.out ? ws + lp.out : nullptr, pl.P, pl.NB, lp.dil, pl.h,
+                    lengths, cp ? ws + lp.cs_partial : nullptr, pl.B, pl.T, pl.I, pl.H};
+#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_nfwd<HT_, KXT_>(a, lp.chains, st);
+    ESRNN_LSTM_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_lstm_backward_narrow(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st)
+{
+    const LayerPlan &lp = pl.layer[layer];
+    NarrowBwdArgs a{};
+    const bool cp = lp.first_in_block && pl.cfg.lambda_cs != 0.0f;
+    a.lengths = lengths;
+    a.sc = cp ? reinterpret_cast<const Scalars *>(ws + pl.scalars) : nullptr;
+    a.two_lambda_cs = 2.0f * pl.cfg.lambda_cs;
+    a.B = pl.B; a.T = pl.T; a.I = pl.I; a.H = pl.H;
+    a.wpack = ws + lp.wpack_bwd; a.xsrc = ws + lp.xsrc; a.gates = ws + lp.gates; a.c = ws + lp.c;
+    a.hid_minus_xsrc = (ptrdiff_t)lp.hid - (ptrdiff_t)lp.xsrc;
+    a.n_gsrc = lp.n_gsrc < 2 ? lp.n_gsrc : 2;
+    a.gsrc[0] = ws + lp.gsrc[0];
+    a.gsrc[1] = ws + (lp.n_gsrc > 2 ? pl.gsum : lp.gsrc[lp.n_gsrc >= 2 ? 1 : 0]);
+    a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
+    a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
+#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_nbwd<HT_, KXT_>(a, lp.chains, st);
+    ESRNN_LSTM_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+}  // namespace esrnn

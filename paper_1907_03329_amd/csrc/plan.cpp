@@ -1,6 +1,7 @@
 // Host-side launch plan: validates a configuration, lays out the workspace and
 // the packed operand blocks.  No device work happens here.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 #include "esrnn_internal.h"
@@ -20,6 +21,8 @@ struct Bump {
 };
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+constexpr int kNarrowBelowDefault = 160;
 
 // hidden sizes are padded to one of the instantiated unit-tile counts
 int pick_ht(int hidden)
@@ -61,6 +64,10 @@ HeadPack head_pack_layout(const Plan &pl)
 esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
 {
     std::memset(&pl, 0, sizeof(pl));
+    // Layers whose 16-series grid has fewer workgroups than this run on the 4-series kernels.
+    // ESRNN_NARROW_BELOW overrides the threshold (0: never, a large number: always), for measurements.
+    int narrow_below = kNarrowBelowDefault;
+    if (const char *env = std::getenv("ESRNN_NARROW_BELOW")) narrow_below = std::atoi(env);
     pl.cfg = cfg;
     if (cfg.B < 1 || cfg.T < 1 || cfg.I < 1 || cfg.H < 1 || cfg.hidden < 1) return ESRNN_ERR_CONFIG;
     if (cfg.hidden > ESRNN_MAX_HIDDEN || cfg.I > ESRNN_MAX_WINDOW || cfg.H > ESRNN_MAX_WINDOW) return ESRNN_ERR_CONFIG;
@@ -162,18 +169,30 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         LayerPlan &lp = pl.layer[l];
         const int KT = lp.KXT + pl.HT;
         const int MB = ceil_div(KT, 4);
-        lp.wpack_fwd = ws.take((size_t)pl.HT * KT * 64);
-        lp.bias_pack = ws.take((size_t)pl.HT * 16);
-        lp.wpack_bwd = ws.take((size_t)MB * 4 * pl.HT * 64);
+        // Few workgroups (small batch, small dilation): four series per workgroup instead of sixteen.
+        // `narrow_below`: use the 4-series kernels when the 16-series grid would have fewer workgroups.
+        const int wide_chains = std::min(std::min(lp.dil, pl.P), std::max(1, ceil_div(512, pl.NB)));
+        lp.narrow = pl.NB * wide_chains < narrow_below ? 1 : 0;
+        const int groups = lp.narrow ? 4 * pl.NB : pl.NB;
+        // enough workgroups to put several on every compute unit, without more
+        // weight-gradient partials than the reduction can read cheaply
+        const int max_chains = std::max(1, ceil_div(512, groups));
+        lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
+        if (lp.narrow) {
+            const int KT4 = 4 * KT, NG = ceil_div(KT4, 64);
+            lp.wpack_fwd = ws.take((size_t)4 * KT4 * 64);
+            lp.bias_pack = lp.wpack_fwd;                       // unused: the kernels read the caller's bias
+            lp.wpack_bwd = ws.take((size_t)4 * NG * 4 * pl.HT * 64);
+        } else {
+            lp.wpack_fwd = ws.take((size_t)pl.HT * KT * 64);
+            lp.bias_pack = ws.take((size_t)pl.HT * 16);
+            lp.wpack_bwd = ws.take((size_t)MB * 4 * pl.HT * 64);
+        }
         lp.gates = ws.take(PN * tileH * 4);
         lp.c = ws.take(PN * tileH);
         lp.hid = ws.take(PN * tileH);
-        // enough workgroups to put several on every compute unit, without more
-        // weight-gradient partials than the reduction can read cheaply
-        const int max_chains = std::max(1, ceil_div(512, pl.NB));
-        lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
-        lp.dw_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * MB * 256);
-        lp.db_partial = ws.take((size_t)pl.NB * lp.chains * pl.HT * 16);
+        lp.dw_partial = ws.take((size_t)groups * lp.chains * pl.HT * MB * 256);
+        lp.db_partial = ws.take((size_t)groups * lp.chains * pl.HT * 16);
         lp.dw_reduced = ws.take((size_t)kReduceSplits * pl.HT * MB * 256);
         lp.db_reduced = ws.take((size_t)kReduceSplits * pl.HT * 16);
         pl.dx[l] = l > 0 ? ws.take(PN * tileH) : pl.gX;
@@ -186,7 +205,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
             LayerPlan &lp = pl.layer[l];
             if (!lp.first_in_block) continue;
             lp.cs_partial = pl.cs_partial + pl.n_cs_partial;
-            pl.n_cs_partial += pl.NB * lp.chains;
+            pl.n_cs_partial += pl.partial_groups(lp);
         }
     ws.take((size_t)pl.n_cs_partial);
     // block outputs: block 0's is the hidden state of its last layer

@@ -26,7 +26,7 @@ def predict_both(cfg, seed):
 
 def test_static_workspace_matches_caller_workspace_twice_in_a_row():
     from oracle import oracle
-    big = CONFIGS["quarterly"].with_(B=50)
+    big = CONFIGS["quarterly"].with_(B=45)
     small = CONFIGS["quarterly"].with_(B=9, T=40)
     for cfg, seed in ((big, 31), (small, 32), (big, 33)):
         step, inp, want, got = predict_both(cfg, seed)
