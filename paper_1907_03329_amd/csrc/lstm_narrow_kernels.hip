@@ -188,25 +188,25 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
         for (int i = 0; i < n; ++i) {
             const int c = i / CH, ii = i % CH;
             const int p = r + i * a.d;
-            const size_t pb = (size_t)p * a.NB + bt;
-            const float res = rc[ii][threadIdx.x];
             // [x_p ; h_{p-d}] of the four series: lane (b, s) of register m holds column 16m + b of series s
             float vh[HG], vx[XG];
 #pragma unroll
             for (int m = 0; m < HG; ++m) vh[m] = hb[i & 1][64 * m + lane];
 #pragma unroll
             for (int m = 0; m < XG; ++m) vx[m] = xc[c & 1][ii][64 * m + lane];
-            // two accumulators: consecutive instructions never depend on each other
+            const float res = rc[ii][threadIdx.x];
+            // two accumulators: consecutive instructions never depend on each other (measured: one is
+            // slower, four are slower too)
             f32x4 acc0 = f32x4{bias, bias, bias, bias}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
             static_for<0, KX / 2>([&](auto ic) {
                 constexpr int k = 2 * decltype(ic)::value;
                 acc0 = mfma4_bcast<k % 16>(vx[k / 16], wx[k], acc0);
-                acc1 = mfma4_bcast<(k + 1) % 16>(vx[(k + 1) / 16], wx[k + 1], acc1);
+                acc1 = mfma4_bcast<(k + 1) % 16>(vx[k / 16], wx[k + 1], acc1);
             });
             static_for<0, HP / 2>([&](auto ic) {
                 constexpr int k = 2 * decltype(ic)::value;
                 acc0 = mfma4_bcast<k % 16>(vh[k / 16], wh[k], acc0);
-                acc1 = mfma4_bcast<(k + 1) % 16>(vh[(k + 1) / 16], wh[k + 1], acc1);
+                acc1 = mfma4_bcast<(k + 1) % 16>(vh[k / 16], wh[k + 1], acc1);
             });
             f32x4 pre = acc0 + acc1;        // gate j of the unit, series 0..3
             quad_transpose(pre, j);         // gates 0..3 of the unit, series j
@@ -226,11 +226,12 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
                 flush_chunk(c + 1);
                 load_chunk(c + 2);
             }
-            const size_t e = pb * (HP * 16) + lane_off;
-            __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + e);
-            __builtin_nontemporal_store(cn, a.c + e);
-            a.hid[e] = hn;
-            if (has_out) a.out[e] = res + hn;
+            // wave-uniform tile base plus the lane's element: scalar address arithmetic
+            const size_t tile = ((size_t)p * a.NB + bt) * (HP * 16);
+            __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + tile + lane_off);
+            __builtin_nontemporal_store(cn, a.c + tile + lane_off);
+            (a.hid + tile)[lane_off] = hn;
+            if (has_out) (a.out + tile)[lane_off] = res + hn;
             lds_barrier();
         }
     }
@@ -377,14 +378,15 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
         load_chunk(1);
         lds_barrier();
 
+        // per-thread operands of the first position; those of position i+1 are read before the barrier
+        // that ends position i
+        f32x4 gt = lc[0][0][threadIdx.x];      // activated input, forget, candidate, output gate
+        f32x4 o = lc[0][1][threadIdx.x];       // c, c_{p-d}, gradient sources
         for (int i = 0; i < n; ++i) {
             const int c = i / CH, ii = i % CH, par = i & 1;
             const int p = p_last - i * a.d;
-            const size_t pb = (size_t)p * a.NB + bt;
             const bool has_prev = p >= a.d;
             // ---- A: gate gradients of (unit, series)
-            const f32x4 gt = lc[ii][0][threadIdx.x];      // activated input, forget, candidate, output gate
-            const f32x4 o = lc[ii][1][threadIdx.x];       // c, c_{p-d}, gradient sources
             const float dh = o[2] + g2_scale * o[3] + dhreg;
             const float tc = tanh_f(o[0]);
             float dc = dcreg + dh * gt[3] * (1.0f - tc * tc);
@@ -399,28 +401,43 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
             if (valid) dbacc += da;
             *reinterpret_cast<f32x4 *>(&da_all[par][16 * unit + 4 * j]) = da;    // for step C
             // ---- B: partial W^T da over the k-steps (unit, gate) of this wave; da of unit u is
-            // broadcast from the registers of block u.  Two accumulators per column group:
-            // consecutive instructions never depend on each other.
-            f32x4 acc[NG][2];
+            // broadcast from the registers of block u.  Two chains of dependent instructions: the two
+            // column groups, or with one group two accumulators (more would cost the second resident
+            // workgroup its registers at hidden 40).
+            constexpr int kBwdAcc = NG == 1 ? 2 : 1;
+            f32x4 acc[NG][4];
 #pragma unroll
-            for (int g = 0; g < NG; ++g) acc[g][0] = acc[g][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int g = 0; g < NG; ++g) acc[g][0] = acc[g][1] = acc[g][2] = acc[g][3] = f32x4{0.f, 0.f, 0.f, 0.f};
             static_for<0, HT>([&](auto ic) {
                 constexpr int ul = decltype(ic)::value;
 #pragma unroll
                 for (int g = 0; g < NG; ++g) {
                     acc[g][0] = mfma4_bcast<ul>(da[0], wreg[g][4 * ul + 0], acc[g][0]);
-                    acc[g][1] = mfma4_bcast<ul>(da[1], wreg[g][4 * ul + 1], acc[g][1]);
+                    acc[g][1 % kBwdAcc] = mfma4_bcast<ul>(da[1], wreg[g][4 * ul + 1], acc[g][1 % kBwdAcc]);
                 }
 #pragma unroll
                 for (int g = 0; g < NG; ++g) {
-                    acc[g][0] = mfma4_bcast<ul>(da[2], wreg[g][4 * ul + 2], acc[g][0]);
-                    acc[g][1] = mfma4_bcast<ul>(da[3], wreg[g][4 * ul + 3], acc[g][1]);
+                    acc[g][2 % kBwdAcc] = mfma4_bcast<ul>(da[2], wreg[g][4 * ul + 2], acc[g][2 % kBwdAcc]);
+                    acc[g][3 % kBwdAcc] = mfma4_bcast<ul>(da[3], wreg[g][4 * ul + 3], acc[g][3 % kBwdAcc]);
                 }
             });
             // lane l of group g holds column 64g + l for the four series
 #pragma unroll
             for (int g = 0; g < NG; ++g)
-                *reinterpret_cast<f32x4 *>(&part[par][w][(64 * g + lane) * 4]) = acc[g][0] + acc[g][1];
+                *reinterpret_cast<f32x4 *>(&part[par][w][(64 * g + lane) * 4]) =
+                    kBwdAcc == 4 ? (acc[g][0] + acc[g][1]) + (acc[g][2] + acc[g][3]) : kBwdAcc == 2 ? acc[g][0] + acc[g][1] : acc[g][0];
+            // per-thread operands of the next position (staged at least one barrier ago)
+            {
+                const int i1 = min(i + 1, n - 1);
+                gt = lc[i1 % CH][0][threadIdx.x];
+                o = lc[i1 % CH][1][threadIdx.x];
+            }
+            // one position before the end of a chunk: stage the next chunk, request the one after it
+            // (after this thread has read its operands of the chunk's last position)
+            if (ii == CH - 2 && (c + 1) * CH < n) {
+                flush_chunk(c + 1);
+                load_chunk(c + 2);
+            }
             lds_barrier();
             // ---- sums of the four partials: recurrent dh of this lane; input gradient
             {
@@ -428,13 +445,7 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
                 dhreg = (part[par][0][e] + part[par][1][e]) + (part[par][2][e] + part[par][3][e]);
             }
             const float dxv = (part[par][0][dx_el] + part[par][1][dx_el]) + (part[par][2][dx_el] + part[par][3][dx_el]);
-            // last position of a chunk: stage the next chunk, request the one after it (ahead of this
-            // position's store: the wait for the staged registers only meets stores a position old)
-            if (ii == CH - 1 && i + 1 < n) {
-                flush_chunk(c + 1);
-                load_chunk(c + 2);
-            }
-            a.gdst[(pb * KX + (dx_el >> 2)) * 16 + 4 * q + (dx_el & 3)] = dxv;
+            (a.gdst + ((size_t)p * a.NB + bt) * (KX * 16))[(dx_el >> 2) * 16 + 4 * q + (dx_el & 3)] = dxv;
             // ---- C: weight gradient, k = the four series
             {
                 float xb[CT];
