@@ -66,6 +66,145 @@ def stage_model(cfg, name):
     return None, 0.0, ""
 
 
+def lstm_stash_bytes(cfg, name):
+    """Algorithmic HBM bytes of one LSTM layer launch (fp32): the forward pass reads its input and writes the
+    activation stash (four activated gates, cell state, hidden state per unit); the reverse pass reads the
+    stash, the previous cell and hidden state, the input and the arriving gradient, and writes the input
+    gradient.  The last layer of a block >= 1 also reads the block input and writes the block output."""
+    B, I, H, h = cfg.B, cfg.I, cfg.H, cfg.hidden
+    P = cfg.T - I - H + 1
+    layer = int(name.rsplit("l", 1)[1])
+    k_in = I + cfg.n_cat if layer == 0 else h
+    ends, n = [], 0
+    for blk in cfg.blocks:
+        n += len(blk)
+        ends.append(n - 1)
+    residual = layer in ends[1:]
+    if name.startswith("lstm_forward"):
+        per = k_in + 6 * h + (2 * h if residual else 0)
+    else:
+        per = 6 * h + 2 * h + k_in + h + k_in
+    return 4.0 * per * B * P
+
+
+def price(cfg, name, ms):
+    """Roofline position of one stage: {"ms", bound, achieved, frac, ...}.  An LSTM layer is priced against
+    both of its roofs (fp32 MFMA flops and HBM bytes of the stash design) and reported against the tighter one."""
+    b, amt, _ = stage_model(cfg, name)
+    e = {"ms": round(ms, 4)}
+    if b == "mfma":
+        tf = amt / (ms * 1e-3) / 1e12
+        gbs = lstm_stash_bytes(cfg, name) / (ms * 1e-3) / 1e9
+        e.update(tflops=round(tf, 2), frac_mfma_peak=round(tf / PEAK_FP32_MFMA_TFLOPS, 4),
+                 gbs=round(gbs, 1), frac_hbm_peak=round(gbs / PEAK_HBM_GBS, 4))
+        e["bound"] = "mfma" if e["frac_mfma_peak"] >= e["frac_hbm_peak"] else "hbm"
+    elif b == "hbm":
+        gbs = amt / (ms * 1e-3) / 1e9
+        e.update(gbs=round(gbs, 1), frac_hbm_peak=round(gbs / PEAK_HBM_GBS, 4), bound="hbm")
+    return e
+
+
+def roofline_of(cfg, name, entry):
+    """The `roofline` object of the JSON line for the stage `name` priced in `entry`."""
+    if entry.get("bound") == "mfma":
+        achieved, peak, unit, frac = entry["tflops"], PEAK_FP32_MFMA_TFLOPS, "TFLOP/s", entry["frac_mfma_peak"]
+    elif entry.get("bound") == "hbm":
+        achieved, peak, unit, frac = entry["gbs"], PEAK_HBM_GBS, "GB/s", entry["frac_hbm_peak"]
+    else:
+        achieved, peak, unit, frac = 0.0, 1.0, "", 0.0
+    out = {"kernel": name, "bound": entry.get("bound"), "achieved": achieved, "peak": peak, "unit": unit, "frac": frac,
+           "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.B), {}).get(name),
+           "avg_launch_ms": entry["ms"]}
+    if "frac_mfma_peak" in entry and "frac_hbm_peak" in entry:
+        out["other_bound"] = ({"bound": "hbm", "achieved": entry["gbs"], "unit": "GB/s", "frac": entry["frac_hbm_peak"]}
+                              if entry["bound"] == "mfma" else
+                              {"bound": "mfma", "achieved": entry["tflops"], "unit": "TFLOP/s", "frac": entry["frac_mfma_peak"]})
+    return out
+
+
+def oracle_baseline(cfg, inp, loss, threads, budget_flops):
+    """The float64 CPU oracle as it stands, timed on the host cores on a prefix of the series of the batch
+    whose matrix work stays below `budget_flops` (the whole batch if it fits)."""
+    from oracle import oracle
+    from paper_1907_03329_amd import synth
+    if threads > 0:
+        oracle.set_num_threads(threads)
+    flops = 3.0 * sum(stage_model(cfg, f"lstm_forward_l{l}")[1] for l in range(cfg.n_layers))
+    nb = cfg.B
+    while nb > 64 and flops * nb / cfg.B > budget_flops:
+        nb //= 2
+    sub = synth.take_series(inp, range(nb))
+    scfg = cfg.with_(B=nb)
+    reps = 2
+
+    def oracle_step():
+        f = oracle.forward(scfg, sub["y"], sub["lengths"], sub["es_params"], sub["weights"], want_forecasts=True,
+                           categories=sub.get("categories"))
+        oracle.backward(scfg, f, want_adjoints=False)
+        return f
+
+    f = oracle_step()                                  # warm-up, also checks the GPU loss when nb == B
+    t1 = time.perf_counter()
+    for _ in range(reps):
+        oracle_step()
+    cpu_s = (time.perf_counter() - t1) / reps
+    cpu = {"value": round(nb * cfg.T / cpu_s, 1), "unit": "series-steps/s", "cores": oracle.max_threads(),
+           "kind": "oracle",
+           "sample": f"{nb} of {cfg.B} series of the same batch, forward+backward, float64, {reps} reps",
+           "ms_per_step_sample": round(1e3 * cpu_s, 1)}
+    if nb == cfg.B:
+        cpu["loss_rel_diff_vs_gpu"] = abs(loss - f.loss) / abs(f.loss)
+    return cpu
+
+
+def measure(cfg, inp, steps, warmup, profile_steps, torch, binding, with_update=False):
+    """Times `steps` training steps of one workload (inputs already on the device) and the stages of
+    `profile_steps` more with the library's HIP events.  Returns a dict of results."""
+    dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
+    step = binding.TrainingStep(cfg, want_forecasts=True)
+    if cfg.n_cat:
+        step.set_categories(dev["categories"])
+    if with_update:
+        opt = binding.AdamConfig(1e-4, 1e-4, 0.9, 0.999, 1e-8, 20.0)
+        mom = [torch.zeros_like(dev["weights"]), torch.zeros_like(dev["weights"]),
+               torch.zeros_like(dev["es_params"]), torch.zeros_like(dev["es_params"])]
+        counter = [0]
+
+    def one_step():
+        step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+        step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+        if with_update:
+            counter[0] += 1
+            binding.esrnn_adam_update(step.handle, opt, counter[0], dev["weights"], step.grad_weights, mom[0], mom[1],
+                                      dev["es_params"], step.grad_es_params, mom[2], mom[3], step.workspace)
+
+    for _ in range(warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    loss = float(step.loss.item())
+    # per-stage durations: HIP events recorded by the library on the launch stream
+    binding.esrnn_profile_enable(step.handle, True)
+    for _ in range(max(1, profile_steps)):
+        one_step()
+        binding.esrnn_profile_collect(step.handle)
+    stages = binding.esrnn_profile_read(step.handle)
+    binding.esrnn_profile_enable(step.handle, False)
+    stage_ms = {name: tot / max(cnt, 1) for name, tot, cnt in stages if cnt}
+    report = {name: price(cfg, name, ms) for name, ms in stage_ms.items()}
+    dominant = max(stage_ms, key=stage_ms.get)
+    step.close()
+    del step, dev
+    per_step = elapsed / steps
+    return {"ms_per_step": round(1e3 * per_step, 4), "value": round(cfg.B * cfg.T / per_step, 1),
+            "window_steps_per_s": round(cfg.B * cfg.P / per_step, 1), "loss": loss, "stages": report,
+            "sum_stage_ms": round(sum(stage_ms.values()), 4), "roofline": roofline_of(cfg, dominant, report[dominant])}
+
+
 def es_window_sweep(args, torch, binding, synth):
     """Smoothing and window stages alone at large batch sizes (their HBM roofline is only meaningful there:
     at the benchmark batch a 72-step dependent chain on 64 waves is latency-bound)."""
@@ -105,12 +244,22 @@ def es_window_sweep(args, torch, binding, synth):
         del ws, ges, dev
 
 
+def config_summary(cfg, with_update=False):
+    return {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "seasons": [m for m in (cfg.m1, cfg.m2) if m],
+            "I": cfg.I, "H": cfg.H, "hidden": cfg.hidden, "dilations": [list(b) for b in cfg.blocks],
+            "tau": cfg.tau, "lambda_lv": cfg.lambda_lv, "window_steps": cfg.B * cfg.P,
+            "parameter_update": bool(with_update), "categories": cfg.n_cat}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="quarterly")
+    ap.add_argument("--workload", default="quarterly",
+                    help="the headline workload is quarterly (B=4096); with the default, the JSON line also carries "
+                         "the other four workloads under \"workloads\" unless --only-headline is given")
+    ap.add_argument("--only-headline", action="store_true", help="time the named workload only")
     ap.add_argument("--batch", type=int, default=0, help="override the number of series")
     ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -149,10 +298,6 @@ def main():
         cfg = cfg.with_(n_cat=args.categories)
     inp = synth.make_inputs(cfg, seed=0)
     torch.cuda.set_device(0)
-    dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
-    step = binding.TrainingStep(cfg, want_forecasts=True)
-    if args.categories:
-        step.set_categories(dev["categories"])
 
     if args.copy_probe_mib:
         src = torch.ones(args.copy_probe_mib * 262144, dtype=torch.float32, device="cuda")
@@ -163,6 +308,10 @@ def main():
 
     if args.predict:
         import numpy as np
+        dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
+        step = binding.TrainingStep(cfg, want_forecasts=True)
+        if args.categories:
+            step.set_categories(dev["categories"])
         n = torch.from_numpy(np.full(cfg.B, cfg.T - cfg.H, dtype=np.int32)).cuda()
         for _ in range(args.warmup):
             out = step.predict(dev["y"], n, dev["es_params"], dev["weights"])
@@ -185,123 +334,55 @@ def main():
                           "mean_forecast": float(out.mean().item())}))
         return
 
-    if args.with_update:
-        opt = binding.AdamConfig(1e-4, 1e-4, 0.9, 0.999, 1e-8, 20.0)
-        mom = [torch.zeros_like(dev["weights"]), torch.zeros_like(dev["weights"]),
-               torch.zeros_like(dev["es_params"]), torch.zeros_like(dev["es_params"])]
-        counter = [0]
-
-    def one_step():
-        step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
-        step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
-        if args.with_update:
-            counter[0] += 1
-            binding.esrnn_adam_update(step.handle, opt, counter[0], dev["weights"], step.grad_weights, mom[0], mom[1],
-                                      dev["es_params"], step.grad_es_params, mom[2], mom[3], step.workspace)
-
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
-    series_steps = cfg.B * cfg.T
-    value = series_steps / (elapsed / args.steps)
-    loss = float(step.loss.item())
-
-    # per-stage durations: HIP events recorded by the library on the launch stream
-    binding.esrnn_profile_enable(step.handle, True)
-    for _ in range(max(1, args.profile_steps)):
-        one_step()
-        binding.esrnn_profile_collect(step.handle)
-    stages = binding.esrnn_profile_read(step.handle)
-    binding.esrnn_profile_enable(step.handle, False)
-    stage_ms = {name: tot / max(cnt, 1) for name, tot, cnt in stages}
-    total_stage_ms = sum(stage_ms.values())
-    dominant = max(stage_ms, key=stage_ms.get)
-    bound, amount, _ = stage_model(cfg, dominant)
-    dur_s = stage_ms[dominant] * 1e-3
-    if bound == "mfma":
-        achieved, peak, unit = amount / dur_s / 1e12, PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"
-    elif bound == "hbm":
-        achieved, peak, unit = amount / dur_s / 1e9, PEAK_HBM_GBS, "GB/s"
-    else:
-        achieved, peak, unit = 0.0, 1.0, ""
-    roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, cfg.B), {}).get(dominant),
-                "avg_launch_ms": round(stage_ms[dominant], 4)}
-    stage_report = {}
-    for name, ms in stage_ms.items():
-        b, amt, _ = stage_model(cfg, name)
-        entry = {"ms": round(ms, 4)}
-        if b == "mfma":
-            entry["tflops"] = round(amt / (ms * 1e-3) / 1e12, 2)
-            entry["frac_mfma_peak"] = round(entry["tflops"] / PEAK_FP32_MFMA_TFLOPS, 4)
-        elif b == "hbm":
-            entry["gbs"] = round(amt / (ms * 1e-3) / 1e9, 1)
-            entry["frac_hbm_peak"] = round(entry["gbs"] / PEAK_HBM_GBS, 4)
-        stage_report[name] = entry
-
+    m = measure(cfg, inp, args.steps, args.warmup, args.profile_steps, torch, binding, with_update=args.with_update)
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import oracle
-        if args.cpu_threads > 0:
-            oracle.set_num_threads(args.cpu_threads)
-        # the full workload if it is small enough, else a prefix of the series
-        flops = 3.0 * sum(stage_model(cfg, f"lstm_forward_l{l}")[1] for l in range(cfg.n_layers))
-        nb = cfg.B
-        while nb > 64 and flops * nb / cfg.B > 1.2e11:
-            nb //= 2
-        sub = synth.take_series(inp, range(nb))
-        scfg = cfg.with_(B=nb)
-        reps = 2
+        cpu = oracle_baseline(cfg, inp, m["loss"], args.cpu_threads, 1.2e11)
 
-        def oracle_step():
-            f = oracle.forward(scfg, sub["y"], sub["lengths"], sub["es_params"], sub["weights"], want_forecasts=True,
-                               categories=sub.get("categories"))
-            oracle.backward(scfg, f, want_adjoints=False)
-            return f
-
-        f = oracle_step()                                  # warm-up, also checks the GPU loss when nb == B
-        t1 = time.perf_counter()
-        for _ in range(reps):
-            oracle_step()
-        cpu_s = (time.perf_counter() - t1) / reps
-        cpu = {"value": round(nb * cfg.T / cpu_s, 1), "unit": "series-steps/s", "cores": oracle.max_threads(),
-               "kind": "oracle",
-               "sample": f"{nb} of {cfg.B} series of the same batch, forward+backward, float64, {reps} reps",
-               "ms_per_step_sample": round(1e3 * cpu_s, 1)}
-        if nb == cfg.B:
-            cpu["loss_rel_diff_vs_gpu"] = abs(loss - f.loss) / abs(f.loss)
+    # The other workloads, when the default headline run is asked for: same measurement, fewer steps, a
+    # smaller sample for the oracle, so that the whole run stays within a few minutes.
+    others = None
+    plain = (args.workload == "quarterly" and not args.batch and not args.categories and not args.with_update
+             and not args.only_headline)
+    if plain:
+        others = {}
+        for name in synth.CONFIG_ORDER:
+            if name == cfg.name:
+                continue
+            ocfg = synth.CONFIGS[name]
+            oinp = synth.make_inputs(ocfg, seed=0)
+            om = measure(ocfg, oinp, max(10, args.steps // 4), max(3, args.warmup // 2), max(3, args.profile_steps // 4),
+                         torch, binding)
+            entry = {"config": config_summary(ocfg), "ms_per_step": om["ms_per_step"], "value": om["value"],
+                     "unit": "series-steps/s", "window_steps_per_s": om["window_steps_per_s"], "loss": om["loss"],
+                     "roofline": om["roofline"], "stages": om["stages"], "sum_stage_ms": om["sum_stage_ms"]}
+            if not args.no_cpu_baseline:
+                entry["cpu_baseline"] = oracle_baseline(ocfg, oinp, om["loss"], args.cpu_threads, 3e10)
+            others[name] = entry
 
     out = {
         "metric": "training-step series-steps/sec (fwd+bwd)",
-        "value": round(value, 1),
+        "value": m["value"],
         "unit": "series-steps/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": m["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "seasons": [m for m in (cfg.m1, cfg.m2) if m],
-                   "I": cfg.I, "H": cfg.H, "hidden": cfg.hidden, "dilations": [list(b) for b in cfg.blocks],
-                   "tau": cfg.tau, "lambda_lv": cfg.lambda_lv, "window_steps": cfg.B * cfg.P,
-                   "parameter_update": bool(args.with_update), "categories": cfg.n_cat},
-        "window_steps_per_s": round(cfg.B * cfg.P / (elapsed / args.steps), 1),
-        "loss": loss,
-        "roofline": roofline,
+        "config": config_summary(cfg, args.with_update),
+        "window_steps_per_s": m["window_steps_per_s"],
+        "loss": m["loss"],
+        "roofline": m["roofline"],
         "cpu_baseline": cpu,
-        "stages": stage_report,
-        "sum_stage_ms": round(total_stage_ms, 4),
+        "stages": m["stages"],
+        "sum_stage_ms": m["sum_stage_ms"],
     }
+    if others is not None:
+        out["workloads"] = others
     print(json.dumps(out))
 
 
