@@ -268,3 +268,47 @@ def adam_update(params, grads, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8,
         new_v.append(v2)
     return new_p, new_m, new_v
 
+
+
+def adam_update_indexed(weights, grad_weights, m_w, v_w, step, es_store, grad_es, m_es, v_es, counts, index,
+                        lr, beta1=0.9, beta2=0.999, eps=1e-8, clip_norm=0.0):
+    """One training-loop update when the batch is a subset of a store of N series (Section 3.3: every series
+    has its own smoothing parameters, N (2 + S) in all, trained jointly with the shared weights; Table 5:
+    training runs over epochs of batches).
+
+    The shared weights take a plain Adam step with step counter ``step``.  The per-series parameters live in
+    ``es_store`` [K, N] with moments ``m_es``, ``v_es`` [K, N] and one update counter per series ``counts``
+    [N]; only the columns named by ``index`` [B] (distinct) are touched: column index[b] takes an Adam step
+    with gradient grad_es[:, b] and its own counter counts[index[b]] + 1 in the bias correction, as if that
+    series were optimised on its own and simply had no step when it is not in the batch.  The gradient is
+    clipped by its global L2 norm over the weights and the batch's per-series gradients, as in adam_update.
+    Reading: the paper names neither the optimiser nor how per-series state is handled between batches.
+    Returns new (weights, m_w, v_w, es_store, m_es, v_es, counts); inputs are not modified."""
+    gw = np.asarray(grad_weights, dtype=np.float64)
+    ge = np.asarray(grad_es, dtype=np.float64)
+    index = np.asarray(index, dtype=np.int64)
+    assert len(np.unique(index)) == len(index), "a series may appear once per batch"
+    lr_w, lr_e = lr
+    scale = 1.0
+    if clip_norm > 0.0:
+        norm = np.sqrt(float(np.sum(gw * gw)) + float(np.sum(ge * ge)))
+        scale = min(1.0, clip_norm / (norm + 1e-6))
+    # shared weights
+    g = gw * scale
+    m_w2 = beta1 * np.asarray(m_w, dtype=np.float64) + (1.0 - beta1) * g
+    v_w2 = beta2 * np.asarray(v_w, dtype=np.float64) + (1.0 - beta2) * g * g
+    w2 = np.asarray(weights, dtype=np.float64) - lr_w * (m_w2 / (1.0 - beta1 ** step)) / (
+        np.sqrt(v_w2 / (1.0 - beta2 ** step)) + eps)
+    # per-series parameters, one series at a time
+    es2 = np.array(es_store, dtype=np.float64)
+    m_e2 = np.array(m_es, dtype=np.float64)
+    v_e2 = np.array(v_es, dtype=np.float64)
+    counts2 = np.array(counts, dtype=np.int64)
+    for b, n in enumerate(index):
+        t = int(counts2[n]) + 1
+        g = ge[:, b] * scale
+        m_e2[:, n] = beta1 * m_e2[:, n] + (1.0 - beta1) * g
+        v_e2[:, n] = beta2 * v_e2[:, n] + (1.0 - beta2) * g * g
+        es2[:, n] -= lr_e * (m_e2[:, n] / (1.0 - beta1 ** t)) / (np.sqrt(v_e2[:, n] / (1.0 - beta2 ** t)) + eps)
+        counts2[n] = t
+    return w2, m_w2, v_w2, es2, m_e2, v_e2, counts2
