@@ -205,6 +205,59 @@ def measure(cfg, inp, steps, warmup, profile_steps, torch, binding, with_update=
             "sum_stage_ms": round(sum(stage_ms.values()), 4), "roofline": roofline_of(cfg, dominant, report[dominant])}
 
 
+def epoch_benchmark(args, cfg, torch, binding, synth):
+    """One epoch over a store of N series in random batches of B: esrnn_gather_batch, esrnn_forward,
+    esrnn_backward, esrnn_adam_update_indexed per batch (a last partial batch is dropped).  The paper trains
+    15 epochs on at most 24000 quarterly series (Tables 2 and 5); its 8.94 min are context, other hardware."""
+    import numpy as np
+    N = args.epoch
+    store = synth.make_inputs(cfg.with_(B=N), seed=0, ragged=True)
+    d = {k: torch.from_numpy(v).cuda() for k, v in store.items()}
+    step = binding.TrainingStep(cfg, want_forecasts=False)
+    opt = binding.AdamConfig(1e-4, 1e-4, 0.9, 0.999, 1e-8, 20.0)
+    w = d["weights"]
+    m_w, v_w = torch.zeros_like(w), torch.zeros_like(w)
+    m_e, v_e = torch.zeros_like(d["es_params"]), torch.zeros_like(d["es_params"])
+    counts = torch.zeros(N, dtype=torch.int32, device="cuda")
+    y = torch.empty((cfg.T, cfg.B), dtype=torch.float32, device="cuda")
+    n = torch.empty(cfg.B, dtype=torch.int32, device="cuda")
+    es = torch.empty((cfg.K, cfg.B), dtype=torch.float32, device="cuda")
+    nb = N // cfg.B
+    rng = np.random.default_rng(0)
+    t = [0]
+
+    def epoch():
+        perm = torch.from_numpy(rng.permutation(N).astype(np.int32)).cuda()
+        for s in range(nb):
+            idx = perm[s * cfg.B:(s + 1) * cfg.B]
+            t[0] += 1
+            binding.esrnn_gather_batch(step.handle, d["y"], d["lengths"], d["es_params"], idx, y, n, es)
+            step.forward(y, n, es, w)
+            step.backward(y, n, es, w)
+            binding.esrnn_adam_update_indexed(step.handle, opt, t[0], w, step.grad_weights, m_w, v_w, d["es_params"],
+                                              step.grad_es_params, m_e, v_e, counts, idx, step.workspace)
+
+    epoch()                                   # warm-up epoch
+    torch.cuda.synchronize()
+    loss0 = float(step.loss.item())
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        epoch()
+    torch.cuda.synchronize()
+    el = (time.perf_counter() - t0) / reps
+    series_steps = float(store["lengths"][:nb * cfg.B].sum())      # valid time steps; ragged lengths
+    print(json.dumps({"metric": "training series-steps/sec over an epoch (gather + fwd + bwd + indexed Adam)",
+                      "value": round(nb * cfg.B * cfg.T / el, 1), "unit": "series-steps/s", "n_gpus": 1,
+                      "ms_per_epoch": round(1e3 * el, 3), "batches_per_epoch": nb, "ms_per_batch": round(1e3 * el / nb, 4),
+                      "higher_is_better": True, "dtype": "f32", "data": "synthetic, ragged lengths",
+                      "config": {"workload": cfg.name, "N": N, "B": cfg.B, "T": cfg.T},
+                      "unpadded_series_steps_per_s": round(series_steps / el, 1),
+                      "loss_after_first_epoch": loss0, "loss_after_last_epoch": float(step.loss.item()),
+                      "epochs_timed": reps}))
+    step.close()
+
+
 def es_window_sweep(args, torch, binding, synth):
     """Smoothing and window stages alone at large batch sizes (their HBM roofline is only meaningful there:
     at the benchmark batch a 72-step dependent chain on 64 waves is latency-bound)."""
@@ -276,6 +329,10 @@ def main():
     ap.add_argument("--predict", action="store_true",
                     help="time esrnn_predict (out-of-sample forecasts of every series, lengths T - H) instead of "
                          "the training step; one JSON line, not the headline metric")
+    ap.add_argument("--epoch", type=int, default=0,
+                    help="train one epoch over a store of this many synthetic series of the workload's shape (the paper's "
+                         "quarterly set has 24000, Table 2) in batches of B: gather, forward, backward, indexed Adam "
+                         "update per batch; reports series-steps/s over the epoch instead of the headline line")
     ap.add_argument("--es-window-sweep", default="",
                     help="comma-separated batch sizes: time only the smoothing and window stages (forward and "
                          "adjoint) at each, one JSON line per size, instead of the training-step benchmark")
@@ -305,6 +362,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.epoch:
+        epoch_benchmark(args, cfg, torch, binding, synth)
+        return
 
     if args.predict:
         import numpy as np

@@ -166,6 +166,34 @@ esrnn_status esrnn_adam_update(esrnn_handle *h, const esrnn_adam_config *opt, in
                                void *workspace, void *stream);
 
 /*
+ * Training over a store of N series, a batch of B at a time (Section 3.3: every series has its own smoothing
+ * parameters, N (2 + S) in all, trained jointly with the shared weights; Table 5: training runs for epochs of
+ * batches).  The store holds y_store [T][N], lengths_store [N], es_store [K][N], the Adam moments of the
+ * per-series parameters m_es_store, v_es_store [K][N] (zero before the first step) and one update counter per
+ * series counts_store [N] (int32, zero before the first step); index [B] (int32, distinct values in [0, N))
+ * names the series of the batch.  All device pointers.
+ *
+ * esrnn_gather_batch copies the batch's series, lengths and parameters out of the store into the [T][B], [B]
+ * and [K][B] arrays that esrnn_forward / esrnn_backward take.
+ *
+ * esrnn_adam_update_indexed is esrnn_adam_update for such a batch: the shared weights take the Adam step with
+ * counter `step`; of the store only the columns named by index are touched, column index[b] with the gradient
+ * grad_es_params[:, b] and, in the bias correction, its own counter counts_store[index[b]] + 1 (a series is
+ * optimised as if on its own and simply has no step while it is not in a batch; a reading: the paper names
+ * neither the optimiser nor the handling of per-series state between batches).  Clipping is by the global L2
+ * norm over the weight gradient and the batch's per-series gradients.  The counters of the batch's series
+ * are incremented.  Series outside the batch keep parameters, moments and counters bit for bit.
+ */
+esrnn_status esrnn_gather_batch(esrnn_handle *h, const float *y_store, const int32_t *lengths_store,
+                                const float *es_store, const int32_t *index, int32_t N,
+                                float *y, int32_t *lengths, float *es_params, void *stream);
+esrnn_status esrnn_adam_update_indexed(esrnn_handle *h, const esrnn_adam_config *opt, int32_t step,
+                                       float *weights, const float *grad_weights, float *m_weights, float *v_weights,
+                                       float *es_store, const float *grad_es_params, float *m_es_store,
+                                       float *v_es_store, int32_t *counts_store, const int32_t *index, int32_t N,
+                                       void *workspace, void *stream);
+
+/*
  * Out-of-sample forecasts (Section 3.4 "testing of the network", Eq. (4), (5)):
  * the H steps after each series' last observation, from the window of the last
  * I observations, de-normalised with the last level and re-seasonalised with

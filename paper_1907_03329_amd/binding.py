@@ -86,6 +86,11 @@ def load_library():
     lib.esrnn_set_categories.restype = C.c_int
     lib.esrnn_adam_update.argtypes = [vp, C.POINTER(AdamConfig), C.c_int32, fp, fp, fp, fp, fp, fp, fp, fp, vp, vp]
     lib.esrnn_adam_update.restype = C.c_int
+    lib.esrnn_gather_batch.argtypes = [vp, fp, i32p, fp, i32p, C.c_int32, fp, i32p, fp, vp]
+    lib.esrnn_gather_batch.restype = C.c_int
+    lib.esrnn_adam_update_indexed.argtypes = [vp, C.POINTER(AdamConfig), C.c_int32, fp, fp, fp, fp, fp, fp, fp, fp,
+                                              i32p, i32p, C.c_int32, vp, vp]
+    lib.esrnn_adam_update_indexed.restype = C.c_int
     lib.esrnn_predict.argtypes = [vp, fp, i32p, fp, fp, vp, fp, vp]
     lib.esrnn_predict_static.argtypes = [vp, fp, i32p, fp, fp, fp, vp]
     lib.esrnn_forecast_metrics.argtypes = [vp, fp, fp, fp, i32p, C.c_int32, fp, fp, vp]
@@ -297,6 +302,29 @@ def esrnn_adam_update(handle, opt: "AdamConfig", step, weights, grad_weights, m_
                                           _stream(stream))
     if st != ESRNN_OK:
         raise EsrnnError(st, "esrnn_adam_update")
+
+
+def esrnn_gather_batch(handle, y_store, lengths_store, es_store, index, y, lengths, es_params, stream=None) -> None:
+    import torch
+    f, i = torch.float32, torch.int32
+    st = load_library().esrnn_gather_batch(handle, _ptr(y_store, f), _ptr(lengths_store, i), _ptr(es_store, f),
+                                           _ptr(index, i), int(lengths_store.numel()), _ptr(y, f), _ptr(lengths, i),
+                                           _ptr(es_params, f), _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_gather_batch")
+
+
+def esrnn_adam_update_indexed(handle, opt: "AdamConfig", step, weights, grad_weights, m_weights, v_weights,
+                              es_store, grad_es_params, m_es_store, v_es_store, counts_store, index, workspace,
+                              stream=None) -> None:
+    import torch
+    f, i = torch.float32, torch.int32
+    st = load_library().esrnn_adam_update_indexed(
+        handle, C.byref(opt), int(step), _ptr(weights, f), _ptr(grad_weights, f), _ptr(m_weights, f),
+        _ptr(v_weights, f), _ptr(es_store, f), _ptr(grad_es_params, f), _ptr(m_es_store, f), _ptr(v_es_store, f),
+        _ptr(counts_store, i), _ptr(index, i), int(counts_store.numel()), _ptr(workspace), _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_adam_update_indexed")
 
 
 def esrnn_predict(handle, y, lengths, es_params, weights, workspace, forecasts, stream=None) -> None:

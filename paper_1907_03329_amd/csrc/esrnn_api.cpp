@@ -212,6 +212,37 @@ esrnn_status esrnn_adam_update(esrnn_handle *h, const esrnn_adam_config *opt, in
     return ESRNN_OK;
 }
 
+esrnn_status esrnn_gather_batch(esrnn_handle *h, const float *y_store, const int32_t *lengths_store,
+                                const float *es_store, const int32_t *index, int32_t N,
+                                float *y, int32_t *lengths, float *es_params, void *stream)
+{
+    if (!h || !y_store || !lengths_store || !es_store || !index || !y || !lengths || !es_params) return ESRNN_ERR_NULL;
+    if (N < 1) return ESRNN_ERR_CONFIG;
+    ESRNN_TRY(launch_gather_batch(h->plan, y_store, lengths_store, es_store, index, N, y, lengths, es_params,
+                                  static_cast<hipStream_t>(stream)));
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_adam_update_indexed(esrnn_handle *h, const esrnn_adam_config *opt, int32_t step,
+                                       float *weights, const float *grad_weights, float *m_weights, float *v_weights,
+                                       float *es_store, const float *grad_es_params, float *m_es_store,
+                                       float *v_es_store, int32_t *counts_store, const int32_t *index, int32_t N,
+                                       void *workspace, void *stream)
+{
+    if (!h || !opt || !weights || !grad_weights || !m_weights || !v_weights || !es_store || !grad_es_params ||
+        !m_es_store || !v_es_store || !counts_store || !index || !workspace)
+        return ESRNN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
+    if (step < 1 || N < 1 || !(opt->beta1 >= 0.0f && opt->beta1 < 1.0f) || !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) ||
+        !(opt->eps > 0.0f))
+        return ESRNN_ERR_CONFIG;
+    ESRNN_TRY(launch_adam_update_indexed(h->plan, *opt, step, weights, grad_weights, m_weights, v_weights, es_store,
+                                         grad_es_params, m_es_store, v_es_store, counts_store, index, N,
+                                         static_cast<float *>(workspace), static_cast<hipStream_t>(stream)));
+    h->forward_done = false;
+    return ESRNN_OK;
+}
+
 esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengths, const float *es_params,
                            const float *weights, void *workspace, float *forecasts, void *stream)
 {

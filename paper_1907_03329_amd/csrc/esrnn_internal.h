@@ -129,6 +129,12 @@ hipError_t launch_reduce_weight_grads(const Plan &pl, float *ws, float *grad_wei
 hipError_t launch_adam_update(const Plan &pl, const esrnn_adam_config &opt, int step, float *weights,
                               const float *grad_weights, float *m_w, float *v_w, float *es_params,
                               const float *grad_es, float *m_es, float *v_es, float *ws, hipStream_t st);
+hipError_t launch_gather_batch(const Plan &pl, const float *store_y, const int32_t *store_len, const float *store_es,
+                               const int32_t *index, int N, float *y, int32_t *len, float *es, hipStream_t st);
+hipError_t launch_adam_update_indexed(const Plan &pl, const esrnn_adam_config &opt, int step, float *weights,
+                                      const float *grad_weights, float *m_w, float *v_w, float *es_store,
+                                      const float *grad_es, float *m_es, float *v_es, int32_t *counts,
+                                      const int32_t *index, int N, float *ws, hipStream_t st);
 hipError_t launch_extend_lengths(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st);
 hipError_t launch_forecast_tail(const Plan &pl, const int32_t *lengths, float *ws, float *out, hipStream_t st);
 hipError_t launch_forecast_metrics(const Plan &pl, const float *forecasts, const float *actuals, const float *y,
