@@ -329,6 +329,10 @@ def main():
     ap.add_argument("--predict", action="store_true",
                     help="time esrnn_predict (out-of-sample forecasts of every series, lengths T - H) instead of "
                          "the training step; one JSON line, not the headline metric")
+    ap.add_argument("--ragged", default="", choices=["", "sorted", "unsorted"],
+                    help="draw ragged lengths (the fraction 652/912 .. 1 of T, the range of lengths of the paper's hourly "
+                         "series, Table 3) and time the training step with the series sorted by length or in random "
+                         "order; the JSON line also carries the full-length time of the same batch")
     ap.add_argument("--epoch", type=int, default=0,
                     help="train one epoch over a store of this many synthetic series of the workload's shape (the paper's "
                          "quarterly set has 24000, Table 2) in batches of B: gather, forward, backward, indexed Adam "
@@ -365,6 +369,29 @@ def main():
 
     if args.epoch:
         epoch_benchmark(args, cfg, torch, binding, synth)
+        return
+
+    if args.ragged:
+        import numpy as np
+        full = measure(cfg, inp, args.steps, args.warmup, args.profile_steps, torch, binding)
+        rng = np.random.default_rng(1)
+        lo = max(int(np.ceil(cfg.T * 652.0 / 912.0)), cfg.I + cfg.H + max(cfg.m1, cfg.m2, 2))
+        n = rng.integers(lo, cfg.T + 1, size=cfg.B).astype(np.int32)
+        if args.ragged == "sorted":
+            n = np.sort(n)[::-1].copy()
+        rinp = dict(inp)
+        rinp["lengths"] = n
+        rinp["y"] = inp["y"].copy()
+        rinp["y"][np.arange(cfg.T)[:, None] >= n[None, :]] = 1.0
+        m = measure(cfg, rinp, args.steps, args.warmup, args.profile_steps, torch, binding)
+        frac = float(n.sum()) / (cfg.B * cfg.T)
+        print(json.dumps({"metric": "training-step series-steps/sec (fwd+bwd), ragged batch", "order": args.ragged,
+                          "value": round(float(n.sum()) / (m["ms_per_step"] * 1e-3), 1), "unit": "unpadded series-steps/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": m["ms_per_step"],
+                          "ms_per_step_full_length": full["ms_per_step"], "filled_fraction": round(frac, 4),
+                          "time_fraction": round(m["ms_per_step"] / full["ms_per_step"], 4),
+                          "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+                          "config": config_summary(cfg), "stages": m["stages"]}))
         return
 
     if args.predict:

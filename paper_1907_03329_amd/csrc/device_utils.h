@@ -46,6 +46,14 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// maximum over the ACTIVE lanes of the wave, the same value in every lane (wave-uniform)
+__device__ __forceinline__ int wave_max_int(int v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = max(v, __shfl_xor(v, off, 64));
+    return __builtin_amdgcn_readfirstlane(v);
+}
+
 // sum over the 16 lanes that share lane/16
 __device__ __forceinline__ float group16_sum(float v)
 {

@@ -18,6 +18,8 @@ __device__ __forceinline__ int clamp_len(int len, int T) { return len < 0 ? 0 : 
 struct PrepArgs {
     const int32_t *lengths;
     Scalars *sc;
+    int32_t *pmax;       // [NB] window positions needed by the longest series of every 16-series tile
+    int NB;
     int B, T, I, H;
     int cs_per_window;   // cell-state values per valid window in the cell-state penalty: hidden * blocks
 };
@@ -60,6 +62,20 @@ __device__ void prep_body(const PrepArgs &pa)
         sc->inv_n_lv = s_lv[0] > 0.0 ? (float)(1.0 / s_lv[0]) : 0.0f;
         const double n_cs = s_pin[0] / (double)H * (double)pa.cs_per_window;   // valid windows x hidden x blocks
         sc->inv_n_cs = n_cs > 0.0 ? (float)(1.0 / n_cs) : 0.0f;
+    }
+}
+
+// Ragged batches (Section 8.1: padding multiplies the iterations of the recursions): every later kernel
+// stops a 16-series tile at the number of window positions its longest series has.  One thread per tile.
+__device__ void pmax_body(const PrepArgs &pa, int first_block, int n_blocks)
+{
+    for (int bt = (blockIdx.x - first_block) * 256 + threadIdx.x; bt < pa.NB; bt += n_blocks * 256) {
+        int best = 0;
+        for (int k = 0; k < kTileN; ++k) {
+            const int b = bt * kTileN + k;
+            if (b < pa.B) best = max(best, clamp_len(pa.lengths[b], pa.T) - pa.I - pa.H + 1);
+        }
+        pa.pmax[bt] = best;
     }
 }
 
@@ -216,6 +232,7 @@ __global__ void __launch_bounds__(256) setup_kernel(SetupArgs a)
     if (a.pack && z < a.L) pack_lstm_body(a.lstm[z]);
     else if (a.pack && z == a.L) pack_head_body(a.head);
     else if (blockIdx.x == 0) prep_body(a.prep);
+    else pmax_body(a.prep, 1, gridDim.x - 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -340,9 +357,13 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
             dst[k] = a.y[(size_t)(t < len ? t : 0) * a.B + (in_batch ? b : 0)];
         }
     };
+    // Ragged batches (Section 8.1): the sweep ends at the longest series of the wave.  Rows between a
+    // series' own length and that bound get the defined padding values; rows beyond it are neither written
+    // here nor read by any later kernel (their bounds are those of 16-series tiles, never larger).
+    const int t_end = wave_max_int(len);
     load_chunk(0, ybuf);
     int t0 = 0;
-    for (; t0 + CH <= a.T; t0 += CH) {
+    for (; t0 + CH <= t_end; t0 += CH) {
         load_chunk(t0 + CH, ynext);
 #pragma unroll
         for (int k = 0; k < CH; ++k) step(t0 + k, ybuf[k]);
@@ -351,7 +372,7 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
     }
 #pragma unroll
     for (int k = 0; k < CH; ++k)
-        if (t0 + k < a.T) step(t0 + k, ybuf[k]);
+        if (t0 + k < t_end) step(t0 + k, ybuf[k]);
     const float tot = wave_sum(lv_sum);
     if (lane == 0) a.lv_partial[blockIdx.x] = tot;
 }
@@ -366,7 +387,7 @@ __global__ void __launch_bounds__(256) window_forward_kernel(const float *__rest
                                                               float *__restrict__ X, float *__restrict__ Z,
                                                               int P, int NB, int Bp, int I, int H, int xrows, int zrows,
                                                               int p_per_wave, const int32_t *__restrict__ categories,
-                                                              int n_cat, int B)
+                                                              int n_cat, int B, const int32_t *__restrict__ pmax)
 {
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, n = lane & 15;
@@ -378,7 +399,8 @@ __global__ void __launch_bounds__(256) window_forward_kernel(const float *__rest
     const int col = bt * 16 + n;
     // Section 5.3: the one-hot block of the series' category follows the window (rows I .. I+n_cat-1)
     const int hot = (n_cat > 0 && col < B) ? I + categories[col] : -1;
-    for (int p = p0; p < p0 + p_per_wave && p < P; ++p) {
+    const int Pt = min(P, pmax[bt]);     // windows past the tile's longest series are not needed by any later kernel
+    for (int p = p0; p < p0 + p_per_wave && p < Pt; ++p) {
         const size_t tile = (size_t)p * NB + bt;
         const int t = p + I - 1;
         const float ut = u[(size_t)t * Bp + col];
@@ -434,12 +456,14 @@ __global__ void __launch_bounds__(256) window_backward_kernel(const float *__res
                                                                const float *__restrict__ u, const int32_t *__restrict__ lengths,
                                                                const Scalars *__restrict__ sc, float lambda,
                                                                float *__restrict__ gu, float *__restrict__ gv,
-                                                               int P, int NB, int B, int Bp, int T, int I, int H, int xrows, int zrows)
+                                                               int P_all, int NB, int B, int Bp, int T, int I, int H, int xrows, int zrows,
+                                                               const int32_t *__restrict__ pmax)
 {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long long)T * Bp) return;
     const int t = (int)(idx / Bp), col = (int)(idx % Bp);
     const int bt = col >> 4, n = col & 15;
+    const int P = min(P_all, pmax[bt]);      // window gradients past the tile's longest series do not exist
     float sv = 0.0f, su = 0.0f;
     for (int i = 0; i < I; ++i) {
         const int p = t - i;
@@ -496,8 +520,11 @@ __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
     extern __shared__ float ring[];
     const int lane = threadIdx.x;
     const int b = blockIdx.x * 64 + lane;
+    const int len = b < a.B ? clamp_len(a.lengths[b], a.T) : 0;
+    // the sweep starts at the last observation of the wave's longest series (rows beyond were not produced);
+    // taken while all lanes are still active
+    const int t_top = max(wave_max_int(len), 1) - 1;
     if (b >= a.B) return;   // no barriers in this kernel
-    const int len = clamp_len(a.lengths[b], a.T);
     float *ring1 = ring, *ring2 = ring + (size_t)a.m1 * 64;
     float alpha = a.es[b], g1 = 0.0f, g2 = 0.0f;
     if (NS >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
@@ -533,7 +560,6 @@ __global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
             c.s2[k] = NS >= 2 ? (a.S2 + row)[b] : 1.0f;
         }
     };
-    const int t_top = a.T - 1;
     float lt = a.lvl[(size_t)t_top * a.Bp + b];
     int i1 = NS >= 1 ? t_top % a.m1 : 0, i2 = NS >= 2 ? t_top % a.m2 : 0;   // ring slot of time t: t mod m
     // adjoint of the factor for time t + m, requested one step ahead of its use
@@ -780,10 +806,11 @@ hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *wei
     SetupArgs a{};
     a.L = pl.L;
     a.pack = weights != nullptr;
-    a.prep = PrepArgs{lengths, reinterpret_cast<Scalars *>(ws + pl.scalars), pl.B, pl.T, pl.I, pl.H,
-                      pl.h * pl.cfg.n_blocks};
+    a.prep = PrepArgs{lengths, reinterpret_cast<Scalars *>(ws + pl.scalars), reinterpret_cast<int32_t *>(ws + pl.pmax), pl.NB,
+                      pl.B, pl.T, pl.I, pl.H, pl.h * pl.cfg.n_blocks};
     if (!a.pack) {
-        setup_kernel<<<dim3(1, 1, 1), 256, 0, st>>>(a);
+        // block 0 counts the loss normalisers, the others find the position bound of every tile
+        setup_kernel<<<dim3(1 + std::min((pl.NB + 255) / 256, 63), 1, 1), 256, 0, st>>>(a);
         return hipGetLastError();
     }
     int max_total = 256;
@@ -800,7 +827,7 @@ hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *wei
     a.head = PackHeadArgs{weights + pl.Wa_off, weights + pl.ba_off, weights + pl.Wo_off, weights + pl.bo_off,
                           f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, b + hp.WoT, b + hp.WaT,
                           pl.h, pl.H, pl.HT, pl.MA, pl.MO, pl.OT};
-    const int blocks = std::min((max_total + 255) / 256, 64);   // the bodies loop over their elements
+    const int blocks = std::max(2, std::min((max_total + 255) / 256, 64));   // the bodies loop over their elements
     setup_kernel<<<dim3(blocks, 1, pl.L + 2), 256, 0, st>>>(a);
     return hipGetLastError();
 }
@@ -834,7 +861,8 @@ hipError_t launch_window_forward(const Plan &pl, const int32_t *categories, floa
     const int p_per_wave = pl.NB >= 2048 ? 8 : (pl.NB >= 512 ? 4 : 1);
     window_forward_kernel<<<dim3((pl.NB + 3) / 4, (pl.P + p_per_wave - 1) / p_per_wave), 256, 0, st>>>(ws + pl.u, ws + pl.v, ws + pl.X, ws + pl.Z,
                                                                          pl.P, pl.NB, pl.Bp, pl.I, pl.H, 4 * pl.IT,
-                                                                         pl.OP, p_per_wave, categories, pl.C, pl.B);
+                                                                         pl.OP, p_per_wave, categories, pl.C, pl.B,
+                                                                         reinterpret_cast<const int32_t *>(ws + pl.pmax));
     return hipGetLastError();
 }
 
@@ -852,7 +880,8 @@ hipError_t launch_window_backward(const Plan &pl, const int32_t *lengths, float 
     const long long n = (long long)pl.T * pl.Bp;
     window_backward_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
         ws + pl.gX, ws + pl.gO, ws + pl.u, lengths, reinterpret_cast<const Scalars *>(ws + pl.scalars), pl.cfg.lambda_lv,
-        ws + pl.gu, ws + pl.gv, pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, 4 * pl.IT, pl.OP);
+        ws + pl.gu, ws + pl.gv, pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, 4 * pl.IT, pl.OP,
+        reinterpret_cast<const int32_t *>(ws + pl.pmax));
     return hipGetLastError();
 }
 

@@ -66,6 +66,7 @@ struct Plan {
     size_t scalars;      // float[16]: see Scalars
     size_t sink;         // float[64]: where the lanes past the padded batch put their stores
     size_t len_ext;      // int32[B]: lengths extended by the horizon (out-of-sample forecasts)
+    size_t pmax;         // int32[NB]: window positions the series of a 16-series tile need (max over the tile), by setup
     size_t opt_partial;  // float[512]: sums of squares of the gradients, per workgroup (parameter update)
     size_t lvl, S1, S2, u, v, gu, gv;   // [T][Bp]
     size_t X, Z;         // TL(4*IT), TL(OP)

@@ -28,6 +28,7 @@ struct HeadArgs {
     const float *Z;         // TL(OP) targets
     const float *u, *S1, *S2;   // [T][Bp]
     const int32_t *lengths;
+    const int32_t *pmax;    // [NB] window positions the longest series of a tile has
     const Scalars *sc;
     float *O;               // TL(OP) outputs
     float *forecasts;       // [P][B][H] or null
@@ -186,6 +187,19 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
             load_ops(tn, pn, btn, nxt);
         }
         const int b = bt * 16 + n;
+        // Ragged batches: a tile past the longest series of its 16 holds no window.  Nothing was computed
+        // for it upstream and nothing downstream reads it; only its forecasts are defined (zero).
+        if (p >= a.pmax[bt]) {
+            if (a.forecasts && b < a.B) {
+#pragma unroll
+                for (int ks = 0; ks < OTMAX; ++ks) {
+                    const int j = 4 * ks + g;
+                    if (j < a.H) (a.forecasts + ((size_t)p * a.B + bt * 16) * a.H)[n * a.H + j] = 0.0f;
+                }
+            }
+            cur = nxt;
+            continue;
+        }
         int len = cur.len < 0 ? 0 : (cur.len > a.T ? a.T : cur.len);
         if (b >= a.B) len = 0;
         const bool valid = p < len - a.I - a.H + 1;
@@ -333,7 +347,7 @@ hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float 
     const int blocks = pl.n_head_waves / 4;
     HeadArgs a{f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, bk + hp.WoT, bk + hp.WaT,
                ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z, ws + pl.u, ws + pl.S1, ws + pl.S2, lengths,
-               reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.O, forecasts, ws + pl.loss_partial,
+               reinterpret_cast<const int32_t *>(ws + pl.pmax), reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.O, forecasts, ws + pl.loss_partial,
                ws + pl.gO, ws + pl.gTop, ws + pl.head_dw_partial,
                pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.head_dw_stride, pl.OP, pl.cfg.tau};
 #define X(HT_, MO_)                                              \

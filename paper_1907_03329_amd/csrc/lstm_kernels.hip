@@ -31,6 +31,7 @@ struct LstmFwdArgs {
     const float *resid;   // TL(HP) or null
     float *out;           // TL(HP) or null: resid + hid
     int P, NB, d;
+    const int32_t *pmax;  // [NB] positions the longest series of a tile has: the tile's chains stop there
     // cell-state penalty (Section 8.4) of a block's first layer, kernels instantiated with CP only
     const int32_t *lengths;
     float *cs_partial;    // [NB * gridDim.y] sums of squared cell states over valid window positions
@@ -46,6 +47,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
 
     const int lane = threadIdx.x & 63, bt = blockIdx.x;
     const int s = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
+    const int Pt = a.pmax[bt];      // positions past the tile's longest series are never computed (nor read later)
 
     float wreg[MTW][KT];
     f32x4 bias[MTW];
@@ -69,7 +71,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         n_valid = len - a.I - a.H + 1;
     }
 
-    for (int r = blockIdx.y; r < a.d && r < a.P; r += gridDim.y) {
+    for (int r = blockIdx.y; r < a.d && r < Pt; r += gridDim.y) {
         // start of a chain: zero state
         float creg[MTW];
 #pragma unroll
@@ -88,7 +90,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
 #pragma unroll
             for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
         {
-            const size_t nb = ((size_t)min(r + a.d, a.P - 1) * a.NB + bt) * xtile;
+            const size_t nb = ((size_t)min(r + a.d, Pt - 1) * a.NB + bt) * xtile;
 #pragma unroll
             for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + nb + ks * 64)[lane];
         }
@@ -100,11 +102,11 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         lds_barrier();
 
         int it = 0;
-        for (int p = r; p < a.P; p += a.d, ++it) {
+        for (int p = r; p < Pt; p += a.d, ++it) {
             const size_t pb = (size_t)p * a.NB + bt;
             float res_next[MTW];
             if (a.out) {
-                const size_t nb = ((size_t)min(p + a.d, a.P - 1) * a.NB + bt) * HT;
+                const size_t nb = ((size_t)min(p + a.d, Pt - 1) * a.NB + bt) * HT;
 #pragma unroll
                 for (int j = 0; j < MTW; ++j)
                     res_next[j] = (a.resid + (nb + min(s + kLstmWaves * j, HT - 1)) * 64)[lane];
@@ -155,14 +157,14 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
             // input part of the next position of the chain: independent of the
             // recurrence, so it runs on the matrix pipe while the waves meet at
             // the barrier
-            if (p + a.d < a.P) {
+            if (p + a.d < Pt) {
 #pragma unroll
                 for (int j = 0; j < MTW; ++j) acc[j] = bias[j];
 #pragma unroll
                 for (int ks = 0; ks < KXT; ++ks)
 #pragma unroll
                     for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
-                const size_t nb = ((size_t)min(p + 2 * a.d, a.P - 1) * a.NB + bt) * xtile;
+                const size_t nb = ((size_t)min(p + 2 * a.d, Pt - 1) * a.NB + bt) * xtile;
 #pragma unroll
                 for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + nb + ks * 64)[lane];
             }
@@ -215,6 +217,7 @@ struct LstmBwdArgs {
     float *dw_partial;    // [NB*chains][HT*MB][4][64]
     float *db_partial;    // [NB*chains][HT][4][4]
     int P, NB, d;
+    const int32_t *pmax;  // [NB] positions the longest series of a tile has: the tile's chains stop there
     // cell-state penalty (Section 8.4) of a block's first layer, kernels instantiated with CP only
     const int32_t *lengths;
     const Scalars *sc;
@@ -243,6 +246,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 
     const int lane = threadIdx.x & 63, bt = blockIdx.x;
     const int s = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
+    const int Pt = a.pmax[bt];      // the chains of this tile stop at its longest series
     const int g = lane >> 4, n = lane & 15;
     const bool last_own_valid = s + W * (MTW - 1) < HT;           // unit tile s + 4(MTW-1)
     const bool last_row_valid = (W - 1 - s) + W * (MTW - 1) < HT; // dW row (3-s) + 4(MTW-1)
@@ -410,8 +414,8 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = mfma16(ar[j][ks], xb[nbk][ks], dw[j][nbk]);
     };
 
-    for (int r0 = blockIdx.y; r0 < a.d && r0 < a.P; r0 += gridDim.y) {
-        const int p_last = r0 + ((a.P - 1 - r0) / a.d) * a.d;
+    for (int r0 = blockIdx.y; r0 < a.d && r0 < Pt; r0 += gridDim.y) {
+        const int p_last = r0 + ((Pt - 1 - r0) / a.d) * a.d;
         // start of a chain: no gradient arrives from later positions
 #pragma unroll
         for (int j = 0; j < MTW; ++j) { dcreg[j] = 0.0f; dhreg[j] = 0.0f; }
@@ -517,6 +521,7 @@ hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths
     const bool cp = lp.first_in_block && pl.cfg.lambda_cs != 0.0f;
     LstmFwdArgs a{ws + lp.wpack_fwd, ws + lp.bias_pack, ws + lp.xsrc, ws + lp.gates, ws + lp.c, ws + lp.hid,
                   lp.out ? ws + lp.resid : nullptr, lp.out ? ws + lp.out : nullptr, pl.P, pl.NB, lp.dil,
+                  reinterpret_cast<const int32_t *>(ws + pl.pmax),
                   lengths, cp ? ws + lp.cs_partial : nullptr, pl.B, pl.T, pl.I, pl.H};
 #define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_fwd<HT_, KXT_>(a, lp.chains, st);
     ESRNN_LSTM_SHAPES(X)
@@ -552,6 +557,7 @@ hipError_t launch_lstm_backward(const Plan &pl, int layer, const int32_t *length
     if (lp.narrow) return launch_lstm_backward_narrow(pl, layer, lengths, ws, st);
     a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
     a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
+    a.pmax = reinterpret_cast<const int32_t *>(ws + pl.pmax);
 #define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X

@@ -110,6 +110,7 @@ struct NarrowFwdArgs {
     const float *resid;   // TL(HP) or null
     float *out;           // TL(HP) or null: resid + hid
     int P, NB, d, h;
+    const int32_t *pmax;  // [NB] positions the longest series of a 16-series tile has: its chains stop there
     const int32_t *lengths;
     float *cs_partial;    // [4*NB * gridDim.y] (cell-state penalty, CP instantiations only)
     int B, T, I, H;
@@ -129,6 +130,9 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int blk = lane >> 2, j = lane & 3;
     const int bt = blockIdx.x >> 2, q = blockIdx.x & 3;
+    // All four workgroups of a 16-series tile stop at the tile's longest series: what lies beyond is
+    // neither computed here nor read by any later kernel.
+    const int Pt = a.pmax[bt];
     const bool valid = blk < HT;
     const int unit = w * HT + min(blk, HT - 1);     // blocks past HT repeat the last unit
 
@@ -158,8 +162,8 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
     for (int e = threadIdx.x; e < 2 * CH * XG * 64; e += kNT) (&xc[0][0][0])[e] = 0.0f;
     for (int e = threadIdx.x; e < 2 * HG * 64; e += kNT) (&hb[0][0])[e] = 0.0f;
 
-    for (int r = blockIdx.y; r < a.d && r < a.P; r += gridDim.y) {
-        const int n = (a.P - r + a.d - 1) / a.d;            // positions of this chain: r, r+d, ...
+    for (int r = blockIdx.y; r < a.d && r < Pt; r += gridDim.y) {
+        const int n = (Pt - r + a.d - 1) / a.d;            // positions of this chain: r, r+d, ...
         float xs[CH], rs[CH];
         auto load_chunk = [&](int c) {
 #pragma unroll
@@ -275,6 +279,7 @@ struct NarrowBwdArgs {
     float *dw_partial;    // [4*NB*chains][HT*CT][4][64]
     float *db_partial;    // [4*NB*chains][HT][4][4]
     int P, NB, d;
+    const int32_t *pmax;  // [NB] positions the longest series of a 16-series tile has: its chains stop there
     const int32_t *lengths;
     const Scalars *sc;
     float two_lambda_cs;
@@ -299,6 +304,9 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int blk = lane >> 2, j = lane & 3;
     const int bt = blockIdx.x >> 2, q = blockIdx.x & 3;
+    // All four workgroups of a 16-series tile stop at the tile's longest series: what lies beyond is
+    // neither computed here nor read by any later kernel.
+    const int Pt = a.pmax[bt];
     const bool valid = blk < HT;
     const int unit = w * HT + min(blk, HT - 1);     // blocks past HT repeat the last unit
     const int lane_off = unit * 16 + 4 * q + j;
@@ -331,8 +339,8 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
         pen = a.two_lambda_cs * a.sc->inv_n_cs;
     }
 
-    for (int r0 = blockIdx.y; r0 < a.d && r0 < a.P; r0 += gridDim.y) {
-        const int n = (a.P - r0 + a.d - 1) / a.d;
+    for (int r0 = blockIdx.y; r0 < a.d && r0 < Pt; r0 += gridDim.y) {
+        const int n = (Pt - r0 + a.d - 1) / a.d;
         const int p_last = r0 + (n - 1) * a.d;
         // operands of the i-th position from the end of the chain (requests past the chain repeat the last)
         f32x4 s_gt[CH], s_o[CH];     // (native vectors: arrays of the HIP float4 class do not stay in registers)
@@ -521,7 +529,7 @@ hipError_t launch_lstm_forward_narrow(const Plan &pl, int layer, const int32_t *
     const bool cp = lp.first_in_block && pl.cfg.lambda_cs != 0.0f;
     NarrowFwdArgs a{ws + lp.wpack_fwd, weights + lp.b_off, ws + lp.xsrc, ws + lp.gates, ws + lp.c, ws + lp.hid,
                     lp.out ? ws + lp.resid : nullptr, lp.out ? ws + lp.out : nullptr, pl.P, pl.NB, lp.dil, pl.h,
-                    lengths, cp ? ws + lp.cs_partial : nullptr, pl.B, pl.T, pl.I, pl.H};
+                    reinterpret_cast<const int32_t *>(ws + pl.pmax), lengths, cp ? ws + lp.cs_partial : nullptr, pl.B, pl.T, pl.I, pl.H};
 #define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_nfwd<HT_, KXT_>(a, lp.chains, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X
@@ -544,6 +552,7 @@ hipError_t launch_lstm_backward_narrow(const Plan &pl, int layer, const int32_t 
     a.gsrc[1] = ws + (lp.n_gsrc > 2 ? pl.gsum : lp.gsrc[lp.n_gsrc >= 2 ? 1 : 0]);
     a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
     a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
+    a.pmax = reinterpret_cast<const int32_t *>(ws + pl.pmax);
 #define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_nbwd<HT_, KXT_>(a, lp.chains, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X

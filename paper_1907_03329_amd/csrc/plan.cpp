@@ -153,6 +153,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.scalars = ws.take(64);
     pl.sink = ws.take(64);
     pl.len_ext = ws.take((size_t)pl.B);
+    pl.pmax = ws.take((size_t)pl.NB);
     pl.opt_partial = ws.take(512);
     pl.n_loss_partial = head_blocks + pl.es_blocks;
     pl.loss_partial = ws.take((size_t)pl.n_loss_partial);

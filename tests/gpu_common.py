@@ -180,8 +180,12 @@ def check_backward(cfg, inp, step, f, g=None, stages=True, want_adjoints=None):
     if g is None or np.any(side[near] != own[near]) or (want_adjoints and not hasattr(g, "gO")):
         g = oracle.backward(cfg, f, want_adjoints=want_adjoints, pin_side=side if near.any() else None)
     if stages:
-        full = np.ones((wm.shape[0], cfg.B, cfg.H), dtype=bool)
-        chk("grad_O", gO_gpu, g.gO.transpose(1, 0, 2), full, TOL_GRAD)
+        # the loss gradient is defined (zero where masked) at every position a 16-series tile computes,
+        # i.e. up to the window count of the tile's longest series; beyond that nothing is produced
+        Pb = np.maximum(lengths.astype(np.int64) - cfg.I - cfg.H + 1, 0)
+        tile_max = np.array([Pb[16 * (b // 16): 16 * (b // 16) + 16].max() for b in range(cfg.B)])
+        computed = np.arange(wm.shape[0])[:, None] < tile_max[None, :]
+        chk("grad_O", gO_gpu, g.gO.transpose(1, 0, 2), np.broadcast_to(computed[:, :, None], gO_gpu.shape), TOL_GRAD)
         chk("grad_top", step.buffer("grad_top").cpu().numpy(), g.gR.transpose(1, 0, 2), wm, TOL_GRAD)
         chk("grad_X", step.buffer("grad_X").cpu().numpy(), g.gX.transpose(1, 0, 2), wm, TOL_GRAD)
         chk("grad_u", step.buffer("grad_u").cpu().numpy(), g.gu.T, live, TOL_GRAD)
