@@ -86,8 +86,9 @@ typedef struct {
 
 typedef struct esrnn_handle esrnn_handle;
 
-/* Validates the configuration (I + H <= T, periods <= T, dilations >= 1, sizes
- * within the ESRNN_MAX_* limits, 0 < tau < 1) and builds the launch plan.
+/* Validates the configuration (I + H <= T, periods <= T and m1 + m2 <= 640 (the seasonal rings of 64 series
+ * must fit into the 160 KB of LDS), dilations >= 1, sizes within the ESRNN_MAX_* limits, 0 < tau < 1) and
+ * builds the launch plan.
  * Host-only; touches no device. */
 esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out);
 esrnn_status esrnn_destroy(esrnn_handle *h);
@@ -96,6 +97,11 @@ esrnn_status esrnn_destroy(esrnn_handle *h);
  * later esrnn_forward, esrnn_predict and esrnn_es_window_forward on this handle; it must stay valid until
  * then.  Required before those calls when n_categories > 0 (they return ESRNN_ERR_NULL otherwise). */
 esrnn_status esrnn_set_categories(esrnn_handle *h, const int32_t *categories);
+
+/* Callers that only evaluate (loss and forecasts of esrnn_forward, no esrnn_backward): with on != 0 the output
+ * stage of esrnn_forward skips its reverse pass (Sections 3.4, 3.5 forward only) and esrnn_backward returns
+ * ESRNN_ERR_ORDER until it is switched off again.  Off by default.  esrnn_predict never runs that reverse pass. */
+esrnn_status esrnn_set_forward_only(esrnn_handle *h, int32_t on);
 
 /* Sizes the caller needs to allocate buffers. */
 esrnn_status esrnn_workspace_bytes(const esrnn_handle *h, size_t *bytes);

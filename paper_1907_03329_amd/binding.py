@@ -82,6 +82,8 @@ def load_library():
     lib.esrnn_es_window_backward.argtypes = [vp, fp, i32p, fp, vp, fp, vp]
     for fn in ("esrnn_es_window_workspace_bytes", "esrnn_es_window_forward", "esrnn_es_window_backward"):
         getattr(lib, fn).restype = C.c_int
+    lib.esrnn_set_forward_only.argtypes = [vp, C.c_int32]
+    lib.esrnn_set_forward_only.restype = C.c_int
     lib.esrnn_set_categories.argtypes = [vp, i32p]
     lib.esrnn_set_categories.restype = C.c_int
     lib.esrnn_adam_update.argtypes = [vp, C.POINTER(AdamConfig), C.c_int32, fp, fp, fp, fp, fp, fp, fp, fp, vp, vp]
@@ -283,6 +285,12 @@ def esrnn_es_window_backward(handle, y, lengths, es_params, workspace, grad_es_p
                                                  _ptr(grad_es_params, torch.float32), _stream(stream))
     if st != ESRNN_OK:
         raise EsrnnError(st, "esrnn_es_window_backward")
+
+
+def esrnn_set_forward_only(handle, on: bool) -> None:
+    st = load_library().esrnn_set_forward_only(handle, 1 if on else 0)
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_set_forward_only")
 
 
 def esrnn_set_categories(handle, categories) -> None:

@@ -2,6 +2,7 @@
 // exponential-smoothing recursions (forward and adjoint), window extraction
 // (forward and adjoint), loss reduction and weight-gradient reduction.
 #include <algorithm>
+#include <mutex>
 
 #include "device_utils.h"
 #include "esrnn_internal.h"
@@ -801,6 +802,30 @@ __global__ void __launch_bounds__(256) reduce_stage2_kernel(ReduceStage2Args a)
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
+namespace {
+// Dynamic LDS above 64 KB has to be allowed per kernel.  Done once per kernel and device for the whole
+// 160 KB, on the first launch that needs it (not on every launch: the call is not a stream operation).
+hipError_t allow_large_lds(const void *kernel, size_t lds)
+{
+    if (lds <= 64 * 1024) return hipSuccess;
+    constexpr int kMaxKernels = 8, kMaxDevices = 64;
+    static std::mutex mu;
+    static const void *known[kMaxKernels];
+    static bool done[kMaxKernels][kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    int slot = -1;
+    for (int i = 0; i < kMaxKernels && slot < 0; ++i)
+        if (known[i] == kernel || known[i] == nullptr) { known[i] = kernel; slot = i; }
+    if (slot >= 0 && dev >= 0 && dev < kMaxDevices && done[slot][dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess && slot >= 0 && dev >= 0 && dev < kMaxDevices) done[slot][dev] = true;
+    return e;
+}
+}  // namespace
+
 hipError_t launch_setup(const Plan &pl, const int32_t *lengths, const float *weights, float *ws, hipStream_t st)
 {
     SetupArgs a{};
@@ -842,11 +867,8 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
              c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
     const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
     auto run = [&](auto kernel) {
-        if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel), lds);
+        if (e != hipSuccess) return e;
         kernel<<<pl.es_blocks, 64, lds, st>>>(a);
         return hipGetLastError();
     };
@@ -894,11 +916,8 @@ hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *len
                 c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
     const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
     auto run = [&](auto kernel) {
-        if (lds > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel), lds);
+        if (e != hipSuccess) return e;
         kernel<<<(pl.B + 63) / 64, 64, lds, st>>>(a);
         return hipGetLastError();
     };

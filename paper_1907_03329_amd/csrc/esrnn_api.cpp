@@ -28,6 +28,7 @@ struct esrnn_handle {
     int st_setup, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head, st_loss;
     int st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce, st_tail;
     const int32_t *categories;   // device array of the caller, or null
+    bool forward_only;           // esrnn_forward skips the reverse pass of the output stage; esrnn_backward is refused
 };
 
 namespace {
@@ -80,6 +81,7 @@ esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
     h->forward_done = false;
     h->profiling = false;
     h->categories = nullptr;
+    h->forward_only = false;
     h->n_stages = 0;
     const Plan &pl = h->plan;
     h->st_setup = add_stage(h, "setup", 0);
@@ -113,6 +115,14 @@ esrnn_status esrnn_set_categories(esrnn_handle *h, const int32_t *categories)
     if (!h) return ESRNN_ERR_NULL;
     if (h->plan.C == 0 && categories) return ESRNN_ERR_CONFIG;
     h->categories = categories;
+    return ESRNN_OK;
+}
+
+esrnn_status esrnn_set_forward_only(esrnn_handle *h, int32_t on)
+{
+    if (!h) return ESRNN_ERR_NULL;
+    h->forward_only = on != 0;
+    h->forward_done = false;
     return ESRNN_OK;
 }
 
@@ -167,9 +177,9 @@ esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengt
     for (int l = 0; l < pl.L; ++l)
         ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, lengths, weights, ws, st); }));
     // the output stage runs its reverse pass in the same launch: the loss gradient needs nothing beyond it
-    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, lengths, ws, forecasts, st); }));
+    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, lengths, ws, forecasts, !h->forward_only, st); }));
     ESRNN_TRY(run_stage(h, h->st_loss, st, [&] { return launch_loss_finalize(pl, ws, loss, st); }));
-    h->forward_done = true;
+    h->forward_done = !h->forward_only;
     return ESRNN_OK;
 }
 
@@ -260,7 +270,7 @@ esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengt
     ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, h->categories, ws, st); }));
     for (int l = 0; l < pl.L; ++l)
         ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ext, weights, ws, st); }));
-    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, ext, ws, nullptr, st); }));
+    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, ext, ws, nullptr, false, st); }));
     ESRNN_TRY(run_stage(h, h->st_tail, st, [&] { return launch_forecast_tail(pl, lengths, ws, forecasts, st); }));
     return ESRNN_OK;
 }

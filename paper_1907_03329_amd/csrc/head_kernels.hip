@@ -39,6 +39,7 @@ struct HeadArgs {
     int P, NB, B, Bp, T, I, H, n_seas, stride;
     int orows;              // rows of the Z, O and gO tiles: 4 * ceil(H / 4)
     float tau;
+    int reverse;            // 0: forward only (outputs, loss, forecasts); the reverse pass and its stores are skipped
 };
 
 template <int HT, int MO>
@@ -249,6 +250,10 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
             go_l[j * kLdsPad + n] = val;
             dbo[ks] += val;
         }
+        if (!a.reverse) {       // forward-only callers (out-of-sample forecasts): nothing below is needed
+            cur = nxt;
+            continue;
+        }
         // ---- reverse: dA = Wo^T gO (unit-tile order), through the tanh
 #pragma unroll
         for (int ma = 0; ma < MA; ++ma) acc[ma] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -340,7 +345,7 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
 
 }  // namespace
 
-hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st)
+hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, bool reverse, hipStream_t st)
 {
     const HeadPack hp = head_pack_layout(pl);
     const float *f = ws + pl.head_fwd_pack, *bk = ws + pl.head_bwd_pack;
@@ -349,7 +354,8 @@ hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float 
                ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z, ws + pl.u, ws + pl.S1, ws + pl.S2, lengths,
                reinterpret_cast<const int32_t *>(ws + pl.pmax), reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.O, forecasts, ws + pl.loss_partial,
                ws + pl.gO, ws + pl.gTop, ws + pl.head_dw_partial,
-               pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.head_dw_stride, pl.OP, pl.cfg.tau};
+               pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.head_dw_stride, pl.OP, pl.cfg.tau,
+               reverse ? 1 : 0};
 #define X(HT_, MO_)                                              \
     if (pl.HT == HT_ && pl.MO == MO_) {                          \
         head_kernel<HT_, MO_><<<blocks, 256, 0, st>>>(a);        \

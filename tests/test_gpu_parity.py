@@ -205,6 +205,39 @@ def test_backward_before_forward_is_refused():
     step.close()
 
 
+def test_forward_only_gives_the_same_loss_and_forecasts_and_refuses_backward():
+    import torch
+    from paper_1907_03329_amd import binding
+    cfg = small("fwd_only", B=40)
+    inp = synth.make_inputs(cfg, seed=25, ragged=True)
+    dev = gc.to_device(inp)
+    ref = gc.run_gpu(cfg, inp, backward=False)
+    step = binding.TrainingStep(cfg)
+    binding.esrnn_set_forward_only(step.handle, True)
+    step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    torch.cuda.synchronize()
+    assert torch.equal(step.loss, ref.loss)
+    assert torch.equal(step.forecasts, ref.forecasts)
+    with pytest.raises(binding.EsrnnError) as ei:
+        step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    assert ei.value.status == 4
+    binding.esrnn_set_forward_only(step.handle, False)
+    step.forward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    step.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    ref.backward(dev["y"], dev["lengths"], dev["es_params"], dev["weights"])
+    torch.cuda.synchronize()
+    assert torch.equal(step.grad_weights, ref.grad_weights)
+    step.close(); ref.close()
+
+
+def test_long_seasonal_periods_use_large_lds():
+    """Periods whose rings need more than 64 KB of LDS per 64 series (the attribute that allows it is set
+    once per kernel): 200 + 120 periods -> 80 KB."""
+    cfg = small("long_rings", T=420, n_seas=2, m1=200, m2=120, seas_sd2=0.1, I=4, H=8, B=20, blocks=((1, 2),))
+    report(gc.run_and_check(cfg, seed=26))
+    report(gc.run_and_check(cfg, seed=27, ragged=True))
+
+
 def test_forecasts_may_be_omitted_and_stream_is_honoured():
     import torch
     from paper_1907_03329_amd import binding

@@ -88,6 +88,7 @@ def bad(**kw):
     bad(I=65, T=200),
     bad(H=65, T=200),
     bad(hidden=8, I=40, T=100),      # input window wider than the padded hidden size and no dedicated shape
+    bad(n_seas=2, m1=400, m2=300, T=800),   # seasonal rings of 64 series beyond the LDS of a compute unit
 ])
 def test_invalid_configurations_are_rejected(lib, cfg):
     with pytest.raises(binding.EsrnnError) as ei:
@@ -110,6 +111,12 @@ def test_null_and_order_errors_need_no_device(lib):
     assert lib.esrnn_forward(h, fake, fake, fake, fake, C.c_void_p(4097), fake, None, None) == 3
     assert lib.esrnn_backward(h, fake, fake, fake, fake, fake, fake, fake, None) == 4
     assert binding.status_string(4).startswith("backward")
+    # forward-only handles refuse esrnn_backward; null handle
+    assert lib.esrnn_set_forward_only(None, 1) == 1
+    assert lib.esrnn_set_forward_only(h, 1) == 0
+    assert lib.esrnn_backward(h, fake, fake, fake, fake, fake, fake, fake, None) == 4
+    # periods up to 640 in total are accepted
+    binding.esrnn_destroy(binding.esrnn_create(bad(n_seas=2, m1=400, m2=240, T=800)))
     binding.esrnn_destroy(h)
 
 
