@@ -267,13 +267,13 @@ esrnn_status esrnn_es_window_backward(esrnn_handle *h, const float *y, const int
 /*
  * Where an intermediate lives inside the workspace, for tests and profiling.
  * Layout kinds:
- *   ESRNN_LAYOUT_TIME_MAJOR  [T][Bp], Bp = 16 * ceil(B / 16)
- *   ESRNN_LAYOUT_TILE        [P][Bp/16][R][16]: element (p, b, r) at
+ *   ESRNN_LAYOUT_TIME_MAJOR  [T][Bt], Bt = 64 * ceil(B / 64)
+ *   ESRNN_LAYOUT_TILE        [P][Bp/16][R][16], Bp = 16 * ceil(B / 16): element (p, b, r) at
  *                            ((p * Bp/16 + b/16) * R + r) * 16 + b%16; rows past
  *                            the logical count are padding
  *   ESRNN_LAYOUT_GATE_TILE   as TILE with a trailing [4] (activated input,
  *                            forget, candidate, output gate of hidden unit r)
- * dims = {T or P, Bp, R (padded rows), logical rows}.
+ * dims = {T or P, Bt or Bp, R (padded rows), logical rows}.
  */
 typedef enum {
     ESRNN_BUF_LEVEL = 0, ESRNN_BUF_S1, ESRNN_BUF_S2, ESRNN_BUF_U, ESRNN_BUF_V,   /* time-major */

@@ -3,6 +3,7 @@
 // (forward and adjoint), loss reduction and weight-gradient reduction.
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 #include "device_utils.h"
 #include "esrnn_internal.h"
@@ -248,14 +249,18 @@ struct EsArgs {
     const float *y;           // [T][B]
     const int32_t *lengths;
     const float *es;          // [K][B]
-    float *lvl, *S1, *S2, *u, *v;   // [T][Bp]
+    float *lvl, *S1, *S2, *u, *v;   // [T][Bp], one column per lane of every wave
     float *lv_partial;        // [gridDim.x]
-    float *sink;              // [64] target of the stores of lanes past the padded batch
-    int B, Bp, T, n_seas, m1, m2, logit;
+    int B, Bp, T, n_seas, m1, m2, logit;   // Bp: row stride of the time-major arrays (batch padded to 64)
     int row_gamma1, row_gamma2, row_s1, row_s2;
 };
 
-template <int NS>
+// CS: how many consecutive time steps take their seasonal factors out of the ring together (and put the
+// new ones back together): a divisor of 8 not larger than the shorter period, so that no factor a group
+// reads is produced inside the group.  Within a group the steps are then plain register arithmetic whose
+// only chain is the level (one multiply-add per step); divisions, logarithms, seasonal updates and stores
+// of the other steps overlap with it.
+template <int NS, int CS>
 __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
 {
     extern __shared__ float ring[];   // [m1 + m2][64]
@@ -286,76 +291,76 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
             float s = in_batch ? a.es[(size_t)(a.row_s2 + k) * a.B + b] : 1.0f;
             ring2[k * 64 + lane] = (a.logit && in_batch) ? expf(s) : s;
         }
-    // Lanes past the padded batch (last workgroup only) keep storing, into a sink, with stride 0:
-    // no store is ever skipped, so every path through a step issues the same memory operations.
-    const bool store = b < a.Bp;
-    const int row_stride = store ? a.Bp : 0;
-    float *const lvl_b = store ? a.lvl + b : a.sink + lane;
-    float *const u_b = store ? a.u + b : a.sink + lane;
-    float *const v_b = store ? a.v + b : a.sink + lane;
-    float *const S1_b = store ? a.S1 + b : a.sink + lane;
-    float *const S2_b = store ? a.S2 + b : a.sink + lane;
+    // Every lane owns a column of the time-major arrays (their rows are padded to whole waves), so no store
+    // is ever skipped and a row address is a wave-uniform base plus the lane: scalar address arithmetic,
+    // and no vector register is tied up by an address while a request is in flight.
+    const unsigned ub = b;
     float l_prev = 1.0f, u1 = 0.0f, u2 = 0.0f, lv_sum = 0.0f;
-    int i1 = 0, i2 = 0;
+    int i1 = 0, i2 = 0;           // ring slot of the current time: t mod m
     const float one_m_alpha = 1.0f - alpha;
-    // factors for the current time, read from the ring one step ahead of their use
-    float s1_cur = 1.0f, s2_cur = 1.0f;
-    if (NS >= 1) s1_cur = ring1[lane];
-    if (NS >= 2) s2_cur = ring2[lane];
-    auto step = [&](int t, float yraw) {
-        const bool live = t < len;
-        const float yt = live ? yraw : 1.0f;
-        const float s1 = s1_cur, s2 = s2_cur;
-        // slot of time t+1: last written m-1 steps ago unless m = 1 (then it is the value written below)
-        const int j1 = i1 + 1 == a.m1 ? 0 : i1 + 1, j2 = i2 + 1 == a.m2 ? 0 : i2 + 1;
-        float s1_nxt = 1.0f, s2_nxt = 1.0f;
-        if (NS >= 1) s1_nxt = ring1[j1 * 64 + lane];
-        if (NS >= 2) s2_nxt = ring2[j2 * 64 + lane];
-        const float q = (yt) * fast_rcp(s1 * s2);
-        // reading for the state before the first observation: l_{-1} = y_0 / S[0]
-        const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
-        if (t >= 1) {
-            // Eq. (3): divide by the previous level (and the other factor)
-            const float ry = (yt) * fast_rcp(l_prev);
-            if (NS >= 1) {
-                const float w = g1 * (ry) * fast_rcp(s2) + (1.0f - g1) * s1;
-                ring1[i1 * 64 + lane] = w;
-                if (a.m1 == 1) s1_nxt = w;
-            }
-            if (NS >= 2) {
-                const float w = g2 * (ry) * fast_rcp(s1) + (1.0f - g2) * s2;
-                ring2[i2 * 64 + lane] = w;
-                if (a.m2 == 1) s2_nxt = w;
-            }
+
+    // N consecutive steps t0 .. t0+N-1 (N = CS, or 1 for the last steps of the sweep)
+    auto steps = [&](auto nc, int t0, const float *yv) {
+        constexpr int N = decltype(nc)::value;
+        float s1v[N], s2v[N], w1v[N], w2v[N];
+        int sl1[N], sl2[N];
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            sl1[k] = i1 + k < a.m1 ? i1 + k : i1 + k - a.m1;       // N <= m: at most one wrap
+            sl2[k] = i2 + k < a.m2 ? i2 + k : i2 + k - a.m2;
+            s1v[k] = NS >= 1 ? ring1[sl1[k] * 64 + lane] : 1.0f;
+            s2v[k] = NS >= 2 ? ring2[sl2[k] * 64 + lane] : 1.0f;
         }
-        s1_cur = s1_nxt; s2_cur = s2_nxt;
-        const float ut = live ? fast_log(lt) : 0.0f;
-        const float vt = live ? fast_log(q) : 0.0f;      // ln y - ln(S1 S2)
-        const int o = t * row_stride;
-        lvl_b[o] = live ? lt : 1.0f;
-        u_b[o] = ut;
-        v_b[o] = vt;
-        if (NS >= 1) S1_b[o] = live ? s1 : 1.0f;
-        if (NS >= 2) S2_b[o] = live ? s2 : 1.0f;
-        // Section 8.4: squared second difference of the log level
-        const float e = ut - 2.0f * u1 + u2;
-        lv_sum += (live && t >= 2) ? e * e : 0.0f;
-        u2 = u1; u1 = ut;
-        if (live) l_prev = lt;
-        i1 = j1; i2 = j2;
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            const int t = t0 + k;
+            const bool live = t < len;
+            const float yt = live ? yv[k] : 1.0f;
+            const float s1 = s1v[k], s2 = s2v[k];
+            const float r12 = fast_rcp(s1 * s2);         // one reciprocal serves 1/(s1 s2), 1/s1 and 1/s2
+            const float q = yt * r12;
+            // reading for the state before the first observation: l_{-1} = y_0 / S[0]
+            const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
+            // Eq. (3): divide by the previous level (and the other factor); at t = 0 the produced factor
+            // equals the initial one
+            const float ry = yt * fast_rcp(l_prev);
+            w1v[k] = (NS >= 1 && t >= 1) ? g1 * ry * (NS >= 2 ? r12 * s1 : 1.0f) + (1.0f - g1) * s1 : s1;
+            w2v[k] = (NS >= 2 && t >= 1) ? g2 * ry * (r12 * s2) + (1.0f - g2) * s2 : s2;
+            const float ut = live ? fast_log(lt) : 0.0f;
+            const float vt = live ? fast_log(q) : 0.0f;      // ln y - ln(S1 S2)
+            const size_t row = (size_t)t * a.Bp;        // wave-uniform; the lane index is unsigned: scalar base + 32-bit offset
+            (a.lvl + row)[ub] = live ? lt : 1.0f;
+            (a.u + row)[ub] = ut;
+            (a.v + row)[ub] = vt;
+            if (NS >= 1) (a.S1 + row)[ub] = live ? s1 : 1.0f;
+            if (NS >= 2) (a.S2 + row)[ub] = live ? s2 : 1.0f;
+            // Section 8.4: squared second difference of the log level
+            const float e = ut - 2.0f * u1 + u2;
+            lv_sum += (live && t >= 2) ? e * e : 0.0f;
+            u2 = u1; u1 = ut;
+            if (live) l_prev = lt;
+        }
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            if (NS >= 1) ring1[sl1[k] * 64 + lane] = w1v[k];     // the factor for time t + m
+            if (NS >= 2) ring2[sl2[k] * 64 + lane] = w2v[k];
+        }
+        if (NS >= 1) { i1 += N; if (i1 >= a.m1) i1 -= a.m1; }
+        if (NS >= 2) { i2 += N; if (i2 >= a.m2) i2 -= a.m2; }
     };
     // Observations are requested a chunk ahead so that no step waits for memory.  The body of a whole
     // chunk has no wave-level branch: memory operations complete in order, and only with a fixed number
     // of stores between a request and its use can the wait for the request leave those stores in flight.
     constexpr int CH = 8;
+    static_assert(CH % CS == 0, "groups tile a chunk");
     float ybuf[CH], ynext[CH];
     auto load_chunk = [&](int t0, float *dst) {
 #pragma unroll
         for (int k = 0; k < CH; ++k) {
-            const int t = t0 + k;
-            // raw value; the step replaces what lies past the series' length (no use of the load here,
-            // so that nothing waits for it before the chunk is needed)
-            dst[k] = a.y[(size_t)(t < len ? t : 0) * a.B + (in_batch ? b : 0)];
+            // raw value of a wave-uniform row (the last row again past the end); the step replaces what lies
+            // past the series' length
+            const int t = min(t0 + k, a.T - 1);
+            dst[k] = (a.y + (size_t)t * a.B)[in_batch ? ub : 0u];
         }
     };
     // Ragged batches (Section 8.1): the sweep ends at the longest series of the wave.  Rows between a
@@ -367,13 +372,13 @@ __global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
     for (; t0 + CH <= t_end; t0 += CH) {
         load_chunk(t0 + CH, ynext);
 #pragma unroll
-        for (int k = 0; k < CH; ++k) step(t0 + k, ybuf[k]);
+        for (int k = 0; k < CH; k += CS) steps(std::integral_constant<int, CS>{}, t0 + k, ybuf + k);
 #pragma unroll
         for (int k = 0; k < CH; ++k) ybuf[k] = ynext[k];
     }
 #pragma unroll
     for (int k = 0; k < CH; ++k)
-        if (t0 + k < t_end) step(t0 + k, ybuf[k]);
+        if (t0 + k < t_end) steps(std::integral_constant<int, 1>{}, t0 + k, ybuf + k);
     const float tot = wave_sum(lv_sum);
     if (lane == 0) a.lv_partial[blockIdx.x] = tot;
 }
@@ -460,9 +465,16 @@ __global__ void __launch_bounds__(256) window_backward_kernel(const float *__res
                                                                int P_all, int NB, int B, int Bp, int T, int I, int H, int xrows, int zrows,
                                                                const int32_t *__restrict__ pmax)
 {
+    // Bp: row stride of the time-major arrays (the batch padded to 64); columns past the 16 * NB series of
+    // the tiles have no windows
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long long)T * Bp) return;
     const int t = (int)(idx / Bp), col = (int)(idx % Bp);
+    if (col >= 16 * NB) {
+        gu[idx] = 0.0f;
+        gv[idx] = 0.0f;
+        return;
+    }
     const int bt = col >> 4, n = col & 15;
     const int P = min(P_all, pmax[bt]);      // window gradients past the tile's longest series do not exist
     float sv = 0.0f, su = 0.0f;
@@ -808,7 +820,7 @@ namespace {
 hipError_t allow_large_lds(const void *kernel, size_t lds)
 {
     if (lds <= 64 * 1024) return hipSuccess;
-    constexpr int kMaxKernels = 8, kMaxDevices = 64;
+    constexpr int kMaxKernels = 32, kMaxDevices = 64;
     static std::mutex mu;
     static const void *known[kMaxKernels];
     static bool done[kMaxKernels][kMaxDevices];
@@ -862,8 +874,8 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
 {
     const esrnn_config &c = pl.cfg;
     EsArgs a{y, lengths, es, ws + pl.lvl, ws + pl.S1, ws + pl.S2, ws + pl.u, ws + pl.v,
-             ws + pl.loss_partial + (pl.n_loss_partial - pl.es_blocks), ws + pl.sink,
-             pl.B, pl.Bp, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
+             ws + pl.loss_partial + (pl.n_loss_partial - pl.es_blocks),
+             pl.B, pl.Bt, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
              c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
     const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
     auto run = [&](auto kernel) {
@@ -872,9 +884,22 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
         kernel<<<pl.es_blocks, 64, lds, st>>>(a);
         return hipGetLastError();
     };
-    if (c.n_seas == 0) return run(es_forward_kernel<0>);
-    if (c.n_seas == 1) return run(es_forward_kernel<1>);
-    return run(es_forward_kernel<2>);
+    // steps per group: the largest divisor of 8 that no period is shorter than
+    int m_min = 8;
+    if (c.n_seas >= 1) m_min = std::min(m_min, c.m1);
+    if (c.n_seas >= 2) m_min = std::min(m_min, c.m2);
+    const int cs = m_min >= 8 ? 8 : (m_min >= 4 ? 4 : (m_min >= 2 ? 2 : 1));
+    if (c.n_seas == 0) return run(es_forward_kernel<0, 8>);
+    if (c.n_seas == 1) {
+        if (cs == 8) return run(es_forward_kernel<1, 8>);
+        if (cs == 4) return run(es_forward_kernel<1, 4>);
+        if (cs == 2) return run(es_forward_kernel<1, 2>);
+        return run(es_forward_kernel<1, 1>);
+    }
+    if (cs == 8) return run(es_forward_kernel<2, 8>);
+    if (cs == 4) return run(es_forward_kernel<2, 4>);
+    if (cs == 2) return run(es_forward_kernel<2, 2>);
+    return run(es_forward_kernel<2, 1>);
 }
 
 hipError_t launch_window_forward(const Plan &pl, const int32_t *categories, float *ws, hipStream_t st)
@@ -882,7 +907,7 @@ hipError_t launch_window_forward(const Plan &pl, const int32_t *categories, floa
     // few positions per wave at small batches (enough waves), more at large ones (less per-wave overhead)
     const int p_per_wave = pl.NB >= 2048 ? 8 : (pl.NB >= 512 ? 4 : 1);
     window_forward_kernel<<<dim3((pl.NB + 3) / 4, (pl.P + p_per_wave - 1) / p_per_wave), 256, 0, st>>>(ws + pl.u, ws + pl.v, ws + pl.X, ws + pl.Z,
-                                                                         pl.P, pl.NB, pl.Bp, pl.I, pl.H, 4 * pl.IT,
+                                                                         pl.P, pl.NB, pl.Bt, pl.I, pl.H, 4 * pl.IT,
                                                                          pl.OP, p_per_wave, categories, pl.C, pl.B,
                                                                          reinterpret_cast<const int32_t *>(ws + pl.pmax));
     return hipGetLastError();
@@ -899,10 +924,10 @@ hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStrea
 
 hipError_t launch_window_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st)
 {
-    const long long n = (long long)pl.T * pl.Bp;
+    const long long n = (long long)pl.T * pl.Bt;
     window_backward_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
         ws + pl.gX, ws + pl.gO, ws + pl.u, lengths, reinterpret_cast<const Scalars *>(ws + pl.scalars), pl.cfg.lambda_lv,
-        ws + pl.gu, ws + pl.gv, pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, 4 * pl.IT, pl.OP,
+        ws + pl.gu, ws + pl.gv, pl.P, pl.NB, pl.B, pl.Bt, pl.T, pl.I, pl.H, 4 * pl.IT, pl.OP,
         reinterpret_cast<const int32_t *>(ws + pl.pmax));
     return hipGetLastError();
 }
@@ -912,7 +937,7 @@ hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *len
 {
     const esrnn_config &c = pl.cfg;
     EsBwdArgs a{y, lengths, es, ws + pl.lvl, ws + pl.S1, ws + pl.S2, ws + pl.gu, ws + pl.gv, grad_es,
-                pl.B, pl.Bp, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
+                pl.B, pl.Bt, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
                 c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
     const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
     auto run = [&](auto kernel) {
@@ -1002,7 +1027,7 @@ hipError_t launch_forecast_tail(const Plan &pl, const int32_t *lengths, float *w
     const esrnn_config &c = pl.cfg;
     const int n = pl.B * pl.H;
     forecast_tail_kernel<<<(n + 255) / 256, 256, 0, st>>>(ws + pl.O, ws + pl.u, ws + pl.S1, ws + pl.S2, lengths, out,
-                                                          pl.B, pl.Bp, pl.NB, pl.T, pl.I, pl.H, pl.OP,
+                                                          pl.B, pl.Bt, pl.NB, pl.T, pl.I, pl.H, pl.OP,
                                                           c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0);
     return hipGetLastError();
 }

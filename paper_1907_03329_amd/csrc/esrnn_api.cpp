@@ -430,7 +430,7 @@ esrnn_status esrnn_workspace_buffer(const esrnn_handle *h, int32_t which, int32_
     out->offset_bytes = off * sizeof(float);
     out->layout = layout;
     out->dims[0] = lead;
-    out->dims[1] = pl.Bp;
+    out->dims[1] = layout == ESRNN_LAYOUT_TIME_MAJOR ? pl.Bt : pl.Bp;
     out->dims[2] = rows;
     out->dims[3] = logical;
     return ESRNN_OK;

@@ -52,7 +52,8 @@ struct Plan {
     esrnn_config cfg;
     int B, T, I, H, h, P;
     int C;               // entries of the category one-hot block that follows the input window (0: none)
-    int NB, Bp;          // series tiles, padded batch
+    int NB, Bp;          // series tiles, padded batch (16 * NB)
+    int Bt;              // row stride of the time-major arrays: the batch padded to whole waves of 64 series
     int HT, HP;          // hidden unit tiles, padded hidden (4*HT)
     int IT;              // unit tiles of the network input (window + one-hot block) as used by layer 0
     int OT, MO, OP;      // horizon: unit tiles, 16-row MFMA tiles, rows of the Z / O / gO tiles (4*OT)
@@ -68,7 +69,7 @@ struct Plan {
     size_t len_ext;      // int32[B]: lengths extended by the horizon (out-of-sample forecasts)
     size_t pmax;         // int32[NB]: window positions the series of a 16-series tile need (max over the tile), by setup
     size_t opt_partial;  // float[512]: sums of squares of the gradients, per workgroup (parameter update)
-    size_t lvl, S1, S2, u, v, gu, gv;   // [T][Bp]
+    size_t lvl, S1, S2, u, v, gu, gv;   // [T][Bt]
     size_t X, Z;         // TL(4*IT), TL(OP)
     size_t blk_out[ESRNN_MAX_BLOCKS];
     size_t O, gO, gTop, gX;

@@ -26,7 +26,7 @@ struct HeadArgs {
     const float *WoT, *WaT;               // transposed A operands
     const float *R;         // TL(HP) top block output
     const float *Z;         // TL(OP) targets
-    const float *u, *S1, *S2;   // [T][Bp]
+    const float *u, *S1, *S2;   // [T][Bp] (Bp here: the row stride of the time-major arrays)
     const int32_t *lengths;
     const int32_t *pmax;    // [NB] window positions the longest series of a tile has
     const Scalars *sc;
@@ -354,7 +354,7 @@ hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float 
                ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z, ws + pl.u, ws + pl.S1, ws + pl.S2, lengths,
                reinterpret_cast<const int32_t *>(ws + pl.pmax), reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.O, forecasts, ws + pl.loss_partial,
                ws + pl.gO, ws + pl.gTop, ws + pl.head_dw_partial,
-               pl.P, pl.NB, pl.B, pl.Bp, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.head_dw_stride, pl.OP, pl.cfg.tau,
+               pl.P, pl.NB, pl.B, pl.Bt, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.head_dw_stride, pl.OP, pl.cfg.tau,
                reverse ? 1 : 0};
 #define X(HT_, MO_)                                              \
     if (pl.HT == HT_ && pl.MO == MO_) {                          \

@@ -90,6 +90,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.P = cfg.T - cfg.I - cfg.H + 1;
     pl.NB = ceil_div(cfg.B, kTileN);
     pl.Bp = pl.NB * kTileN;
+    pl.Bt = ceil_div(cfg.B, 64) * 64;
     pl.HT = pick_ht(cfg.hidden);
     if (pl.HT < 0) return ESRNN_ERR_CONFIG;
     pl.HP = 4 * pl.HT;
@@ -142,7 +143,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
 
     // workspace
     Bump ws;
-    const size_t TB = (size_t)pl.T * pl.Bp;
+    const size_t TB = (size_t)pl.T * pl.Bt;
     const size_t PN = (size_t)pl.P * pl.NB;
     const size_t tileH = (size_t)pl.HT * 64;         // floats of one (p, series-tile) block with HP rows
     // output stage: every wave leaves a block of weight-gradient partials, so no more waves than fill the chip
@@ -150,7 +151,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     const int head_blocks = (int)std::min<size_t>((n_tiles + 3) / 4, 256);
     pl.head_blocks = head_blocks;
     pl.n_head_waves = 4 * head_blocks;
-    pl.es_blocks = ceil_div(pl.Bp, 64);
+    pl.es_blocks = pl.Bt / 64;
     // first everything the smoothing and window stages touch (their own entry points need only this prefix)
     pl.scalars = ws.take(64);
     pl.sink = ws.take(64);
