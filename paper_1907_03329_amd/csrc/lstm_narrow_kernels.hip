@@ -129,7 +129,12 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int blk = lane >> 2, j = lane & 3;
-    const int bt = blockIdx.x >> 2, q = blockIdx.x & 3;
+    // The four workgroups of a 16-series tile share every 64-byte row of the tile.  Consecutive workgroup
+    // ids go round the 8 XCDs, each with its own L2: ids x, x+8, x+16, x+24 of a group of 32 are the four
+    // quarters of ONE tile, so they land on the same XCD at about the same time and a row is fetched from
+    // HBM once, not four times (measured before: 2.3-2.8 times the algorithmic bytes).
+    const int bt = (blockIdx.x >> 5) * 8 + (blockIdx.x & 7), q = (blockIdx.x >> 3) & 3;
+    if (bt >= a.NB) return;     // the grid is padded to whole groups of 32 (before any barrier)
     // All four workgroups of a 16-series tile stop at the tile's longest series: what lies beyond is
     // neither computed here nor read by any later kernel.
     const int Pt = a.pmax[bt];
@@ -245,7 +250,7 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
         if (lane == 0) s_cs[w] = tot;
         __syncthreads();
         if (threadIdx.x == 0)
-            a.cs_partial[blockIdx.x * gridDim.y + blockIdx.y] = (s_cs[0] + s_cs[1]) + (s_cs[2] + s_cs[3]);
+            a.cs_partial[(4 * bt + q) * gridDim.y + blockIdx.y] = (s_cs[0] + s_cs[1]) + (s_cs[2] + s_cs[3]);
     }
 }
 
@@ -303,7 +308,12 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int blk = lane >> 2, j = lane & 3;
-    const int bt = blockIdx.x >> 2, q = blockIdx.x & 3;
+    // The four workgroups of a 16-series tile share every 64-byte row of the tile.  Consecutive workgroup
+    // ids go round the 8 XCDs, each with its own L2: ids x, x+8, x+16, x+24 of a group of 32 are the four
+    // quarters of ONE tile, so they land on the same XCD at about the same time and a row is fetched from
+    // HBM once, not four times (measured before: 2.3-2.8 times the algorithmic bytes).
+    const int bt = (blockIdx.x >> 5) * 8 + (blockIdx.x & 7), q = (blockIdx.x >> 3) & 3;
+    if (bt >= a.NB) return;     // the grid is padded to whole groups of 32 (before any barrier)
     // All four workgroups of a 16-series tile stop at the tile's longest series: what lies beyond is
     // neither computed here nor read by any later kernel.
     const int Pt = a.pmax[bt];
@@ -473,7 +483,7 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
         }
     }
 
-    const size_t partix = (size_t)blockIdx.x * gridDim.y + blockIdx.y;
+    const size_t partix = (size_t)(4 * bt + q) * gridDim.y + blockIdx.y;
 #pragma unroll
     for (int t = 0; t < MTW; ++t) {
         const int mt = w + kNW * t;
@@ -501,19 +511,22 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
     }
 }
 
+// workgroups along x: groups of 32 = 8 tiles x 4 quarters
+inline int narrow_grid_x(int NB) { return ((NB + 7) / 8) * 32; }
+
 template <int HT, int KXT>
 hipError_t run_nfwd(const NarrowFwdArgs &a, int chains, hipStream_t st)
 {
-    if (a.cs_partial) lstm_forward_narrow_kernel<HT, KXT, true><<<dim3(4 * a.NB, chains), 64 * kNW, 0, st>>>(a);
-    else lstm_forward_narrow_kernel<HT, KXT, false><<<dim3(4 * a.NB, chains), 64 * kNW, 0, st>>>(a);
+    if (a.cs_partial) lstm_forward_narrow_kernel<HT, KXT, true><<<dim3(narrow_grid_x(a.NB), chains), 64 * kNW, 0, st>>>(a);
+    else lstm_forward_narrow_kernel<HT, KXT, false><<<dim3(narrow_grid_x(a.NB), chains), 64 * kNW, 0, st>>>(a);
     return hipGetLastError();
 }
 
 template <int HT, int KXT>
 hipError_t run_nbwd(const NarrowBwdArgs &a, int chains, hipStream_t st)
 {
-    if (a.sc) lstm_backward_narrow_kernel<HT, KXT, true><<<dim3(4 * a.NB, chains), 64 * kNW, 0, st>>>(a);
-    else lstm_backward_narrow_kernel<HT, KXT, false><<<dim3(4 * a.NB, chains), 64 * kNW, 0, st>>>(a);
+    if (a.sc) lstm_backward_narrow_kernel<HT, KXT, true><<<dim3(narrow_grid_x(a.NB), chains), 64 * kNW, 0, st>>>(a);
+    else lstm_backward_narrow_kernel<HT, KXT, false><<<dim3(narrow_grid_x(a.NB), chains), 64 * kNW, 0, st>>>(a);
     return hipGetLastError();
 }
 
