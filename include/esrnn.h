@@ -89,6 +89,11 @@ typedef struct esrnn_handle esrnn_handle;
 /* Validates the configuration (I + H <= T, periods <= T and m1 + m2 <= 640 (the seasonal rings of 64 series
  * must fit into the 160 KB of LDS), dilations >= 1, sizes within the ESRNN_MAX_* limits, 0 < tau < 1) and
  * builds the launch plan.
+ * The plan picks, from the batch size, between two kernels each for the LSTM layers (4-series tiles at small
+ * batches, 16-series tiles otherwise) and for the window adjoint (gather, or streaming at very many series);
+ * the results agree to rounding.  Two environment variables, read here, override the choice for measurements:
+ * ESRNN_NARROW_BELOW (16-series workgroups below which a layer uses 4-series tiles) and
+ * ESRNN_WINDOW_STREAM_FROM (16-series tiles from which the window adjoint streams).
  * Host-only; touches no device. */
 esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out);
 esrnn_status esrnn_destroy(esrnn_handle *h);

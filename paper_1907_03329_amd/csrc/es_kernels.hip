@@ -452,24 +452,48 @@ __global__ void __launch_bounds__(256) loss_finalize_kernel(const float *__restr
                         (double)lambda_cs * s_c[0] * (double)sc->inv_n_cs);
 }
 
+// Gradient of the level penalty (Section 8.4) with respect to u[t] of one series, times `scale`:
+// e[k] = u[k] - 2u[k-1] + u[k-2] for 2 <= k < len; d/du[t] of sum e^2 = 2(e[t] - 2e[t+1] + e[t+2]).
+__device__ __forceinline__ float level_penalty_grad(const float *__restrict__ u, int Bp, int col, int t, int len, float scale)
+{
+    float acc = 0.0f;
+#pragma unroll
+    for (int dk = 0; dk <= 2; ++dk) {
+        const int k = t + dk;
+        if (k >= 2 && k < len) {
+            const float e = u[(size_t)k * Bp + col] - 2.0f * u[(size_t)(k - 1) * Bp + col] + u[(size_t)(k - 2) * Bp + col];
+            acc += (dk == 1 ? -2.0f : 1.0f) * e;
+        }
+    }
+    return scale * acc;
+}
+
 // ---------------------------------------------------------------------------
 // Window adjoint in gather form (no atomics): every x and z is v[.] - u[t], so
 //   gv[k] = sum_i gX[k-i][i] + sum_j gZ[k-(I-1)-j][j],  gu[t] = -(sum of row p = t-I+1),
 // with gZ = -gO, plus the gradient of the level penalty (Section 8.4).
-// One thread per (t, series).
+// One thread per (t, series); a workgroup takes 64 series at four consecutive t.
+//
+// Every 128-byte line of gX / gO holds two rows of a tile and is read for two neighbouring t and once
+// more for the row sum, by different workgroups.  The workgroups that touch the tiles of one group of 64
+// series therefore all run on the same XCD (workgroups go to the XCDs in turn), one after the other in
+// time order: the line is then fetched from memory once and found in that XCD's L2 afterwards.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) window_backward_kernel(const float *__restrict__ gX, const float *__restrict__ gO,
                                                                const float *__restrict__ u, const int32_t *__restrict__ lengths,
                                                                const Scalars *__restrict__ sc, float lambda,
                                                                float *__restrict__ gu, float *__restrict__ gv,
                                                                int P_all, int NB, int B, int Bp, int T, int I, int H, int xrows, int zrows,
-                                                               const int32_t *__restrict__ pmax)
+                                                               const int32_t *__restrict__ pmax, int t_chunks)
 {
     // Bp: row stride of the time-major arrays (the batch padded to 64); columns past the 16 * NB series of
     // the tiles have no windows
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)T * Bp) return;
-    const int t = (int)(idx / Bp), col = (int)(idx % Bp);
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int cg = (slot / t_chunks) * 8 + xcd;                 // group of 64 series
+    const int t = (slot % t_chunks) * 4 + (threadIdx.x >> 6);
+    if (cg * 64 >= Bp || t >= T) return;
+    const int col = cg * 64 + (threadIdx.x & 63);
+    const size_t idx = (size_t)t * Bp + col;
     if (col >= 16 * NB) {
         gu[idx] = 0.0f;
         gv[idx] = 0.0f;
@@ -493,22 +517,123 @@ __global__ void __launch_bounds__(256) window_backward_kernel(const float *__res
             for (int j = 0; j < H; ++j) su += gO[((size_t)(p * NB + bt) * zrows + j) * 16 + n];
         }
     }
-    if (lambda != 0.0f) {
-        const int len = col < B ? clamp_len(lengths[col], T) : 0;
-        // e[k] = u[k] - 2u[k-1] + u[k-2] for 2 <= k < len; d/du[t] of sum e^2 = 2(e[t] - 2e[t+1] + e[t+2])
-        float acc = 0.0f;
-#pragma unroll
-        for (int dk = 0; dk <= 2; ++dk) {
-            const int k = t + dk;
-            if (k >= 2 && k < len) {
-                const float e = u[(size_t)k * Bp + col] - 2.0f * u[(size_t)(k - 1) * Bp + col] + u[(size_t)(k - 2) * Bp + col];
-                acc += (dk == 1 ? -2.0f : 1.0f) * e;
-            }
-        }
-        su += lambda * 2.0f * sc->inv_n_lv * acc;
-    }
+    if (lambda != 0.0f)
+        su += level_penalty_grad(u, Bp, col, t, col < B ? clamp_len(lengths[col], T) : 0, lambda * 2.0f * sc->inv_n_lv);
     gu[idx] = su;
     gv[idx] = sv;
+}
+
+// ---------------------------------------------------------------------------
+// Window adjoint in streaming form, for batches with many series tiles.  One wave owns a series tile and
+// walks over the positions in time order.  Every row group of gX and gO (four rows of 16 series, 256
+// contiguous bytes) is loaded exactly once, by one full-width instruction; lane (g, n) adds its element of
+// row c of position p to slot (p + c) mod R of a ring of R >= I + H + 4 anti-diagonal sums in LDS (plain read, add,
+// write: the lanes of one instruction hit different slots, and the LDS unit serves a wave's instructions in
+// order, so no atomic is needed and the sums are formed in a fixed order).  After a block of four positions the four oldest slots are complete:
+// lane group g writes gv[s + g] and clears its slot, and writes gu[s + g + I - 1] from the row sum of its
+// position.  The gather kernel above reads every element twice in 64-byte pieces; this one is the faster
+// of the two once there are enough tiles for the waves to hide each other's memory latency.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) window_backward_stream_kernel(const float *__restrict__ gX, const float *__restrict__ gO,
+                                                                      const float *__restrict__ u, const int32_t *__restrict__ lengths,
+                                                                      const Scalars *__restrict__ sc, float lambda,
+                                                                      float *__restrict__ gu, float *__restrict__ gv,
+                                                                      int P_all, int NB, int B, int Bp, int T, int I, int H, int xrows,
+                                                                      int zrows, const int32_t *__restrict__ pmax, int R)
+{
+    extern __shared__ float ring_all[];                     // [wave][R][16]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int g = lane >> 4, n = lane & 15;
+    const int bt = blockIdx.x * 4 + wave;
+    if (bt >= NB) return;                                   // (no workgroup barrier below)
+    float *ring = ring_all + wave * R * 16;
+    for (int e = lane; e < R * 16; e += 64) ring[e] = 0.0f;
+    const int mask = R - 1;
+    const int Pt = min(P_all, pmax[bt]);
+    const int col = bt * 16 + n;
+    const int len = col < B ? clamp_len(lengths[col], T) : 0;
+    const float pen = lambda * 2.0f * sc->inv_n_lv;
+    const int QX = (I + 3) >> 2, Q = QX + ((H + 3) >> 2);   // row groups that hold window elements
+    // columns between the last tile and the padded batch: the wave of the last tile clears them
+    const int pad_col = 16 * NB + lane;
+    const bool pads = bt == NB - 1 && 16 * NB < Bp;         // (wave-uniform)
+
+    for (int s0 = -((I + 2) & ~3); s0 < T; s0 += 4) {      // output block: gv[s0 .. s0+3], gu[s0+I-1 .. s0+I+2]
+        float su[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (s0 + 3 >= 0 && s0 < Pt) {
+            for (int e0 = 0; e0 < Q; e0 += 4) {
+                float w[4][4];
+                // sixteen independent loads in flight, then sixteen LDS additions
+#pragma unroll
+                for (int sp = 0; sp < 4; ++sp) {
+                    const int p = min(max(s0 + sp, 0), Pt - 1);
+                    const size_t tile = (size_t)p * NB + bt;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int e = min(e0 + j, Q - 1);
+                        const float *src = e < QX ? gX + (tile * xrows + 4 * e) * 16 : gO + (tile * zrows + 4 * (e - QX)) * 16;
+                        w[sp][j] = src[lane];
+                    }
+                }
+#pragma unroll
+                for (int sp = 0; sp < 4; ++sp) {
+                    const int p = s0 + sp;
+                    if (p < 0 || p >= Pt) continue;                     // (wave-uniform)
+                    // The row groups of one position go to different slots in every lane (row c of the window
+                    // part is below I, row c of the horizon part is I or more), so their four read-add-write
+                    // sequences are independent: all reads, then all writes.  Two positions do share slots.
+                    bool ok[4];
+                    int at[4];
+                    float val[4], old[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int e = e0 + j;
+                        const bool is_x = e < QX;
+                        const int r = 4 * (is_x ? e : e - QX) + g;
+                        // gX rows past the window (categories, padding) and gO rows past the horizon do not count
+                        ok[j] = e < Q && r < (is_x ? I : H);
+                        at[j] = ((p + (is_x ? r : I + r)) & mask) * 16 + n;
+                        val[j] = is_x ? w[sp][j] : -w[sp][j];           // dL/dz = -dL/do
+                        if (ok[j]) old[j] = ring[at[j]];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (ok[j]) {
+                            ring[at[j]] = old[j] + val[j];
+                            su[sp] -= val[j];
+                        }
+                    }
+                }
+            }
+        }
+        // row sums over the four lane groups; lane group g keeps the one of position s0 + g
+        float mine = 0.0f;
+#pragma unroll
+        for (int sp = 0; sp < 4; ++sp) {
+            float v = su[sp];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            mine = g == sp ? v : mine;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const int s = s0 + g;
+        if (s >= 0 && s < T) {
+            float *slot = &ring[(s & mask) * 16 + n];
+            gv[(size_t)s * Bp + col] = *slot;
+            *slot = 0.0f;
+        }
+        const int t = s + I - 1;
+        if (t >= 0 && t < T) {
+            gu[(size_t)t * Bp + col] = mine + (lambda != 0.0f ? level_penalty_grad(u, Bp, col, t, len, pen) : 0.0f);
+        }
+        if (pads && pad_col < Bp) {
+            for (int k = 0; k < 4; ++k) {
+                if (s0 + k >= 0 && s0 + k < T) gv[(size_t)(s0 + k) * Bp + pad_col] = 0.0f;
+                if (s0 + k + I - 1 >= 0 && s0 + k + I - 1 < T) gu[(size_t)(s0 + k + I - 1) * Bp + pad_col] = 0.0f;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -924,11 +1049,21 @@ hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStrea
 
 hipError_t launch_window_backward(const Plan &pl, const int32_t *lengths, float *ws, hipStream_t st)
 {
-    const long long n = (long long)pl.T * pl.Bt;
-    window_backward_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
-        ws + pl.gX, ws + pl.gO, ws + pl.u, lengths, reinterpret_cast<const Scalars *>(ws + pl.scalars), pl.cfg.lambda_lv,
-        ws + pl.gu, ws + pl.gv, pl.P, pl.NB, pl.B, pl.Bt, pl.T, pl.I, pl.H, 4 * pl.IT, pl.OP,
-        reinterpret_cast<const int32_t *>(ws + pl.pmax));
+    const Scalars *sc = reinterpret_cast<const Scalars *>(ws + pl.scalars);
+    const int32_t *pmax = reinterpret_cast<const int32_t *>(ws + pl.pmax);
+    if (pl.window_stream) {
+        int R = 16;
+        while (R < pl.I + pl.H + 4) R *= 2;                 // ring of anti-diagonal sums, a power of two
+        window_backward_stream_kernel<<<(unsigned)((pl.NB + 3) / 4), 256, (size_t)4 * R * 16 * sizeof(float), st>>>(
+            ws + pl.gX, ws + pl.gO, ws + pl.u, lengths, sc, pl.cfg.lambda_lv, ws + pl.gu, ws + pl.gv, pl.P, pl.NB, pl.B,
+            pl.Bt, pl.T, pl.I, pl.H, 4 * pl.IT, pl.OP, pmax, R);
+        return hipGetLastError();
+    }
+    const int t_chunks = (pl.T + 3) / 4;                    // four time steps per workgroup
+    const int col_slots = (pl.Bt / 64 + 7) / 8;             // groups of 64 series per XCD
+    window_backward_kernel<<<(unsigned)(8 * col_slots * t_chunks), 256, 0, st>>>(
+        ws + pl.gX, ws + pl.gO, ws + pl.u, lengths, sc, pl.cfg.lambda_lv, ws + pl.gu, ws + pl.gv, pl.P, pl.NB, pl.B, pl.Bt,
+        pl.T, pl.I, pl.H, 4 * pl.IT, pl.OP, pmax, t_chunks);
     return hipGetLastError();
 }
 

@@ -58,6 +58,7 @@ struct Plan {
     int IT;              // unit tiles of the network input (window + one-hot block) as used by layer 0
     int OT, MO, OP;      // horizon: unit tiles, 16-row MFMA tiles, rows of the Z / O / gO tiles (4*OT)
     int MA;              // 16-row tiles of the hidden dimension in "unit-tile" order: ceil(HT/4)
+    int window_stream;   // window adjoint: 1 = streaming kernel (many series tiles), 0 = gather kernel
     int L;
     int K;               // rows of es_params
     int row_gamma1, row_gamma2, row_s1, row_s2;
