@@ -52,9 +52,12 @@ def stage_model(cfg, name):
             per *= 2                      # transposed contraction + weight gradient
         return "mfma", float(per) * B * P, "flop"
     if name == "head_forward_backward":
-        # bound by its streams: read the top block output and the targets; write outputs, forecasts,
-        # the loss gradient and the gradient of the top block output
-        return "hbm", 4.0 * B * P * (2 * h + 4 * H), "byte"
+        # bound by its streams: read the top block output and the targets; write outputs, the loss gradient
+        # and the gradient of the top block output
+        return "hbm", 4.0 * B * P * (2 * h + 3 * H), "byte"
+    if name == "forecasts":
+        # read outputs, log level and seasonal factors of the target times; write forecasts
+        return "hbm", 4.0 * B * P * 2 * H + 4.0 * B * T * (1 + n_seas), "byte"
     if name == "es_forward":
         return "hbm", 4.0 * B * T * (1 + 3 + n_seas) + 4.0 * B * cfg.K, "byte"       # read y; write level, u, v, factors
     if name == "es_backward":

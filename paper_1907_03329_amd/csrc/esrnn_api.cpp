@@ -25,7 +25,7 @@ struct esrnn_handle {
     int n_stages;
     Stage stage[kMaxStages];
     // stage indices
-    int st_setup, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head, st_loss;
+    int st_setup, st_es_fwd, st_win_fwd, st_lstm_fwd[kMaxLayers], st_head, st_fc, st_loss;
     int st_lstm_bwd[kMaxLayers], st_win_bwd, st_es_bwd, st_reduce, st_tail;
     const int32_t *categories;   // device array of the caller, or null
     bool forward_only;           // esrnn_forward skips the reverse pass of the output stage; esrnn_backward is refused
@@ -89,6 +89,7 @@ esrnn_status esrnn_create(const esrnn_config *cfg, esrnn_handle **out)
     h->st_win_fwd = add_stage(h, "window_forward", 0);
     for (int l = 0; l < pl.L; ++l) h->st_lstm_fwd[l] = add_stage(h, "lstm_forward_l%d", l);
     h->st_head = add_stage(h, "head_forward_backward", 0);
+    h->st_fc = add_stage(h, "forecasts", 0);
     h->st_loss = add_stage(h, "loss_finalize", 0);
     for (int l = pl.L - 1; l >= 0; --l) h->st_lstm_bwd[l] = add_stage(h, "lstm_backward_l%d", l);
     h->st_win_bwd = add_stage(h, "window_backward", 0);
@@ -177,7 +178,9 @@ esrnn_status esrnn_forward(esrnn_handle *h, const float *y, const int32_t *lengt
     for (int l = 0; l < pl.L; ++l)
         ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, lengths, weights, ws, st); }));
     // the output stage runs its reverse pass in the same launch: the loss gradient needs nothing beyond it
-    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, lengths, ws, forecasts, !h->forward_only, st); }));
+    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, lengths, ws, !h->forward_only, st); }));
+    if (forecasts)
+        ESRNN_TRY(run_stage(h, h->st_fc, st, [&] { return launch_forecasts(pl, lengths, ws, forecasts, st); }));
     ESRNN_TRY(run_stage(h, h->st_loss, st, [&] { return launch_loss_finalize(pl, ws, loss, st); }));
     h->forward_done = !h->forward_only;
     return ESRNN_OK;
@@ -270,7 +273,7 @@ esrnn_status esrnn_predict(esrnn_handle *h, const float *y, const int32_t *lengt
     ESRNN_TRY(run_stage(h, h->st_win_fwd, st, [&] { return launch_window_forward(pl, h->categories, ws, st); }));
     for (int l = 0; l < pl.L; ++l)
         ESRNN_TRY(run_stage(h, h->st_lstm_fwd[l], st, [&] { return launch_lstm_forward(pl, l, ext, weights, ws, st); }));
-    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, ext, ws, nullptr, false, st); }));
+    ESRNN_TRY(run_stage(h, h->st_head, st, [&] { return launch_head(pl, ext, ws, false, st); }));
     ESRNN_TRY(run_stage(h, h->st_tail, st, [&] { return launch_forecast_tail(pl, lengths, ws, forecasts, st); }));
     return ESRNN_OK;
 }

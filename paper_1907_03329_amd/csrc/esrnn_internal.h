@@ -120,7 +120,8 @@ hipError_t launch_lstm_forward_narrow(const Plan &pl, int layer, const int32_t *
                                       float *ws, hipStream_t st);
 hipError_t launch_lstm_backward_narrow(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
 // output stage, forward and reverse in one launch (needs the loss normalisers of launch_setup)
-hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, bool reverse, hipStream_t st);
+hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, bool reverse, hipStream_t st);
+hipError_t launch_forecasts(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st);
 hipError_t launch_loss_finalize(const Plan &pl, float *ws, float *loss, hipStream_t st);
 
 hipError_t launch_lstm_backward(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);

@@ -1,6 +1,7 @@
 // Output stage of the network (Section 3.4: tanh layer, then linear layer), the
-// pinball loss over unmasked outputs (Section 3.5), the forecasts of Eq. (5),
-// and the reverse pass of all three, in ONE kernel: the gradient of the loss
+// pinball loss over unmasked outputs (Section 3.5) and the reverse pass of both
+// in ONE kernel (the forecasts of Eq. (5) follow in a small kernel of their own,
+// for callers that want them): the gradient of the loss
 // with respect to an output depends only on that output, its target and the
 // number of unmasked outputs (known from the lengths), so the reverse pass of
 // this stage can run while the activations are still in registers.  Every
@@ -26,20 +27,18 @@ struct HeadArgs {
     const float *WoT, *WaT;               // transposed A operands
     const float *R;         // TL(HP) top block output
     const float *Z;         // TL(OP) targets
-    const float *u, *S1, *S2;   // [T][Bp] (Bp here: the row stride of the time-major arrays)
     const int32_t *lengths;
     const int32_t *pmax;    // [NB] window positions the longest series of a tile has
     const Scalars *sc;
     float *O;               // TL(OP) outputs
-    float *forecasts;       // [P][B][H] or null
     float *loss_partial;    // [gridDim.x]
     float *gO;              // TL(OP): dL/d(output); the target's gradient is its negative
     float *gTop;            // TL(HP): dL/d(top block output)
     float *partial;         // [4 * gridDim.x][stride] weight-gradient partials of every wave
-    int P, NB, B, Bp, T, I, H, n_seas, stride;
+    int P, NB, B, T, I, H, stride;
     int orows;              // rows of the Z, O and gO tiles: 4 * ceil(H / 4)
     float tau;
-    int reverse;            // 0: forward only (outputs, loss, forecasts); the reverse pass and its stores are skipped
+    int reverse;            // 0: forward only (outputs and loss); the reverse pass and its stores are skipped
 };
 
 template <int HT, int MO>
@@ -58,7 +57,7 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
     // The transposed weight operands stay in registers where all four operand sets fit; for the larger
     // shapes they are read from LDS, one copy per workgroup (the register file holds the forward operands,
     // the weight-gradient accumulators and two tiles of inputs).
-    constexpr bool kTLds = (HT >= 13 && MO >= 2) || MO >= 4;
+    constexpr bool kTLds = (HT >= 13 && MO >= 2) || MO >= 3;
     // ... and the forward operands too for the largest shapes, as long as the workgroup stays within
     // 128 KB of LDS (this build keeps every kernel below that)
     constexpr int kStagingFloats = 4 * (OP + 3 * HP16) * kLdsPad + 4;
@@ -145,31 +144,23 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
     // operands of one tile; those of the next tile are requested before this one is computed
     struct Ops {
         float br[HT];
-        float z[OTMAX], seas[OTMAX];   // row 4*ks + g
-        float ut;
+        float z[OTMAX];                // row 4*ks + g
         int len;
+        int pmax;                      // window positions of the tile's longest series
     };
     auto load_ops = [&](int tile, int p, int bt, Ops &o) {
         if (tile >= n_tiles) { tile = n_tiles - 1; p = a.P - 1; bt = a.NB - 1; }
         const int b = bt * 16 + n;
-        const int t = p + a.I - 1;
         const float *rt = a.R + (size_t)tile * HT * 64;
 #pragma unroll
         for (int q = 0; q < HT; ++q) o.br[q] = (rt + q * 64)[lane];
         o.len = a.lengths[b < a.B ? b : a.B - 1];
-        o.ut = (a.u + (size_t)t * a.Bp + bt * 16)[n];
+        o.pmax = a.pmax[bt];
         const float *zt = a.Z + (size_t)tile * a.orows * 16;
 #pragma unroll
         for (int ks = 0; ks < OTMAX; ++ks) {
             const int j = 4 * ks + g;
             o.z[ks] = zt[(j < a.orows ? j : a.orows - 1) * 16 + n];
-            const int tj = t + 1 + j < a.T ? t + 1 + j : a.T - 1;
-            float sv = 1.0f;
-            if (a.forecasts) {
-                if (a.n_seas >= 1) sv = (a.S1 + bt * 16)[tj * a.Bp + n];
-                if (a.n_seas >= 2) sv *= (a.S2 + bt * 16)[tj * a.Bp + n];
-            }
-            o.seas[ks] = sv;
         }
     };
     auto advance = [&](int &tile, int &p, int &bt) {
@@ -189,15 +180,10 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
         }
         const int b = bt * 16 + n;
         // Ragged batches: a tile past the longest series of its 16 holds no window.  Nothing was computed
-        // for it upstream and nothing downstream reads it; only its forecasts are defined (zero).
-        if (p >= a.pmax[bt]) {
-            if (a.forecasts && b < a.B) {
-#pragma unroll
-                for (int ks = 0; ks < OTMAX; ++ks) {
-                    const int j = 4 * ks + g;
-                    if (j < a.H) (a.forecasts + ((size_t)p * a.B + bt * 16) * a.H)[n * a.H + j] = 0.0f;
-                }
-            }
+        // for it upstream and nothing downstream reads it.
+        // (the bound travels with the tile's operands: read here, it would stall the wave on every tile until the
+        // operand loads just issued for the next tile had all returned)
+        if (p >= cur.pmax) {
             cur = nxt;
             continue;
         }
@@ -226,7 +212,7 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
 #pragma unroll
             for (int mo = 0; mo < MO; ++mo) oc[mo] = mfma16(wo_op(mo, q), av[q], oc[mo]);
 
-        // ---- outputs, loss, forecasts and the gradient of the pinball loss; k-step ks holds rows 4ks..4ks+3
+        // ---- outputs, loss and the gradient of the pinball loss; k-step ks holds rows 4ks..4ks+3
         float go[OTMAX];
         float *ot = a.O + (size_t)tile * a.orows * 16, *got = a.gO + (size_t)tile * a.orows * 16;
 #pragma unroll
@@ -242,15 +228,10 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
                 ot[j * 16 + n] = o;
                 got[j * 16 + n] = val;
             }
-            if (a.forecasts && b < a.B && j < a.H) {
-                // Eq. (5): exp(output) * level * seasonal factors of the target time
-                const float f = valid ? __expf(o + cur.ut) * cur.seas[ks] : 0.0f;
-                (a.forecasts + ((size_t)p * a.B + bt * 16) * a.H)[n * a.H + j] = f;
-            }
             go_l[j * kLdsPad + n] = val;
             dbo[ks] += val;
         }
-        if (!a.reverse) {       // forward-only callers (out-of-sample forecasts): nothing below is needed
+        if (!a.reverse) {       // forward-only callers: nothing below is needed
             cur = nxt;
             continue;
         }
@@ -339,22 +320,73 @@ __global__ void __launch_bounds__(256) head_kernel(HeadArgs a)
     if (threadIdx.x == 0) a.loss_partial[blockIdx.x] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
 }
 
+// ---------------------------------------------------------------------------
+// Forecasts of Eq. (5) at every window position: exp(output) * level * seasonal factors of the target
+// time, zero where the window does not fit into the series.  One wave per (position, 16-series) tile.
+// Lane (g, n) computes the steps j = g, g+4, ... of series n: the tile of outputs and the rows of the
+// seasonal factors are read in their storage order.  The tile's 16 * H forecasts are contiguous in the
+// [P][B][H] array but ordered [series][step]: they are turned through the wave's corner of LDS and written
+// out in storage order as well.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) forecast_kernel(const float *__restrict__ O, const float *__restrict__ u,
+                                                        const float *__restrict__ S1, const float *__restrict__ S2,
+                                                        const int32_t *__restrict__ lengths, const int32_t *__restrict__ pmax,
+                                                        float *__restrict__ forecasts, int P, int NB, int B, int Bp, int T,
+                                                        int I, int H, int orows, int n_seas)
+{
+    __shared__ float s_f[4][16 * ESRNN_MAX_WINDOW];
+    const int lane = threadIdx.x & 63, g = lane >> 4, n = lane & 15;
+    float *fl = s_f[threadIdx.x >> 6];
+    const long long tile = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= (long long)P * NB) return;              // (no workgroup barrier below)
+    const int p = (int)(tile / NB), bt = (int)(tile % NB);
+    const int t = p + I - 1;
+    const int b = bt * 16 + n;
+    const int cols = min(16, B - bt * 16);              // series of this tile that exist
+    const int len = b < B ? min(max(lengths[b], 0), T) : 0;
+    const bool valid = p < pmax[bt] && p < len - I - H + 1;     // past pmax the tile of outputs holds nothing
+    const float ut = valid ? u[(size_t)t * Bp + b] : 0.0f;
+    const float *ot = O + (size_t)tile * orows * 16;
+    for (int j = g; j < H; j += 4) {
+        float f = 0.0f;
+        if (valid) {
+            float seas = 1.0f;
+            if (n_seas >= 1) seas = S1[(size_t)(t + 1 + j) * Bp + b];
+            if (n_seas >= 2) seas *= S2[(size_t)(t + 1 + j) * Bp + b];
+            f = __expf(ot[j * 16 + n] + ut) * seas;
+        }
+        fl[n * H + j] = f;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");     // same wave: LDS serves its instructions in order
+    float *ft = forecasts + ((size_t)p * B + bt * 16) * H;
+    for (int e = lane; e < cols * H; e += 64) ft[e] = fl[e];
+}
+
 #define ESRNN_HEAD_SHAPES(X) \
     X(2, 1) X(2, 2) X(2, 3) X(2, 4) X(8, 1) X(8, 2) X(8, 3) X(8, 4) X(10, 1) X(10, 2) X(10, 3) X(10, 4) \
     X(13, 1) X(13, 2) X(13, 3) X(13, 4) X(16, 1) X(16, 2) X(16, 3) X(16, 4)
 
 }  // namespace
 
-hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, bool reverse, hipStream_t st)
+hipError_t launch_forecasts(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st)
+{
+    const long long tiles = (long long)pl.P * pl.NB;
+    forecast_kernel<<<(unsigned)((tiles + 3) / 4), 256, 0, st>>>(
+        ws + pl.O, ws + pl.u, ws + pl.S1, ws + pl.S2, lengths, reinterpret_cast<const int32_t *>(ws + pl.pmax), forecasts,
+        pl.P, pl.NB, pl.B, pl.Bt, pl.T, pl.I, pl.H, pl.OP, pl.cfg.n_seas);
+    return hipGetLastError();
+}
+
+hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, bool reverse, hipStream_t st)
 {
     const HeadPack hp = head_pack_layout(pl);
     const float *f = ws + pl.head_fwd_pack, *bk = ws + pl.head_bwd_pack;
     const int blocks = pl.n_head_waves / 4;
     HeadArgs a{f + hp.WaF, f + hp.baF, f + hp.WoF, f + hp.boF, bk + hp.WoT, bk + hp.WaT,
-               ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z, ws + pl.u, ws + pl.S1, ws + pl.S2, lengths,
-               reinterpret_cast<const int32_t *>(ws + pl.pmax), reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.O, forecasts, ws + pl.loss_partial,
+               ws + pl.blk_out[pl.cfg.n_blocks - 1], ws + pl.Z, lengths,
+               reinterpret_cast<const int32_t *>(ws + pl.pmax), reinterpret_cast<const Scalars *>(ws + pl.scalars), ws + pl.O, ws + pl.loss_partial,
                ws + pl.gO, ws + pl.gTop, ws + pl.head_dw_partial,
-               pl.P, pl.NB, pl.B, pl.Bt, pl.T, pl.I, pl.H, pl.cfg.n_seas, pl.head_dw_stride, pl.OP, pl.cfg.tau,
+               pl.P, pl.NB, pl.B, pl.T, pl.I, pl.H, pl.head_dw_stride, pl.OP, pl.cfg.tau,
                reverse ? 1 : 0};
 #define X(HT_, MO_)                                              \
     if (pl.HT == HT_ && pl.MO == MO_) {                          \
