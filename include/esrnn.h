@@ -86,8 +86,8 @@ typedef struct {
 
 typedef struct esrnn_handle esrnn_handle;
 
-/* Validates the configuration (I + H <= T, periods <= T and m1 + m2 <= 640 (the seasonal rings of 64 series
- * must fit into the 160 KB of LDS), dilations >= 1, sizes within the ESRNN_MAX_* limits, 0 < tau < 1) and
+/* Validates the configuration (I + H <= T, periods <= T and m1 + m2 <= 448 (the seasonal rings of 64 series
+ * and a 48 KB staging buffer must fit into the 160 KB of LDS), dilations >= 1, sizes within the ESRNN_MAX_* limits, 0 < tau < 1) and
  * builds the launch plan.
  * The plan picks, from the batch size, between two kernels each for the LSTM layers (4-series tiles at small
  * batches, 16-series tiles otherwise) and for the window adjoint (gather, or streaming at very many series);

@@ -4,9 +4,22 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 namespace esrnn {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1 (for indices that must be immediates:
+// MFMA broadcast blocks, register sets that rotate through a loop)
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 // D = A(16x4) * B(4x16) + C(16x16), fp32.  Lane l supplies A[l%16][l/16] and
 // B[l/16][l%16]; it holds D[4*(l/16) + r][l%16] in component r.

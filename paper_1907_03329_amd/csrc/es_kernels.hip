@@ -258,129 +258,237 @@ struct EsArgs {
 // CS: how many consecutive time steps take their seasonal factors out of the ring together (and put the
 // new ones back together): a divisor of 8 not larger than the shorter period, so that no factor a group
 // reads is produced inside the group.  Within a group the steps are then plain register arithmetic whose
-// only chain is the level (one multiply-add per step); divisions, logarithms, seasonal updates and stores
-// of the other steps overlap with it.
+// only chain is the level (one multiply-add per step); divisions and seasonal updates of the other steps
+// overlap with it.
+//
+// Division of labour.  A workgroup serves 64 series with two or three waves.  Wave 0 runs the recursion and
+// nothing else: it reads observations (a chunk ahead), keeps the rings, and leaves level, de-seasonalised
+// value and factors of every step in an LDS staging buffer; it issues no global store, so nothing it waits
+// for is ever queued behind one.  Of the previous chunk, wave 1 turns the staged level into lvl, u = ln(level)
+// and the level penalty, wave 2 the staged value into v, and wave 3 (seasonal shapes) stores the factors.
+// A wave can have only so many memory operations in flight; five stores per step on the wave that also
+// carries the chain made the chain wait for store latency.
+constexpr int kEsChunk = 8;                 // steps per staging buffer
+constexpr int kEsAhead = 4;                 // chunks between the request of a row and its use
+constexpr int kEsStageFloats = 2 * kEsChunk * 4 * 64;
+
 template <int NS, int CS>
-__global__ void __launch_bounds__(64) es_forward_kernel(EsArgs a)
+__global__ void __launch_bounds__(NS == 0 ? 192 : 256) es_forward_kernel(EsArgs a)
 {
-    extern __shared__ float ring[];   // [m1 + m2][64]
-    const int lane = threadIdx.x;
+    extern __shared__ float ring[];   // [m1 + m2][64] rings, then [2][kEsChunk][4][64] staging
+    constexpr int CH = kEsChunk;
+    static_assert(CH % CS == 0, "groups tile a chunk");
+    const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * 64 + lane;
     const bool in_batch = b < a.B;
     const int len = in_batch ? clamp_len(a.lengths[b], a.T) : 0;
     float *ring1 = ring, *ring2 = ring + (size_t)a.m1 * 64;
-
-    float alpha = 0.5f, g1 = 0.0f, g2 = 0.0f;
-    if (in_batch) {
-        alpha = a.es[b];
-        if (NS >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
-        if (NS >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
-        if (a.logit) {
-            alpha = 1.0f / (1.0f + expf(-alpha));
-            g1 = 1.0f / (1.0f + expf(-g1));
-            g2 = 1.0f / (1.0f + expf(-g2));
-        }
-    }
-    if (NS >= 1)
-        for (int k = 0; k < a.m1; ++k) {
-            float s = in_batch ? a.es[(size_t)(a.row_s1 + k) * a.B + b] : 1.0f;
-            ring1[k * 64 + lane] = (a.logit && in_batch) ? expf(s) : s;
-        }
-    if (NS >= 2)
-        for (int k = 0; k < a.m2; ++k) {
-            float s = in_batch ? a.es[(size_t)(a.row_s2 + k) * a.B + b] : 1.0f;
-            ring2[k * 64 + lane] = (a.logit && in_batch) ? expf(s) : s;
-        }
-    // Every lane owns a column of the time-major arrays (their rows are padded to whole waves), so no store
-    // is ever skipped and a row address is a wave-uniform base plus the lane: scalar address arithmetic,
-    // and no vector register is tied up by an address while a request is in flight.
-    const unsigned ub = b;
-    float l_prev = 1.0f, u1 = 0.0f, u2 = 0.0f, lv_sum = 0.0f;
-    int i1 = 0, i2 = 0;           // ring slot of the current time: t mod m
-    const float one_m_alpha = 1.0f - alpha;
-
-    // N consecutive steps t0 .. t0+N-1 (N = CS, or 1 for the last steps of the sweep)
-    auto steps = [&](auto nc, int t0, const float *yv) {
-        constexpr int N = decltype(nc)::value;
-        float s1v[N], s2v[N], w1v[N], w2v[N];
-        int sl1[N], sl2[N];
-#pragma unroll
-        for (int k = 0; k < N; ++k) {
-            sl1[k] = i1 + k < a.m1 ? i1 + k : i1 + k - a.m1;       // N <= m: at most one wrap
-            sl2[k] = i2 + k < a.m2 ? i2 + k : i2 + k - a.m2;
-            s1v[k] = NS >= 1 ? ring1[sl1[k] * 64 + lane] : 1.0f;
-            s2v[k] = NS >= 2 ? ring2[sl2[k] * 64 + lane] : 1.0f;
-        }
-#pragma unroll
-        for (int k = 0; k < N; ++k) {
-            const int t = t0 + k;
-            const bool live = t < len;
-            const float yt = live ? yv[k] : 1.0f;
-            const float s1 = s1v[k], s2 = s2v[k];
-            const float r12 = fast_rcp(s1 * s2);         // one reciprocal serves 1/(s1 s2), 1/s1 and 1/s2
-            const float q = yt * r12;
-            // reading for the state before the first observation: l_{-1} = y_0 / S[0]
-            const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
-            // Eq. (3): divide by the previous level (and the other factor); at t = 0 the produced factor
-            // equals the initial one
-            const float ry = yt * fast_rcp(l_prev);
-            w1v[k] = (NS >= 1 && t >= 1) ? g1 * ry * (NS >= 2 ? r12 * s1 : 1.0f) + (1.0f - g1) * s1 : s1;
-            w2v[k] = (NS >= 2 && t >= 1) ? g2 * ry * (r12 * s2) + (1.0f - g2) * s2 : s2;
-            const float ut = live ? fast_log(lt) : 0.0f;
-            const float vt = live ? fast_log(q) : 0.0f;      // ln y - ln(S1 S2)
-            const size_t row = (size_t)t * a.Bp;        // wave-uniform; the lane index is unsigned: scalar base + 32-bit offset
-            (a.lvl + row)[ub] = live ? lt : 1.0f;
-            (a.u + row)[ub] = ut;
-            (a.v + row)[ub] = vt;
-            if (NS >= 1) (a.S1 + row)[ub] = live ? s1 : 1.0f;
-            if (NS >= 2) (a.S2 + row)[ub] = live ? s2 : 1.0f;
-            // Section 8.4: squared second difference of the log level
-            const float e = ut - 2.0f * u1 + u2;
-            lv_sum += (live && t >= 2) ? e * e : 0.0f;
-            u2 = u1; u1 = ut;
-            if (live) l_prev = lt;
-        }
-#pragma unroll
-        for (int k = 0; k < N; ++k) {
-            if (NS >= 1) ring1[sl1[k] * 64 + lane] = w1v[k];     // the factor for time t + m
-            if (NS >= 2) ring2[sl2[k] * 64 + lane] = w2v[k];
-        }
-        if (NS >= 1) { i1 += N; if (i1 >= a.m1) i1 -= a.m1; }
-        if (NS >= 2) { i2 += N; if (i2 >= a.m2) i2 -= a.m2; }
-    };
-    // Observations are requested a chunk ahead so that no step waits for memory.  The body of a whole
-    // chunk has no wave-level branch: memory operations complete in order, and only with a fixed number
-    // of stores between a request and its use can the wait for the request leave those stores in flight.
-    constexpr int CH = 8;
-    static_assert(CH % CS == 0, "groups tile a chunk");
-    float ybuf[CH], ynext[CH];
-    auto load_chunk = [&](int t0, float *dst) {
-#pragma unroll
-        for (int k = 0; k < CH; ++k) {
-            // raw value of a wave-uniform row (the last row again past the end); the step replaces what lies
-            // past the series' length
-            const int t = min(t0 + k, a.T - 1);
-            dst[k] = (a.y + (size_t)t * a.B)[in_batch ? ub : 0u];
-        }
-    };
+    float *stage = ring + (size_t)(a.m1 + a.m2) * 64;       // [buffer][step][lt, q, s1, s2][lane]
     // Ragged batches (Section 8.1): the sweep ends at the longest series of the wave.  Rows between a
     // series' own length and that bound get the defined padding values; rows beyond it are neither written
     // here nor read by any later kernel (their bounds are those of 16-series tiles, never larger).
+    // (every wave of the workgroup holds the same 64 series, so the bound is the same in all of them)
     const int t_end = wave_max_int(len);
-    load_chunk(0, ybuf);
-    int t0 = 0;
-    for (; t0 + CH <= t_end; t0 += CH) {
-        load_chunk(t0 + CH, ynext);
+    const int n_chunks = (t_end + CH - 1) / CH;
+    // Every lane owns a column of the time-major arrays (their rows are padded to whole waves), so no store
+    // is ever skipped and a row address is a wave-uniform base plus the lane: scalar address arithmetic.
+    const unsigned ub = b;
+
+    // Initial seasonal factors into the rings (ring 2 follows ring 1): all waves of the workgroup share the
+    // rows, eight requests in flight each - read one after the other by a single wave, the m1 + m2 rows of a
+    // long-period shape took longer than the whole recursion.
+    {
+        constexpr int NWV = NS == 0 ? 3 : 4;
+        const int rows = a.m1 + a.m2;
+        for (int k0 = role * 8; k0 < rows; k0 += NWV * 8) {
+            float sv[8];
 #pragma unroll
-        for (int k = 0; k < CH; k += CS) steps(std::integral_constant<int, CS>{}, t0 + k, ybuf + k);
+            for (int j = 0; j < 8; ++j) {
+                const int k = min(k0 + j, rows - 1);
+                const int row = k < a.m1 ? a.row_s1 + k : a.row_s2 + (k - a.m1);
+                sv[j] = in_batch ? a.es[(size_t)row * a.B + b] : 1.0f;
+            }
 #pragma unroll
-        for (int k = 0; k < CH; ++k) ybuf[k] = ynext[k];
+            for (int j = 0; j < 8; ++j)
+                if (k0 + j < rows) ring[(k0 + j) * 64 + lane] = (a.logit && in_batch) ? expf(sv[j]) : sv[j];
+        }
+        __syncthreads();
     }
+    if (role == 0) {
+        float alpha = 0.5f, g1 = 0.0f, g2 = 0.0f;
+        if (in_batch) {
+            alpha = a.es[b];
+            if (NS >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
+            if (NS >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
+            if (a.logit) {
+                alpha = 1.0f / (1.0f + expf(-alpha));
+                g1 = 1.0f / (1.0f + expf(-g1));
+                g2 = 1.0f / (1.0f + expf(-g2));
+            }
+        }
+        float l_prev = 1.0f;
+        int i1 = 0, i2 = 0;           // ring slot of the current time: t mod m
+        const float one_m_alpha = 1.0f - alpha;
+
+        // CS consecutive steps t0 .. t0+CS-1, staged at `out`.  WRAP: whether a ring index may pass the end of
+        // its ring inside the group; if not, the group's slots are consecutive and every LDS address is one
+        // per-lane base plus a constant.
+        auto steps = [&](auto wrap, int t0, const float *yv, float *out) {
+            constexpr bool WRAP = decltype(wrap)::value;
+            float s1v[CS], s2v[CS], w1v[CS], w2v[CS];
+            float *r1 = ring1 + i1 * 64 + lane, *r2 = ring2 + i2 * 64 + lane;
+            auto slot1 = [&](int k) { return WRAP ? ring1 + (i1 + k < a.m1 ? i1 + k : i1 + k - a.m1) * 64 + lane : r1 + k * 64; };
+            auto slot2 = [&](int k) { return WRAP ? ring2 + (i2 + k < a.m2 ? i2 + k : i2 + k - a.m2) * 64 + lane : r2 + k * 64; };
 #pragma unroll
-    for (int k = 0; k < CH; ++k)
-        if (t0 + k < t_end) steps(std::integral_constant<int, 1>{}, t0 + k, ybuf + k);
-    const float tot = wave_sum(lv_sum);
-    if (lane == 0) a.lv_partial[blockIdx.x] = tot;
+            for (int k = 0; k < CS; ++k) {
+                s1v[k] = NS >= 1 ? *slot1(k) : 1.0f;             // CS <= m: at most one wrap
+                s2v[k] = NS >= 2 ? *slot2(k) : 1.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < CS; ++k) {
+                const int t = t0 + k;
+                // Past the end of a series the observation is replaced by 1: levels and factors stay finite,
+                // the storing waves replace what they write there by the padding values.
+                const float yt = t < len ? yv[k] : 1.0f;
+                const float s1 = s1v[k], s2 = s2v[k];
+                const float r12 = fast_rcp(s1 * s2);         // one reciprocal serves 1/(s1 s2), 1/s1 and 1/s2
+                const float q = yt * r12;
+                // reading for the state before the first observation: l_{-1} = y_0 / S[0]
+                const float lt = (t == 0) ? q : alpha * q + one_m_alpha * l_prev;
+                // Eq. (3): divide by the previous level (and the other factor); at t = 0 the produced factor
+                // equals the initial one
+                const float ry = yt * fast_rcp(l_prev);
+                w1v[k] = (NS >= 1 && t >= 1) ? g1 * ry * (NS >= 2 ? r12 * s1 : 1.0f) + (1.0f - g1) * s1 : s1;
+                w2v[k] = (NS >= 2 && t >= 1) ? g2 * ry * (r12 * s2) + (1.0f - g2) * s2 : s2;
+                float *o = out + k * 4 * 64 + lane;
+                o[0] = lt;
+                o[64] = q;
+                if (NS >= 1) o[128] = s1;
+                if (NS >= 2) o[192] = s2;
+                l_prev = t < len ? lt : l_prev;
+            }
+#pragma unroll
+            for (int k = 0; k < CS; ++k) {
+                if (NS >= 1) *slot1(k) = w1v[k];     // the factor for time t + m
+                if (NS >= 2) *slot2(k) = w2v[k];
+            }
+            if (NS >= 1) { i1 += CS; if (i1 >= a.m1) i1 -= a.m1; }
+            if (NS >= 2) { i2 += CS; if (i2 >= a.m2) i2 -= a.m2; }
+        };
+        // Observations are requested kEsAhead chunks ahead: a request takes about as long as a chunk of steps,
+        // and one chunk of lead made every chunk wait for memory.  The register sets rotate through a loop
+        // unrolled kEsAhead times, so that their indices are constants.  Row offsets in 32 bits (B * T is at
+        // most 2^30): one scalar multiply per request instead of a 64-bit product.
+        float ybuf[kEsAhead][CH];
+        const unsigned ycol = in_batch ? ub : 0u;
+        auto load_chunk = [&](int c, float *dst) {
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                // raw value of a wave-uniform row (the last row again past the end); the step replaces what
+                // lies past the series' length
+                const unsigned t = (unsigned)min(c * CH + k, a.T - 1);
+                dst[k] = a.y[t * (unsigned)a.B + ycol];
+            }
+        };
+        static_for<0, kEsAhead>([&](auto d) { load_chunk(decltype(d)::value, ybuf[decltype(d)::value]); });
+        for (int c0 = 0; c0 < n_chunks; c0 += kEsAhead) {
+            static_for<0, kEsAhead>([&](auto dd) {
+                constexpr int d = decltype(dd)::value;
+                const int c = c0 + d;
+                if (c < n_chunks) {                         // (wave-uniform)
+                    float *out = stage + (c & 1) * (CH * 4 * 64);
+#pragma unroll
+                    for (int k = 0; k < CH; k += CS) {
+                        const bool wraps = (NS >= 1 && i1 + CS > a.m1) || (NS >= 2 && i2 + CS > a.m2);   // (wave-uniform)
+                        if (wraps) steps(std::true_type{}, c * CH + k, ybuf[d] + k, out + k * 4 * 64);
+                        else steps(std::false_type{}, c * CH + k, ybuf[d] + k, out + k * 4 * 64);
+                    }
+                    load_chunk(c + kEsAhead, ybuf[d]);
+                    // chunk c is staged; the other waves have finished with chunk c - 1, whose buffer chunk
+                    // c + 1 reuses
+                    lds_barrier();
+                }
+            });
+        }
+        return;
+    }
+
+    // ---- the storing waves: chunk c after the barrier that publishes it.  One loop per role, the staged
+    // values of a whole chunk read together, no branch inside a full chunk.
+    const int full_chunks = t_end / CH;            // chunks that lie entirely below the bound
+    if (role == 1) {
+        float u1 = 0.0f, u2 = 0.0f, lv_sum = 0.0f;
+        auto chunk = [&](int c, int n_steps) {
+            const float *in = stage + (c & 1) * (CH * 4 * 64) + lane;
+            float lt[CH];
+#pragma unroll
+            for (int k = 0; k < CH; ++k) lt[k] = in[k * 256];
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                if (k >= n_steps) break;
+                const int t = c * CH + k;
+                const bool live = t < len;
+                const float l = live ? lt[k] : 1.0f;
+                const float ut = live ? fast_log(l) : 0.0f;
+                const unsigned at = (unsigned)t * (unsigned)a.Bp + ub;     // (B * T is at most 2^30)
+                a.lvl[at] = l;
+                a.u[at] = ut;
+                // Section 8.4: squared second difference of the log level
+                const float e = ut - 2.0f * u1 + u2;
+                lv_sum += (live && t >= 2) ? e * e : 0.0f;
+                u2 = u1; u1 = ut;
+            }
+        };
+        for (int c = 0; c < n_chunks; ++c) {
+            lds_barrier();
+            if (c < full_chunks) chunk(c, CH);
+            else chunk(c, t_end - c * CH);
+        }
+        const float tot = wave_sum(lv_sum);
+        if (lane == 0) a.lv_partial[blockIdx.x] = tot;
+    } else if (role == 2) {
+        auto chunk = [&](int c, int n_steps) {
+            const float *in = stage + (c & 1) * (CH * 4 * 64) + 64 + lane;
+            float q[CH];
+#pragma unroll
+            for (int k = 0; k < CH; ++k) q[k] = in[k * 256];
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                if (k >= n_steps) break;
+                const int t = c * CH + k;
+                a.v[(unsigned)t * (unsigned)a.Bp + ub] = t < len ? fast_log(q[k]) : 0.0f;      // ln y - ln(S1 S2)
+            }
+        };
+        for (int c = 0; c < n_chunks; ++c) {
+            lds_barrier();
+            if (c < full_chunks) chunk(c, CH);
+            else chunk(c, t_end - c * CH);
+        }
+    } else {
+        auto chunk = [&](int c, int n_steps) {
+            const float *in = stage + (c & 1) * (CH * 4 * 64) + 128 + lane;
+            float s1[CH], s2[CH];
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                s1[k] = NS >= 1 ? in[k * 256] : 1.0f;
+                s2[k] = NS >= 2 ? in[k * 256 + 64] : 1.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                if (k >= n_steps) break;
+                const int t = c * CH + k;
+                const unsigned at = (unsigned)t * (unsigned)a.Bp + ub;
+                if (NS >= 1) a.S1[at] = t < len ? s1[k] : 1.0f;
+                if (NS >= 2) a.S2[at] = t < len ? s2[k] : 1.0f;
+            }
+        };
+        for (int c = 0; c < n_chunks; ++c) {
+            lds_barrier();
+            if (c < full_chunks) chunk(c, CH);
+            else chunk(c, t_end - c * CH);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -652,109 +760,183 @@ struct EsBwdArgs {
     int row_gamma1, row_gamma2, row_s1, row_s2;
 };
 
+// Division of labour, as in the forward recursion.  The reverse recursion is linear in the adjoints: at step t
+//   Lb   = gu[t] / l[t] + (carry),            x = Lb * alpha * q,   z1 = A1 * g1 * r1,   z2 = A2 * g2 * r2,
+//   S1b  = -gv[t] / s1 + A1 (1 - g1) - (z2 + x) / s1,        S2b likewise with the indices exchanged,
+//   Lb'  = Lb (1 - alpha) - (z1 + z2) / l[t-1]               (carried to step t-1),
+// with q = y / (s1 s2), r1 = y / (l[t-1] s2), r2 = y / (l[t-1] s1): every coefficient depends on the forward
+// pass only.  Three helper waves read the rows of a chunk of steps (a chunk ahead), form the twelve
+// coefficients of every step - all the divisions - and stage them in LDS; wave 0 carries the adjoints through
+// them: a dozen multiply-adds, the ring accesses and nothing else.
+constexpr int kEsBwdChunk = 6;                // steps per staging buffer
+constexpr int kEsBwdHelpers = 3;              // waves that form coefficients, each every third step
+constexpr int kEsBwdCoef = 12;                // coefficients per step
+constexpr int kEsBwdStageFloats = 2 * kEsBwdChunk * kEsBwdCoef * 64;
+
 template <int NS>
-__global__ void __launch_bounds__(64) es_backward_kernel(EsBwdArgs a)
+__global__ void __launch_bounds__(64 * (1 + kEsBwdHelpers)) es_backward_kernel(EsBwdArgs a)
 {
-    extern __shared__ float ring[];
-    const int lane = threadIdx.x;
-    const int b = blockIdx.x * 64 + lane;
-    const int len = b < a.B ? clamp_len(a.lengths[b], a.T) : 0;
+    extern __shared__ float ring[];           // [m1 + m2][64] rings, then [2][kEsBwdChunk][kEsBwdCoef][64] staging
+    constexpr int CH = kEsBwdChunk, NC = kEsBwdCoef;
+    const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * 64 + lane;     // column of the time-major arrays (their rows are padded to whole waves)
+    const bool in_batch = b < a.B;
+    const int bc = in_batch ? b : a.B - 1;    // column of the arrays with B columns
+    const int len = in_batch ? clamp_len(a.lengths[b], a.T) : 0;
     // the sweep starts at the last observation of the wave's longest series (rows beyond were not produced);
-    // taken while all lanes are still active
+    // both waves hold the same 64 series, so the bound is the same in both
     const int t_top = max(wave_max_int(len), 1) - 1;
-    if (b >= a.B) return;   // no barriers in this kernel
     float *ring1 = ring, *ring2 = ring + (size_t)a.m1 * 64;
-    float alpha = a.es[b], g1 = 0.0f, g2 = 0.0f;
-    if (NS >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + b];
-    if (NS >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + b];
+    float *stage = ring + (size_t)(a.m1 + a.m2) * 64;
+    float alpha = a.es[bc], g1 = 0.0f, g2 = 0.0f;
+    if (NS >= 1) g1 = a.es[(size_t)a.row_gamma1 * a.B + bc];
+    if (NS >= 2) g2 = a.es[(size_t)a.row_gamma2 * a.B + bc];
     if (a.logit) {
         alpha = 1.0f / (1.0f + expf(-alpha));
         g1 = 1.0f / (1.0f + expf(-g1));
         g2 = 1.0f / (1.0f + expf(-g2));
     }
-    for (int k = 0; k < a.m1; ++k) ring1[k * 64 + lane] = 0.0f;
-    for (int k = 0; k < a.m2; ++k) ring2[k * 64 + lane] = 0.0f;
+    for (int e = threadIdx.x; e < (a.m1 + a.m2) * 64; e += 64 * (1 + kEsBwdHelpers)) ring[e] = 0.0f;
+    __syncthreads();
+    // The sweep runs over the same times t_top ... 1 in every lane; a lane takes part from its own last
+    // observation on (its state updates are switched off before that).  Time, ring slots and row addresses
+    // are then wave-uniform.  Rows past a series' length hold defined values (level 1, factors 1, zero
+    // adjoints).  Chunk c holds the steps t = t_top - c CH - k, k = 0 .. CH-1, as far as t >= 1.
+    const int n_chunks = (t_top + CH - 1) / CH;
     float ab = 0.0f, g1b = 0.0f, g2b = 0.0f;
     float Lb_carry = 0.0f;      // contributions to the adjoint of l[t] from later steps
-    // The sweep runs over the same times T-1 ... 1 in every lane; a lane takes part from its own last
-    // observation on (its state updates are switched off before that).  Time, ring slots and row
-    // addresses are then wave-uniform, and a step has no branch: memory operations complete in
-    // order, and only with a fixed number of them between a request and its use can the operands be
-    // requested a chunk ahead without waiting for anything younger.
-    // Rows past a series' length hold defined values (level 1, factors 1, zero adjoints).
-    constexpr int CH = 4;
-    struct Chunk { float gu[CH], gv[CH], y[CH], lp[CH], s1[CH], s2[CH]; };
-    Chunk cur, nxt;
-    auto load_chunk = [&](int t_hi, Chunk &c) {
+
+    // All waves run the same loop and meet at its one barrier: in interval j the helper waves stage chunk j
+    // (helper h the steps k = h, h + 3, ...) while wave 0 consumes chunk j - 1 from the other buffer.
+    if (role >= 1) {
+        constexpr int NK = CH / kEsBwdHelpers;      // steps of a chunk per helper
+        static_assert(CH % kEsBwdHelpers == 0, "helpers share a chunk evenly");
+        struct Raw { float gu, gv, y, lt, lp, s1, s2; };
+        Raw raw[kEsAhead][NK];
+        const unsigned ub = b, ubc = bc;
+        auto load_chunk = [&](int c, Raw *r) {
 #pragma unroll
-        for (int k = 0; k < CH; ++k) {
-            const int tc = max(t_hi - k, 1);                // steps below 1 are not executed
-            const size_t row = (size_t)tc * a.Bp;           // wave-uniform
-            c.gu[k] = (a.gu + row)[b];
-            c.gv[k] = (a.gv + row)[b];
-            c.y[k] = (a.y + (size_t)tc * a.B)[b];
-            c.lp[k] = (a.lvl + row - a.Bp)[b];
-            c.s1[k] = NS >= 1 ? (a.S1 + row)[b] : 1.0f;
-            c.s2[k] = NS >= 2 ? (a.S2 + row)[b] : 1.0f;
+            for (int i = 0; i < NK; ++i) {
+                const int k = (role - 1) + i * kEsBwdHelpers;
+                const unsigned tc = (unsigned)max(t_top - c * CH - k, 1);      // steps below 1 are not executed
+                // element offsets in 32 bits (B * T is at most 2^30): one scalar multiply per row
+                const unsigned at = tc * (unsigned)a.Bp + ub;
+                r[i].gu = a.gu[at];
+                r[i].gv = a.gv[at];
+                r[i].y = a.y[tc * (unsigned)a.B + ubc];
+                r[i].lt = a.lvl[at];
+                r[i].lp = a.lvl[at - (unsigned)a.Bp];
+                r[i].s1 = NS >= 1 ? a.S1[at] : 1.0f;
+                r[i].s2 = NS >= 2 ? a.S2[at] : 1.0f;
+            }
+        };
+        // rows are requested kEsAhead chunks ahead (register sets rotating through an unrolled loop, as in the
+        // forward recursion)
+        static_for<0, kEsAhead>([&](auto d) { load_chunk(decltype(d)::value, raw[decltype(d)::value]); });
+        for (int j0 = 0; j0 <= n_chunks; j0 += kEsAhead) {
+            static_for<0, kEsAhead>([&](auto dd) {
+                constexpr int d = decltype(dd)::value;
+                const int j = j0 + d;
+                if (j > n_chunks) return;                   // (wave-uniform)
+                if (j < n_chunks) {
+                    float *out = stage + (j & 1) * (CH * NC * 64) + lane;
+#pragma unroll
+                    for (int i = 0; i < NK; ++i) {
+                        const int k = (role - 1) + i * kEsBwdHelpers;
+                        const Raw &r = raw[d][i];
+                        const float ilp = fast_rcp(r.lp);
+                        const float is1 = NS >= 1 ? fast_rcp(r.s1) : 1.0f, is2 = NS >= 2 ? fast_rcp(r.s2) : 1.0f;
+                        const float ry = r.y * ilp;
+                        const float r1 = ry * is2, r2 = ry * is1;
+                        const float q = r.y * (is1 * is2);
+                        float *o = out + k * NC * 64;
+                        o[0 * 64] = r.gu * fast_rcp(r.lt);
+                        o[1 * 64] = ilp;
+                        o[2 * 64] = alpha * q;
+                        o[3 * 64] = q - r.lp;
+                        if (NS >= 1) {
+                            o[4 * 64] = -r.gv * is1;
+                            o[5 * 64] = is1;
+                            o[6 * 64] = g1 * r1;
+                            o[7 * 64] = r1 - r.s1;
+                        }
+                        if (NS >= 2) {
+                            o[8 * 64] = -r.gv * is2;
+                            o[9 * 64] = is2;
+                            o[10 * 64] = g2 * r2;
+                            o[11 * 64] = r2 - r.s2;
+                        }
+                    }
+                    load_chunk(j + kEsAhead, raw[d]);
+                }
+                lds_barrier();
+            });
         }
-    };
-    float lt = a.lvl[(size_t)t_top * a.Bp + b];
+        return;
+    }
+
     int i1 = NS >= 1 ? t_top % a.m1 : 0, i2 = NS >= 2 ? t_top % a.m2 : 0;   // ring slot of time t: t mod m
     // adjoint of the factor for time t + m, requested one step ahead of its use
     float A1 = 0.0f, A2 = 0.0f;
-    auto step = [&](int t, int k) {
+    const float one_m_alpha = 1.0f - alpha, one_m_g1 = 1.0f - g1, one_m_g2 = 1.0f - g2;
+    auto step = [&](int t, const float (&cf)[NC]) {
         const bool active = t <= len - 1;
-        const float yt = cur.y[k], lp = cur.lp[k], s1 = cur.s1[k], s2 = cur.s2[k], gvt = cur.gv[k];
         // slot of the next step (time t-1): last written m-1 steps ago unless m = 1
         const int j1 = i1 == 0 ? a.m1 - 1 : i1 - 1, j2 = i2 == 0 ? a.m2 - 1 : i2 - 1;
         float A1n = 0.0f, A2n = 0.0f;
         if (NS >= 1) A1n = ring1[j1 * 64 + lane];
         if (NS >= 2) A2n = ring2[j2 * 64 + lane];
-        const float Lb = (cur.gu[k]) * fast_rcp(lt) + Lb_carry;
-        float S1b = NS >= 1 ? -(gvt) * fast_rcp(s1) : 0.0f;
-        float S2b = NS >= 2 ? -(gvt) * fast_rcp(s2) : 0.0f;
-        float Lb_prev = 0.0f;
-        const float ry = (yt) * fast_rcp(lp);
+        const float Lb = cf[0] + Lb_carry;
+        const float ilp = cf[1];
+        const float x = Lb * cf[2];
+        ab += active ? Lb * cf[3] : 0.0f;
+        const float z1 = NS >= 1 ? A1 * cf[6] : 0.0f;
+        const float z2 = NS >= 2 ? A2 * cf[10] : 0.0f;
         if (NS >= 1) {
-            const float A = A1;
-            const float r = (ry) * fast_rcp(s2);
-            g1b += active ? A * (r - s1) : 0.0f;
-            Lb_prev -= (A * g1 * r) * fast_rcp(lp);
-            S2b -= (A * g1 * r) * fast_rcp(s2);
-            S1b += A * (1.0f - g1);
+            const float S1b = cf[4] + A1 * one_m_g1 - (z2 + x) * cf[5];
+            g1b += active ? A1 * cf[7] : 0.0f;
+            // an inactive lane leaves the slot as it is (zero)
+            ring1[i1 * 64 + lane] = active ? S1b : A1;
+            A1 = (a.m1 == 1 && active) ? S1b : A1n;
+            i1 = j1;
         }
         if (NS >= 2) {
-            const float A = A2;
-            const float r = (ry) * fast_rcp(s1);
-            g2b += active ? A * (r - s2) : 0.0f;
-            Lb_prev -= (A * g2 * r) * fast_rcp(lp);
-            S1b -= (A * g2 * r) * fast_rcp(s1);
-            S2b += A * (1.0f - g2);
+            const float S2b = cf[8] + A2 * one_m_g2 - (z1 + x) * cf[9];
+            g2b += active ? A2 * cf[11] : 0.0f;
+            ring2[i2 * 64 + lane] = active ? S2b : A2;
+            A2 = (a.m2 == 1 && active) ? S2b : A2n;
+            i2 = j2;
         }
-        const float q = (yt) * fast_rcp(s1 * s2);
-        ab += active ? Lb * (q - lp) : 0.0f;
-        S1b -= (Lb * alpha * q) * fast_rcp(s1);
-        S2b -= (Lb * alpha * q) * fast_rcp(s2);
-        Lb_prev += Lb * (1.0f - alpha);
-        // an inactive lane leaves the slot as it is (zero)
-        if (NS >= 1) { ring1[i1 * 64 + lane] = active ? S1b : A1; A1 = (a.m1 == 1 && active) ? S1b : A1n; i1 = j1; }
-        if (NS >= 2) { ring2[i2 * 64 + lane] = active ? S2b : A2; A2 = (a.m2 == 1 && active) ? S2b : A2n; i2 = j2; }
+        const float Lb_prev = Lb * one_m_alpha - (z1 + z2) * ilp;
         Lb_carry = active ? Lb_prev : 0.0f;
-        lt = lp;
     };
     if (NS >= 1) A1 = ring1[i1 * 64 + lane];
     if (NS >= 2) A2 = ring2[i2 * 64 + lane];
-    load_chunk(t_top, cur);
-    int t_hi = t_top;
-    for (; t_hi - CH >= 0; t_hi -= CH) {        // whole chunks: steps t_hi ... t_hi-CH+1, all >= 1
-        load_chunk(t_hi - CH, nxt);
+    for (int j = 0; j <= n_chunks; ++j) {
+        if (j >= 1) {
+            const int c = j - 1;
+            const float *in = stage + (c & 1) * (CH * NC * 64) + lane;
+            const int t_hi = t_top - c * CH;
+            // the coefficients of the whole chunk, read together: one LDS round trip per chunk
+            float cf[CH][NC];
+            constexpr int NU = NS == 0 ? 4 : (NS == 1 ? 8 : 12);    // coefficients in use
 #pragma unroll
-        for (int k = 0; k < CH; ++k) step(t_hi - k, k);
-        cur = nxt;
+            for (int k = 0; k < CH; ++k)
+#pragma unroll
+                for (int i = 0; i < NU; ++i) cf[k][i] = in[(k * NC + i) * 64];
+            if (t_hi - CH >= 0) {                   // a whole chunk: no branch inside
+#pragma unroll
+                for (int k = 0; k < CH; ++k) step(t_hi - k, cf[k]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < CH; ++k)
+                    if (t_hi - k >= 1) step(t_hi - k, cf[k]);
+            }
+        }
+        lds_barrier();
     }
-#pragma unroll
-    for (int k = 0; k < CH; ++k)
-        if (t_hi - k >= 1) step(t_hi - k, k);
+    if (!in_batch) return;      // (no barrier below)
     if (len >= 1) {
         // t = 0: l[0] = y0 / (S1[0] S2[0]); the first produced factors equal the initial ones
         const size_t o = b;
@@ -1002,11 +1184,11 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
              ws + pl.loss_partial + (pl.n_loss_partial - pl.es_blocks),
              pl.B, pl.Bt, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
              c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
-    const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
+    const size_t lds = ((size_t)(a.m1 + a.m2) * 64 + kEsStageFloats) * sizeof(float);
     auto run = [&](auto kernel) {
         hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel), lds);
         if (e != hipSuccess) return e;
-        kernel<<<pl.es_blocks, 64, lds, st>>>(a);
+        kernel<<<pl.es_blocks, c.n_seas == 0 ? 192 : 256, lds, st>>>(a);
         return hipGetLastError();
     };
     // steps per group: the largest divisor of 8 that no period is shorter than
@@ -1074,11 +1256,11 @@ hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *len
     EsBwdArgs a{y, lengths, es, ws + pl.lvl, ws + pl.S1, ws + pl.S2, ws + pl.gu, ws + pl.gv, grad_es,
                 pl.B, pl.Bt, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
                 c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
-    const size_t lds = (size_t)(a.m1 + a.m2) * 64 * sizeof(float);
+    const size_t lds = ((size_t)(a.m1 + a.m2) * 64 + kEsBwdStageFloats) * sizeof(float);
     auto run = [&](auto kernel) {
         hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel), lds);
         if (e != hipSuccess) return e;
-        kernel<<<(pl.B + 63) / 64, 64, lds, st>>>(a);
+        kernel<<<(pl.B + 63) / 64, 64 * (1 + kEsBwdHelpers), lds, st>>>(a);
         return hipGetLastError();
     };
     if (c.n_seas == 0) return run(es_backward_kernel<0>);

@@ -68,16 +68,6 @@ __device__ __forceinline__ f32x4 mfma4_bcast(float a, float b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, c, 4, ABID, 0);
 }
 
-// compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1 (the broadcast block is an immediate)
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
 // value of the same register in another lane of the quad: quad_perm control [a, b, c, d]
 template <int CTRL>
 __device__ __forceinline__ float quad_perm(float v)

@@ -83,8 +83,9 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     if (cfg.n_seas < 0 || cfg.n_seas > 2) return ESRNN_ERR_CONFIG;
     if (cfg.n_seas >= 1 && (cfg.m1 < 1 || cfg.m1 > cfg.T)) return ESRNN_ERR_CONFIG;
     if (cfg.n_seas >= 2 && (cfg.m2 < 1 || cfg.m2 > cfg.T)) return ESRNN_ERR_CONFIG;
-    // the smoothing kernels keep the seasonal rings of 64 series in LDS: (m1 + m2) * 64 floats of at most 160 KB
-    if ((long long)(cfg.n_seas >= 1 ? cfg.m1 : 0) + (cfg.n_seas >= 2 ? cfg.m2 : 0) > 640) return ESRNN_ERR_CONFIG;
+    // the smoothing kernels keep the seasonal rings of 64 series in LDS: (m1 + m2) * 64 floats, which with the
+    // 48 KB staging buffer of the reverse recursion must fit into 160 KB
+    if ((long long)(cfg.n_seas >= 1 ? cfg.m1 : 0) + (cfg.n_seas >= 2 ? cfg.m2 : 0) > 448) return ESRNN_ERR_CONFIG;
     if ((long long)cfg.I + cfg.H > cfg.T) return ESRNN_ERR_CONFIG;
     if (cfg.n_blocks < 1 || cfg.n_blocks > ESRNN_MAX_BLOCKS) return ESRNN_ERR_CONFIG;
     if (!(cfg.tau > 0.0f && cfg.tau < 1.0f)) return ESRNN_ERR_CONFIG;

@@ -115,8 +115,8 @@ def test_null_and_order_errors_need_no_device(lib):
     assert lib.esrnn_set_forward_only(None, 1) == 1
     assert lib.esrnn_set_forward_only(h, 1) == 0
     assert lib.esrnn_backward(h, fake, fake, fake, fake, fake, fake, fake, None) == 4
-    # periods up to 640 in total are accepted
-    binding.esrnn_destroy(binding.esrnn_create(bad(n_seas=2, m1=400, m2=240, T=800)))
+    # periods up to 448 in total are accepted
+    binding.esrnn_destroy(binding.esrnn_create(bad(n_seas=2, m1=400, m2=48, T=800)))
     binding.esrnn_destroy(h)
 
 
