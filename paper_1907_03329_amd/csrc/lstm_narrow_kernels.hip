@@ -106,13 +106,17 @@ struct NarrowFwdArgs {
     int B, T, I, H;
 };
 
-template <int HT, int KXT, bool CP>
+// CP: the layer's cell states enter the cell-state penalty; OUT: the layer ends a residual block (reads the
+// block input, writes the block output).
+template <int HT, int KXT, bool CP, bool OUT>
 __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs a)
 {
     constexpr int KX = 4 * KXT, HP = 4 * HT;
     constexpr int CH = 8;                       // positions per chunk of staged inputs
     constexpr int XG = (KX + 15) / 16, HG = (HP + 15) / 16;   // groups of 16 columns (one register each)
-    __shared__ float xc[2][CH][XG * 64];        // inputs x_p of a chunk of positions [column][series], by chunk parity
+    // inputs x_p of a chunk of positions [column][series], by chunk parity (+ 64 floats that take the writes of
+    // the threads with no input row, so that staging is the same instruction stream in every thread)
+    __shared__ float xc[2][CH][XG * 64 + 64];
     __shared__ float rc[CH][kNT];               // residual input of this thread's (unit, series)
     __shared__ float hb[2][HG * 64];            // h_{p-d} [unit][series], by position parity
 
@@ -144,7 +148,7 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
     // cooperative input load: thread t < 4*KX brings row t/4 of series t%4 (the others repeat row 0)
     const bool x_thread = (int)threadIdx.x < 4 * KX;
     const int x_off = (x_thread ? (int)threadIdx.x >> 2 : 0) * 16 + 4 * q + (threadIdx.x & 3);
-    const bool has_out = a.out != nullptr;
+    const int x_slot = x_thread ? (int)threadIdx.x : XG * 64 + lane;
 
     int n_valid = 0;
     float csq = 0.0f;
@@ -154,7 +158,7 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
         n_valid = len - a.I - a.H + 1;
     }
     // columns past KX / HP in the last group of 16 are never written: zero once (their weights do not exist)
-    for (int e = threadIdx.x; e < 2 * CH * XG * 64; e += kNT) (&xc[0][0][0])[e] = 0.0f;
+    for (int e = threadIdx.x; e < 2 * CH * (XG * 64 + 64); e += kNT) (&xc[0][0][0])[e] = 0.0f;
     for (int e = threadIdx.x; e < 2 * HG * 64; e += kNT) (&hb[0][0])[e] = 0.0f;
 
     for (int r = blockIdx.y; r < a.d && r < Pt; r += gridDim.y) {
@@ -165,35 +169,28 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
             for (int ii = 0; ii < CH; ++ii) {
                 const size_t tile = (size_t)(r + min(c * CH + ii, n - 1) * a.d) * a.NB + bt;
                 xs[ii] = (a.xsrc + tile * (KX * 16))[x_off];
-                rs[ii] = has_out ? (a.resid + tile * (HP * 16))[lane_off] : 0.0f;
+                rs[ii] = OUT ? (a.resid + tile * (HP * 16))[lane_off] : 0.0f;
             }
         };
         auto flush_chunk = [&](int c) {
 #pragma unroll
             for (int ii = 0; ii < CH; ++ii) {
-                if (x_thread) xc[c & 1][ii][threadIdx.x] = xs[ii];
-                rc[ii][threadIdx.x] = rs[ii];
+                xc[c & 1][ii][x_slot] = xs[ii];
+                if (OUT) rc[ii][threadIdx.x] = rs[ii];
             }
         };
-        // start of a chain: zero state, inputs of the first chunk staged, those of the second requested
-        load_chunk(0);
         float creg = 0.0f;
-        __syncthreads();            // LDS free: initial clearing, or the last position of the previous chain
-        for (int e = threadIdx.x; e < 4 * HP; e += kNT) hb[0][e] = 0.0f;
-        flush_chunk(0);
-        load_chunk(1);
-        lds_barrier();
-
-        for (int i = 0; i < n; ++i) {
-            const int c = i / CH, ii = i % CH;
+        // One position.  `staged` runs after the recurrent state is published and before the position's
+        // stores are issued (the staging of the next chunk goes there).
+        auto position = [&](int i, int ii, int cpar, auto staged) {
             const int p = r + i * a.d;
             // [x_p ; h_{p-d}] of the four series: lane (b, s) of register m holds column 16m + b of series s
             float vh[HG], vx[XG];
 #pragma unroll
             for (int m = 0; m < HG; ++m) vh[m] = hb[i & 1][64 * m + lane];
 #pragma unroll
-            for (int m = 0; m < XG; ++m) vx[m] = xc[c & 1][ii][64 * m + lane];
-            const float res = rc[ii][threadIdx.x];
+            for (int m = 0; m < XG; ++m) vx[m] = xc[cpar][ii][64 * m + lane];
+            const float res = OUT ? rc[ii][threadIdx.x] : 0.0f;
             // two accumulators: consecutive instructions never depend on each other (measured: one is
             // slower, four are slower too)
             f32x4 acc0 = f32x4{bias, bias, bias, bias}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -218,21 +215,38 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
             creg = cn;
             if constexpr (CP) csq += (valid && p < n_valid) ? cn * cn : 0.0f;
             hb[(i + 1) & 1][4 * unit + j] = hn;
-            // last position of a chunk: stage the next chunk, request the one after it.  Placed ahead of
-            // this position's stores: the wait for the staged registers then only meets stores that are
-            // a whole position old.
-            if (ii == CH - 1 && i + 1 < n) {
-                flush_chunk(c + 1);
-                load_chunk(c + 2);
-            }
+            staged();
             // wave-uniform tile base plus the lane's element: scalar address arithmetic
             const size_t tile = ((size_t)p * a.NB + bt) * (HP * 16);
             __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + tile + lane_off);
             __builtin_nontemporal_store(cn, a.c + tile + lane_off);
             (a.hid + tile)[lane_off] = hn;
-            if (has_out) (a.out + tile)[lane_off] = res + hn;
+            if (OUT) (a.out + tile)[lane_off] = res + hn;
             lds_barrier();
+        };
+        // start of a chain: zero state, inputs of the first chunk staged
+        load_chunk(0);
+        __syncthreads();            // LDS free: initial clearing, or the last position of the previous chain
+        for (int e = threadIdx.x; e < 4 * HP; e += kNT) hb[0][e] = 0.0f;
+        flush_chunk(0);
+        lds_barrier();
+
+        // Whole chunks: the body of a chunk is one straight run of instructions.  The inputs of the next chunk
+        // are requested at its start and staged at its end, before the stores of its last position: memory
+        // operations complete in order, and with request and use in the same run the wait for a request is a
+        // count of the stores issued since (those of seven positions), never a wait for the newest stores.
+        int c = 0;
+        for (; (c + 1) * CH <= n; ++c) {
+            load_chunk(c + 1);              // (row indices stop at the chain's last position)
+            static_for<0, CH>([&](auto iic) {
+                constexpr int ii = decltype(iic)::value;
+                position(c * CH + ii, ii, c & 1, [&] {
+                    if constexpr (ii == CH - 1) flush_chunk(c + 1);
+                });
+            });
         }
+        // the last, partial chunk (staged by the run before it, or by the start of the chain)
+        for (int i = c * CH; i < n; ++i) position(i, i - c * CH, c & 1, [] {});
     }
     if constexpr (CP) {
         __shared__ float s_cs[kNW];
@@ -281,8 +295,10 @@ struct NarrowBwdArgs {
     int B, T, I, H;
 };
 
+// (up to hidden 40 the kernel is held to 256 registers: two workgroups per compute unit, which the chains of a
+// dilated layer need to run side by side)
 template <int HT, int KXT, bool CP>
-__global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs a)
+__global__ void __launch_bounds__(kNT, HT <= 10 ? 2 : 1) lstm_backward_narrow_kernel(NarrowBwdArgs a)
 {
     constexpr int KX = 4 * KXT, HP = 4 * HT, KT4 = KX + HP;
     constexpr int CH = 4;                        // positions per chunk of staged operands
@@ -383,15 +399,17 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
         float dcreg = 0.0f, dhreg = 0.0f;
         __syncthreads();            // LDS free: initial clearing, or the last position of the previous chain
         flush_chunk(0);
-        load_chunk(1);
         lds_barrier();
 
         // per-thread operands of the first position; those of position i+1 are read before the barrier
         // that ends position i
         f32x4 gt = lc[0][0][threadIdx.x];      // activated input, forget, candidate, output gate
         f32x4 o = lc[0][1][threadIdx.x];       // c, c_{p-d}, gradient sources
-        for (int i = 0; i < n; ++i) {
-            const int c = i / CH, ii = i % CH, par = i & 1;
+        // One position: the i-th from the end of the chain, staged in slot ii of the chunk buffers of parity
+        // cpar; the per-thread operands of the next position are in slot `next`.  `staged` runs after they
+        // have been read and before the barrier (the staging of the next chunk goes there).
+        auto position = [&](int i, int ii, int cpar, int next, auto staged) {
+            const int par = i & 1;
             const int p = p_last - i * a.d;
             const bool has_prev = p >= a.d;
             // ---- A: gate gradients of (unit, series)
@@ -435,17 +453,9 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
                 *reinterpret_cast<f32x4 *>(&part[par][w][(64 * g + lane) * 4]) =
                     kBwdAcc == 4 ? (acc[g][0] + acc[g][1]) + (acc[g][2] + acc[g][3]) : kBwdAcc == 2 ? acc[g][0] + acc[g][1] : acc[g][0];
             // per-thread operands of the next position (staged at least one barrier ago)
-            {
-                const int i1 = min(i + 1, n - 1);
-                gt = lc[i1 % CH][0][threadIdx.x];
-                o = lc[i1 % CH][1][threadIdx.x];
-            }
-            // one position before the end of a chunk: stage the next chunk, request the one after it
-            // (after this thread has read its operands of the chunk's last position)
-            if (ii == CH - 2 && (c + 1) * CH < n) {
-                flush_chunk(c + 1);
-                load_chunk(c + 2);
-            }
+            gt = lc[next][0][threadIdx.x];
+            o = lc[next][1][threadIdx.x];
+            staged();
             lds_barrier();
             // ---- sums of the four partials: recurrent dh of this lane; input gradient
             {
@@ -458,7 +468,7 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
             {
                 float xb[CT];
 #pragma unroll
-                for (int nb = 0; nb < CT; ++nb) xb[nb] = xhc[c & 1][ii][64 * nb + xb_off];
+                for (int nb = 0; nb < CT; ++nb) xb[nb] = xhc[cpar][ii][64 * nb + xb_off];
 #pragma unroll
                 for (int t = 0; t < MTW; ++t) {
                     const int mt = w + kNW * t;
@@ -470,7 +480,23 @@ __global__ void __launch_bounds__(kNT) lstm_backward_narrow_kernel(NarrowBwdArgs
                     }
                 }
             }
+        };
+        // Whole chunks: one straight run of instructions each.  The operands of the next chunk are requested
+        // at its start and staged one position before its end (after this thread has read its operands of the
+        // chunk's last position): request and use in the same run, so the wait for a request counts the
+        // memory operations issued since instead of waiting for all of them.
+        int c = 0;
+        for (; (c + 1) * CH <= n; ++c) {
+            load_chunk(c + 1);              // (requests past the chain repeat its last position)
+            static_for<0, CH>([&](auto iic) {
+                constexpr int ii = decltype(iic)::value;
+                position(c * CH + ii, ii, c & 1, (ii + 1) % CH, [&] {
+                    if constexpr (ii == CH - 2) flush_chunk(c + 1);
+                });
+            });
         }
+        // the last, partial chunk (staged by the run before it, or by the start of the chain)
+        for (int i = c * CH; i < n; ++i) position(i, i - c * CH, c & 1, min(i + 1, n - 1) - c * CH, [] {});
     }
 
     const size_t partix = (size_t)(4 * bt + q) * gridDim.y + blockIdx.y;
@@ -507,8 +533,14 @@ inline int narrow_grid_x(int NB) { return ((NB + 7) / 8) * 32; }
 template <int HT, int KXT>
 hipError_t run_nfwd(const NarrowFwdArgs &a, int chains, hipStream_t st)
 {
-    if (a.cs_partial) lstm_forward_narrow_kernel<HT, KXT, true><<<dim3(narrow_grid_x(a.NB), chains), 64 * kNW, 0, st>>>(a);
-    else lstm_forward_narrow_kernel<HT, KXT, false><<<dim3(narrow_grid_x(a.NB), chains), 64 * kNW, 0, st>>>(a);
+    const dim3 grid(narrow_grid_x(a.NB), chains);
+    if (a.cs_partial) {
+        if (a.out) lstm_forward_narrow_kernel<HT, KXT, true, true><<<grid, 64 * kNW, 0, st>>>(a);
+        else lstm_forward_narrow_kernel<HT, KXT, true, false><<<grid, 64 * kNW, 0, st>>>(a);
+    } else {
+        if (a.out) lstm_forward_narrow_kernel<HT, KXT, false, true><<<grid, 64 * kNW, 0, st>>>(a);
+        else lstm_forward_narrow_kernel<HT, KXT, false, false><<<grid, 64 * kNW, 0, st>>>(a);
+    }
     return hipGetLastError();
 }
 
