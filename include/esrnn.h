@@ -205,7 +205,7 @@ esrnn_status esrnn_adam_update_indexed(esrnn_handle *h, const esrnn_adam_config 
                                        void *workspace, void *stream);
 
 /*
- * Out-of-sample forecasts (Section 3.4 "testing of the network", Eq. (4), (5)):
+ * Out-of-sample forecasts (Section 3.4, the use of the trained network on a series' end; Eq. (4), (5)):
  * the H steps after each series' last observation, from the window of the last
  * I observations, de-normalised with the last level and re-seasonalised with
  * the last m factors of the recursion repeated with period m.

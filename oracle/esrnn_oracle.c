@@ -125,8 +125,8 @@ static void loss_counts(const eso_config *c, const int32_t *lengths, double *n_p
 /* Section 3.1 Eq. (1), (3) without trend (b == 1, text after Eq. (4)), with
  * the Section 8.2 variants.  S[t] is the seasonal factor that applies to time
  * t: the paper's s_{t-m} in Eq. (1); Eq. (3) produces the factor for t + m.
- * Reading for the state before the first observation (Section 3.3 only says
- * "primer estimate"): l_{-1} = y_0 / S[0], which makes l_0 = y_0 / S[0] and
+ * Reading for the state before the first observation (Section 3.3 only asks
+ * for some initial estimate): l_{-1} = y_0 / S[0], which makes l_0 = y_0 / S[0] and
  * the first updated factor equal to the initial one. */
 static void es_forward_series(const eso_config *c, const plan_t *pl, int b, int len,
                               const double *y, const double *es, eso_tape *tp)
@@ -311,8 +311,8 @@ static void loss_series(const eso_config *c, const plan_t *pl, int b, int len,
             }
 }
 
-/* Section 8.4, second kind of penalty: the average squared magnitude of the cell state of the first
- * layer of every block ("stack").  Reading: one average over those layers, the valid window positions
+/* Section 8.4, second kind of penalty: the mean of the squared cell states of the first layer of
+ * every block (the paper's word for a block is stack).  Reading: one average over those layers, the valid window positions
  * of all series and the hidden units; this returns one series' sum of squares. */
 static double cell_state_sumsq(const eso_config *c, const plan_t *pl, int b, int Pb, const eso_tape *tp)
 {
@@ -670,7 +670,7 @@ int eso_backward(const eso_config *cfg, const double *y, const int32_t *lengths,
 /* Out-of-sample forecast, one series at a time                               */
 /* ------------------------------------------------------------------------- */
 
-/* Section 3.4 ("testing of the network") with Eq. (4) and (5): the smoothing
+/* Section 3.4 (forecasting from the end of a series) with Eq. (4) and (5): the smoothing
  * recursions run over the whole series; every position with a complete input
  * window goes through the network (no targets are needed); the output at the
  * last position, whose window ends at the last observation t = len-1, is

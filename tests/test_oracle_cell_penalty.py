@@ -1,5 +1,5 @@
-"""Pins of the cell-state penalty (Section 8.4: the average squared magnitude of the cell state of the
-first layer of every block is penalised).  No GPU."""
+"""Pins of the cell-state penalty (Section 8.4: the mean of the squared cell states of the first layer of
+every block enters the loss).  No GPU."""
 import numpy as np
 
 from oracle import oracle
