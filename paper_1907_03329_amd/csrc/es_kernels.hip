@@ -261,13 +261,13 @@ struct EsArgs {
 // only chain is the level (one multiply-add per step); divisions and seasonal updates of the other steps
 // overlap with it.
 //
-// Division of labour.  A workgroup serves 64 series with two or three waves.  Wave 0 runs the recursion and
-// nothing else: it reads observations (a chunk ahead), keeps the rings, and leaves level, de-seasonalised
-// value and factors of every step in an LDS staging buffer; it issues no global store, so nothing it waits
-// for is ever queued behind one.  Of the previous chunk, wave 1 turns the staged level into lvl, u = ln(level)
-// and the level penalty, wave 2 the staged value into v, and wave 3 (seasonal shapes) stores the factors.
-// A wave can have only so many memory operations in flight; five stores per step on the wave that also
-// carries the chain made the chain wait for store latency.
+// Division of labour.  A workgroup serves 64 series with three or four waves.  Wave 0 runs the recursion and
+// nothing else: it reads observations (several chunks ahead), keeps the rings, and leaves level,
+// de-seasonalised value and factors of every step in an LDS staging buffer; it issues no global store and
+// computes no logarithm.  Of the previous chunk, wave 1 turns the staged level into lvl, u = ln(level) and
+// the level penalty, wave 2 the staged value into v, and wave 3 (seasonal shapes) stores the factors.  A lone
+// wave issues one instruction every few cycles whatever the instruction is; with the chain, five stores and two
+// logarithms per step on the same wave a step took about three times as long as the chain alone.
 constexpr int kEsChunk = 8;                 // steps per staging buffer
 constexpr int kEsAhead = 4;                 // chunks between the request of a row and its use
 constexpr int kEsStageFloats = 2 * kEsChunk * 4 * 64;
