@@ -238,6 +238,13 @@ def test_long_seasonal_periods_use_large_lds():
     report(gc.run_and_check(cfg, seed=27, ragged=True))
 
 
+def test_seasonal_periods_at_the_limit():
+    """m1 + m2 = 448, the most the library accepts: rings of 112 KB beside the staging buffers of the smoothing
+    kernels (128 KB of LDS per workgroup in the forward, 148 KB in the reverse recursion)."""
+    cfg = small("ring_limit", T=470, n_seas=2, m1=300, m2=148, seas_sd2=0.1, I=4, H=8, B=70, blocks=((1, 2),))
+    report(gc.run_and_check(cfg, seed=28, ragged=True))
+
+
 def test_forecasts_may_be_omitted_and_stream_is_honoured():
     import torch
     from paper_1907_03329_amd import binding
