@@ -270,13 +270,14 @@ struct EsArgs {
 // logarithms per step on the same wave a step took about three times as long as the chain alone.
 constexpr int kEsChunk = 8;                 // steps per staging buffer
 constexpr int kEsAhead = 4;                 // chunks between the request of a row and its use
-constexpr int kEsStageFloats = 2 * kEsChunk * 4 * 64;
+// staged per step: level, de-seasonalised value, and one factor per seasonality
+constexpr int es_stage_floats(int n_seas) { return 2 * kEsChunk * (2 + n_seas) * 64; }
 
 template <int NS, int CS>
 __global__ void __launch_bounds__(NS == 0 ? 192 : 256) es_forward_kernel(EsArgs a)
 {
-    extern __shared__ float ring[];   // [m1 + m2][64] rings, then [2][kEsChunk][4][64] staging
-    constexpr int CH = kEsChunk;
+    extern __shared__ float ring[];   // [m1 + m2][64] rings, then [2][kEsChunk][2 + NS][64] staging
+    constexpr int CH = kEsChunk, NF = 2 + NS;
     static_assert(CH % CS == 0, "groups tile a chunk");
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
@@ -361,7 +362,7 @@ __global__ void __launch_bounds__(NS == 0 ? 192 : 256) es_forward_kernel(EsArgs 
                 const float ry = yt * fast_rcp(l_prev);
                 w1v[k] = (NS >= 1 && t >= 1) ? g1 * ry * (NS >= 2 ? r12 * s1 : 1.0f) + (1.0f - g1) * s1 : s1;
                 w2v[k] = (NS >= 2 && t >= 1) ? g2 * ry * (r12 * s2) + (1.0f - g2) * s2 : s2;
-                float *o = out + k * 4 * 64 + lane;
+                float *o = out + k * NF * 64 + lane;
                 o[0] = lt;
                 o[64] = q;
                 if (NS >= 1) o[128] = s1;
@@ -397,12 +398,12 @@ __global__ void __launch_bounds__(NS == 0 ? 192 : 256) es_forward_kernel(EsArgs 
                 constexpr int d = decltype(dd)::value;
                 const int c = c0 + d;
                 if (c < n_chunks) {                         // (wave-uniform)
-                    float *out = stage + (c & 1) * (CH * 4 * 64);
+                    float *out = stage + (c & 1) * (CH * NF * 64);
 #pragma unroll
                     for (int k = 0; k < CH; k += CS) {
                         const bool wraps = (NS >= 1 && i1 + CS > a.m1) || (NS >= 2 && i2 + CS > a.m2);   // (wave-uniform)
-                        if (wraps) steps(std::true_type{}, c * CH + k, ybuf[d] + k, out + k * 4 * 64);
-                        else steps(std::false_type{}, c * CH + k, ybuf[d] + k, out + k * 4 * 64);
+                        if (wraps) steps(std::true_type{}, c * CH + k, ybuf[d] + k, out + k * NF * 64);
+                        else steps(std::false_type{}, c * CH + k, ybuf[d] + k, out + k * NF * 64);
                     }
                     load_chunk(c + kEsAhead, ybuf[d]);
                     // chunk c is staged; the other waves have finished with chunk c - 1, whose buffer chunk
@@ -420,10 +421,10 @@ __global__ void __launch_bounds__(NS == 0 ? 192 : 256) es_forward_kernel(EsArgs 
     if (role == 1) {
         float u1 = 0.0f, u2 = 0.0f, lv_sum = 0.0f;
         auto chunk = [&](int c, int n_steps) {
-            const float *in = stage + (c & 1) * (CH * 4 * 64) + lane;
+            const float *in = stage + (c & 1) * (CH * NF * 64) + lane;
             float lt[CH];
 #pragma unroll
-            for (int k = 0; k < CH; ++k) lt[k] = in[k * 256];
+            for (int k = 0; k < CH; ++k) lt[k] = in[k * NF * 64];
 #pragma unroll
             for (int k = 0; k < CH; ++k) {
                 if (k >= n_steps) break;
@@ -449,10 +450,10 @@ __global__ void __launch_bounds__(NS == 0 ? 192 : 256) es_forward_kernel(EsArgs 
         if (lane == 0) a.lv_partial[blockIdx.x] = tot;
     } else if (role == 2) {
         auto chunk = [&](int c, int n_steps) {
-            const float *in = stage + (c & 1) * (CH * 4 * 64) + 64 + lane;
+            const float *in = stage + (c & 1) * (CH * NF * 64) + 64 + lane;
             float q[CH];
 #pragma unroll
-            for (int k = 0; k < CH; ++k) q[k] = in[k * 256];
+            for (int k = 0; k < CH; ++k) q[k] = in[k * NF * 64];
 #pragma unroll
             for (int k = 0; k < CH; ++k) {
                 if (k >= n_steps) break;
@@ -467,12 +468,12 @@ __global__ void __launch_bounds__(NS == 0 ? 192 : 256) es_forward_kernel(EsArgs 
         }
     } else {
         auto chunk = [&](int c, int n_steps) {
-            const float *in = stage + (c & 1) * (CH * 4 * 64) + 128 + lane;
+            const float *in = stage + (c & 1) * (CH * NF * 64) + 128 + lane;
             float s1[CH], s2[CH];
 #pragma unroll
             for (int k = 0; k < CH; ++k) {
-                s1[k] = NS >= 1 ? in[k * 256] : 1.0f;
-                s2[k] = NS >= 2 ? in[k * 256 + 64] : 1.0f;
+                s1[k] = NS >= 1 ? in[k * NF * 64] : 1.0f;
+                s2[k] = NS >= 2 ? in[k * NF * 64 + 64] : 1.0f;
             }
 #pragma unroll
             for (int k = 0; k < CH; ++k) {
@@ -770,14 +771,15 @@ struct EsBwdArgs {
 // them: a dozen multiply-adds, the ring accesses and nothing else.
 constexpr int kEsBwdChunk = 6;                // steps per staging buffer
 constexpr int kEsBwdHelpers = 3;              // waves that form coefficients, each every third step
-constexpr int kEsBwdCoef = 12;                // coefficients per step
-constexpr int kEsBwdStageFloats = 2 * kEsBwdChunk * kEsBwdCoef * 64;
+// coefficients per step: four, and four more per seasonality
+constexpr int es_bwd_coefs(int n_seas) { return 4 + 4 * n_seas; }
+constexpr int es_bwd_stage_floats(int n_seas) { return 2 * kEsBwdChunk * es_bwd_coefs(n_seas) * 64; }
 
 template <int NS>
 __global__ void __launch_bounds__(64 * (1 + kEsBwdHelpers)) es_backward_kernel(EsBwdArgs a)
 {
-    extern __shared__ float ring[];           // [m1 + m2][64] rings, then [2][kEsBwdChunk][kEsBwdCoef][64] staging
-    constexpr int CH = kEsBwdChunk, NC = kEsBwdCoef;
+    extern __shared__ float ring[];           // [m1 + m2][64] rings, then [2][kEsBwdChunk][4 + 4 NS][64] staging
+    constexpr int CH = kEsBwdChunk, NC = es_bwd_coefs(NS);
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int b = blockIdx.x * 64 + lane;     // column of the time-major arrays (their rows are padded to whole waves)
@@ -891,19 +893,19 @@ __global__ void __launch_bounds__(64 * (1 + kEsBwdHelpers)) es_backward_kernel(E
         const float ilp = cf[1];
         const float x = Lb * cf[2];
         ab += active ? Lb * cf[3] : 0.0f;
-        const float z1 = NS >= 1 ? A1 * cf[6] : 0.0f;
-        const float z2 = NS >= 2 ? A2 * cf[10] : 0.0f;
+        const float z1 = NS >= 1 ? A1 * cf[NS >= 1 ? 6 : 0] : 0.0f;
+        const float z2 = NS >= 2 ? A2 * cf[NS >= 2 ? 10 : 0] : 0.0f;
         if (NS >= 1) {
-            const float S1b = cf[4] + A1 * one_m_g1 - (z2 + x) * cf[5];
-            g1b += active ? A1 * cf[7] : 0.0f;
+            const float S1b = cf[NS >= 1 ? 4 : 0] + A1 * one_m_g1 - (z2 + x) * cf[NS >= 1 ? 5 : 0];
+            g1b += active ? A1 * cf[NS >= 1 ? 7 : 0] : 0.0f;
             // an inactive lane leaves the slot as it is (zero)
             ring1[i1 * 64 + lane] = active ? S1b : A1;
             A1 = (a.m1 == 1 && active) ? S1b : A1n;
             i1 = j1;
         }
         if (NS >= 2) {
-            const float S2b = cf[8] + A2 * one_m_g2 - (z1 + x) * cf[9];
-            g2b += active ? A2 * cf[11] : 0.0f;
+            const float S2b = cf[NS >= 2 ? 8 : 0] + A2 * one_m_g2 - (z1 + x) * cf[NS >= 2 ? 9 : 0];
+            g2b += active ? A2 * cf[NS >= 2 ? 11 : 0] : 0.0f;
             ring2[i2 * 64 + lane] = active ? S2b : A2;
             A2 = (a.m2 == 1 && active) ? S2b : A2n;
             i2 = j2;
@@ -920,11 +922,10 @@ __global__ void __launch_bounds__(64 * (1 + kEsBwdHelpers)) es_backward_kernel(E
             const int t_hi = t_top - c * CH;
             // the coefficients of the whole chunk, read together: one LDS round trip per chunk
             float cf[CH][NC];
-            constexpr int NU = NS == 0 ? 4 : (NS == 1 ? 8 : 12);    // coefficients in use
 #pragma unroll
             for (int k = 0; k < CH; ++k)
 #pragma unroll
-                for (int i = 0; i < NU; ++i) cf[k][i] = in[(k * NC + i) * 64];
+                for (int i = 0; i < NC; ++i) cf[k][i] = in[(k * NC + i) * 64];
             if (t_hi - CH >= 0) {                   // a whole chunk: no branch inside
 #pragma unroll
                 for (int k = 0; k < CH; ++k) step(t_hi - k, cf[k]);
@@ -1184,7 +1185,7 @@ hipError_t launch_es_forward(const Plan &pl, const float *y, const int32_t *leng
              ws + pl.loss_partial + (pl.n_loss_partial - pl.es_blocks),
              pl.B, pl.Bt, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
              c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
-    const size_t lds = ((size_t)(a.m1 + a.m2) * 64 + kEsStageFloats) * sizeof(float);
+    const size_t lds = ((size_t)(a.m1 + a.m2) * 64 + es_stage_floats(c.n_seas)) * sizeof(float);
     auto run = [&](auto kernel) {
         hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel), lds);
         if (e != hipSuccess) return e;
@@ -1256,7 +1257,7 @@ hipError_t launch_es_backward(const Plan &pl, const float *y, const int32_t *len
     EsBwdArgs a{y, lengths, es, ws + pl.lvl, ws + pl.S1, ws + pl.S2, ws + pl.gu, ws + pl.gv, grad_es,
                 pl.B, pl.Bt, pl.T, c.n_seas, c.n_seas >= 1 ? c.m1 : 0, c.n_seas >= 2 ? c.m2 : 0,
                 c.param_space == ESRNN_PARAMS_LOGIT, pl.row_gamma1, pl.row_gamma2, pl.row_s1, pl.row_s2};
-    const size_t lds = ((size_t)(a.m1 + a.m2) * 64 + kEsBwdStageFloats) * sizeof(float);
+    const size_t lds = ((size_t)(a.m1 + a.m2) * 64 + es_bwd_stage_floats(c.n_seas)) * sizeof(float);
     auto run = [&](auto kernel) {
         hipError_t e = allow_large_lds(reinterpret_cast<const void *>(kernel), lds);
         if (e != hipSuccess) return e;
