@@ -283,7 +283,9 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     // elements past the end of [x ; h] alias its last element.
     float4 pf_gt[MTW];
     float pf_c[MTW], pf_cp[MTW], pf_g[MTW], pf_g2[MTW], pf_xh[XH_PER_THREAD];
-    auto fetch = [&](int p) {
+    // `first`: the chain's first request.  Later ones follow a request for position p + d, whose predecessor
+    // cell state c[p] is still in registers: it is not read from memory a second time.
+    auto fetch = [&](int p, bool first) {
         const size_t pb = (size_t)p * a.NB + bt;
         const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
         // wave-uniform tile bases plus the lane index: scalar address arithmetic
@@ -292,7 +294,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             const int mt = min(s + W * j, HT - 1);
             const size_t tile = (pb * HT + mt) * 64;
             pf_gt[j] = (reinterpret_cast<const float4 *>(a.gates) + tile)[lane];
-            pf_c[j] = (a.c + tile)[lane];
+            pf_c[j] = first ? (a.c + tile)[lane] : pf_cp[j];
             pf_cp[j] = (a.c + (pbd * HT + mt) * 64)[lane];
             pf_g[j] = (a.gsrc[0] + tile)[lane];
             pf_g2[j] = (a.gsrc[1] + tile)[lane];    // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
@@ -420,11 +422,11 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 #pragma unroll
         for (int j = 0; j < MTW; ++j) { dcreg[j] = 0.0f; dhreg[j] = 0.0f; }
         __syncthreads();            // LDS free (previous chain / initial clearing)
-        fetch(p_last);
+        fetch(p_last, true);
         store_xh(p_last >= a.d);
 #pragma unroll
         for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d, p_last);
-        fetch(max(p_last - a.d, r0));
+        fetch(max(p_last - a.d, r0), false);
         step_b();
 
         for (int p = p_last; p >= a.d; p -= a.d) {
@@ -440,7 +442,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             }
             step_a_tile(MTW - 1, has_prev, p - a.d);
             if (kDxLate) store_dx(p);
-            fetch(max(p - 2 * a.d, r0));
+            fetch(max(p - 2 * a.d, r0), false);
             if (last_row_valid) dw_row(MTW - 1);
             step_b();
         }
