@@ -37,14 +37,17 @@
 //
 // Global operands.  A position takes a fraction of a microsecond here, less
 // than the latency of HBM, so operands are requested a whole chunk of positions
-// ahead: at the last position of a chunk the registers that hold the next chunk
-// go to LDS and the requests for the chunk after it are issued.  Inside a chunk
-// the position loop issues no load at all, only stores, which nothing waits
-// for.  (A ring of registers with one request per position was slower: memory
-// operations complete in order, and where the paths into a loop differ the
-// compiler's wait for the oldest request also waits for the stores issued
-// since.)  Blocks past HT repeat the last unit of the wave, operands and
-// addresses alike, so no memory operation sits behind a divergent branch.
+// ahead into registers and staged in LDS: the requests for the next chunk go
+// out at the start of a chunk, and at its end the registers are written to LDS.
+// A whole chunk is ONE straight run of instructions (the position loop inside
+// it is unrolled): memory operations complete in order, and only with request
+// and use in the same run does the compiler's wait for a request count the
+// stores issued since instead of waiting for all of them.  (With the request in
+// one loop iteration and the use in another, every chunk waited for its newest
+// stores; a ring of registers with one request per position was slower still.)
+// Blocks past HT repeat the last unit of the wave, operands and addresses alike,
+// and threads without an input row stage into a spare LDS column, so no memory
+// operation sits behind a divergent branch.
 //
 // All tensors keep the layouts of the 16-series kernels (TL(R) tiles of 16
 // series), so layers of both kinds mix freely and the weight-gradient
