@@ -669,6 +669,10 @@ __global__ void __launch_bounds__(256) window_backward_stream_kernel(const float
 
     for (int s0 = -((I + 2) & ~3); s0 < T; s0 += 4) {      // output block: gv[s0 .. s0+3], gu[s0+I-1 .. s0+I+2]
         float su[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        // the penalty term of this lane's gu row, requested ahead of the gradient tiles: its five loads then
+        // travel together with theirs instead of being a second round trip at the end of the block
+        const int t_pen = s0 + g + I - 1;
+        const float pen_grad = (lambda != 0.0f && t_pen >= 0 && t_pen < T) ? level_penalty_grad(u, Bp, col, t_pen, len, pen) : 0.0f;
         if (s0 + 3 >= 0 && s0 < Pt) {
             for (int e0 = 0; e0 < Q; e0 += 4) {
                 float w[4][4];
@@ -733,7 +737,7 @@ __global__ void __launch_bounds__(256) window_backward_stream_kernel(const float
         }
         const int t = s + I - 1;
         if (t >= 0 && t < T) {
-            gu[(size_t)t * Bp + col] = mine + (lambda != 0.0f ? level_penalty_grad(u, Bp, col, t, len, pen) : 0.0f);
+            gu[(size_t)t * Bp + col] = mine + pen_grad;
         }
         if (pads && pad_col < Bp) {
             for (int k = 0; k < 4; ++k) {
