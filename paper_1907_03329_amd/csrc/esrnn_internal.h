@@ -16,7 +16,10 @@ constexpr int kTileN = 16;       // series per tile (N of the 16x16x4 fp32 MFMA)
 constexpr int kMaxLayers = ESRNN_MAX_BLOCKS * ESRNN_MAX_LAYERS_PER_BLOCK;
 constexpr int kLstmWaves = 4;    // waves per workgroup in the LSTM kernels
 constexpr int kReduceSplits = 16; // subsets of producers in the first stage of the weight-gradient reduction
-constexpr int kLdsPad = 17;      // row stride of LDS arrays that are read transposed
+// Row stride of the LDS arrays [row][16 series] that are read transposed (lane = row n, column 4k + g).  With 18
+// the 32 lanes of a half wave (16 rows x 2 columns) hit 32 different banks: (18 n + g) mod 32 takes every value
+// once.  (17, the usual odd padding, leaves one two-way conflict in every such read.)
+constexpr int kLdsPad = 18;
 constexpr int kNarrowSeries = 4; // series per workgroup in the small-batch LSTM kernels
 
 // Tile layout TL(R): [P][NB][R][16]; element (p, b, r) at ((p*NB + b/16)*R + r)*16 + b%16.
