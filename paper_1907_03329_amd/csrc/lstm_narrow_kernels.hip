@@ -222,7 +222,7 @@ __global__ void __launch_bounds__(kNT) lstm_forward_narrow_kernel(NarrowFwdArgs 
             // wave-uniform tile base plus the lane's element: scalar address arithmetic
             const size_t tile = ((size_t)p * a.NB + bt) * (HP * 16);
             __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + tile + lane_off);
-            __builtin_nontemporal_store(cn, a.c + tile + lane_off);
+            (a.c + tile)[lane_off] = cn;     // (a plain store: the four quarter-row writes of a tile then merge in L2)
             (a.hid + tile)[lane_off] = hn;
             if (OUT) (a.out + tile)[lane_off] = res + hn;
             lds_barrier();
