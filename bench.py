@@ -184,9 +184,10 @@ def oracle_baseline(cfg, inp, loss, threads, budget_flops):
     return cpu
 
 
-def measure(cfg, inp, steps, warmup, profile_steps, torch, binding, with_update=False):
+def measure(cfg, inp, steps, warmup, profile_steps, torch, binding, with_update=False, graph=False):
     """Times `steps` training steps of one workload (inputs already on the device) and the stages of
-    `profile_steps` more with the library's HIP events.  Returns a dict of results."""
+    `profile_steps` more with the library's HIP events.  Returns a dict of results.  With `graph`, the step is
+    also recorded once into a HIP graph (torch's capture on a side stream) and `steps` replays are timed."""
     dev = {k: torch.from_numpy(v).cuda() for k, v in inp.items()}
     step = binding.TrainingStep(cfg, want_forecasts=True)
     if cfg.n_cat:
@@ -214,6 +215,23 @@ def measure(cfg, inp, steps, warmup, profile_steps, torch, binding, with_update=
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     loss = float(step.loss.item())
+    graph_ms = None
+    if graph and not with_update:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            one_step()
+        for _ in range(warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = round(1e3 * (time.perf_counter() - t0) / steps, 4)
+        assert abs(float(step.loss.item()) - loss) <= 1e-6 * abs(loss), "the replayed step gives another loss"
+        del g
     # per-stage durations: HIP events recorded by the library on the launch stream
     binding.esrnn_profile_enable(step.handle, True)
     for _ in range(max(1, profile_steps)):
@@ -228,6 +246,7 @@ def measure(cfg, inp, steps, warmup, profile_steps, torch, binding, with_update=
     del step, dev
     per_step = elapsed / steps
     return {"ms_per_step": round(1e3 * per_step, 4), "value": round(cfg.B * cfg.T / per_step, 1),
+            "ms_per_step_graph_replay": graph_ms,
             "window_steps_per_s": round(cfg.B * cfg.P / per_step, 1), "loss": loss, "stages": report,
             "sum_stage_ms": round(sum(stage_ms.values()), 4), "roofline": roofline_of(cfg, dominant, report[dominant])}
 
@@ -353,6 +372,9 @@ def main():
     ap.add_argument("--with-update", action="store_true",
                     help="add the clipped Adam update (esrnn_adam_update) to every step: the training loop rather "
                          "than the headline forward+backward step")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the step once into a HIP graph and time its replays (ms_per_step_graph_replay); "
+                         "the headline value stays the eager one")
     ap.add_argument("--predict", action="store_true",
                     help="time esrnn_predict (out-of-sample forecasts of every series, lengths T - H) instead of "
                          "the training step; one JSON line, not the headline metric")
@@ -449,7 +471,8 @@ def main():
                           "mean_forecast": float(out.mean().item())}))
         return
 
-    m = measure(cfg, inp, args.steps, args.warmup, args.profile_steps, torch, binding, with_update=args.with_update)
+    m = measure(cfg, inp, args.steps, args.warmup, args.profile_steps, torch, binding, with_update=args.with_update,
+                graph=args.graph)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = oracle_baseline(cfg, inp, m["loss"], args.cpu_threads, 1.2e11)
@@ -496,6 +519,8 @@ def main():
         "stages": m["stages"],
         "sum_stage_ms": m["sum_stage_ms"],
     }
+    if m["ms_per_step_graph_replay"] is not None:
+        out["ms_per_step_graph_replay"] = m["ms_per_step_graph_replay"]
     if others is not None:
         out["workloads"] = others
     print(json.dumps(out))
