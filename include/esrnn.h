@@ -110,6 +110,11 @@ esrnn_status esrnn_set_forward_only(esrnn_handle *h, int32_t on);
 
 /* Sizes the caller needs to allocate buffers. */
 esrnn_status esrnn_workspace_bytes(const esrnn_handle *h, size_t *bytes);
+/* The calls below take the workspace as a bare pointer and cannot see its size.  A caller can have both of its
+ * properties checked here, on the host, once: ESRNN_OK if `workspace` is 256-byte aligned and `bytes` is at least
+ * esrnn_workspace_bytes (with es_window_only != 0: at least esrnn_es_window_workspace_bytes, the prefix that the
+ * esrnn_es_window_* calls use), ESRNN_ERR_WORKSPACE otherwise.  The pointer is not dereferenced. */
+esrnn_status esrnn_check_workspace(const esrnn_handle *h, const void *workspace, size_t bytes, int32_t es_window_only);
 esrnn_status esrnn_es_param_rows(const esrnn_handle *h, int32_t *K);   /* K = 1 + n_seas + m1 + m2 (Section 3.3) */
 esrnn_status esrnn_weight_count(const esrnn_handle *h, size_t *n);     /* length of the flat weight vector */
 const char *esrnn_status_string(esrnn_status s);

@@ -70,6 +70,8 @@ def load_library():
     lib.esrnn_create.argtypes = [C.POINTER(EsrnnConfig), C.POINTER(vp)]
     lib.esrnn_destroy.argtypes = [vp]
     lib.esrnn_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
+    lib.esrnn_check_workspace.argtypes = [vp, vp, C.c_size_t, C.c_int32]
+    lib.esrnn_check_workspace.restype = C.c_int
     lib.esrnn_es_param_rows.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.esrnn_weight_count.argtypes = [vp, C.POINTER(C.c_size_t)]
     lib.esrnn_status_string.argtypes = [C.c_int]
@@ -160,6 +162,14 @@ def esrnn_workspace_bytes(handle) -> int:
     if st != ESRNN_OK:
         raise EsrnnError(st, "esrnn_workspace_bytes")
     return int(n.value)
+
+
+def esrnn_check_workspace(handle, workspace, es_window_only: bool = False) -> None:
+    """Raises EsrnnError unless the tensor is large enough and aligned for this handle (host-side check)."""
+    st = load_library().esrnn_check_workspace(handle, C.c_void_p(workspace.data_ptr()),
+                                              workspace.numel() * workspace.element_size(), 1 if es_window_only else 0)
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_check_workspace")
 
 
 def esrnn_es_param_rows(handle) -> int:

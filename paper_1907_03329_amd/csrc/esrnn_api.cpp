@@ -134,6 +134,14 @@ esrnn_status esrnn_workspace_bytes(const esrnn_handle *h, size_t *bytes)
     return ESRNN_OK;
 }
 
+esrnn_status esrnn_check_workspace(const esrnn_handle *h, const void *workspace, size_t bytes, int32_t es_window_only)
+{
+    if (!h || !workspace) return ESRNN_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return ESRNN_ERR_WORKSPACE;
+    const size_t need = (es_window_only ? h->plan.es_window_floats : h->plan.total_floats) * sizeof(float);
+    return bytes >= need ? ESRNN_OK : ESRNN_ERR_WORKSPACE;
+}
+
 esrnn_status esrnn_es_param_rows(const esrnn_handle *h, int32_t *K)
 {
     if (!h || !K) return ESRNN_ERR_NULL;

@@ -103,6 +103,19 @@ def test_null_and_order_errors_need_no_device(lib):
     n = C.c_size_t()
     assert lib.esrnn_workspace_bytes(h, None) == 1
     assert lib.esrnn_workspace_bytes(None, C.byref(n)) == 1
+    # size and alignment of a workspace, checked on the host (the pointer is never dereferenced)
+    assert lib.esrnn_workspace_bytes(h, C.byref(n)) == 0
+    full = n.value
+    assert lib.esrnn_es_window_workspace_bytes(h, C.byref(n)) == 0
+    prefix = n.value
+    assert 0 < prefix < full
+    assert lib.esrnn_check_workspace(h, C.c_void_p(4096), full, 0) == 0
+    assert lib.esrnn_check_workspace(h, C.c_void_p(4096), full - 1, 0) == 3
+    assert lib.esrnn_check_workspace(h, C.c_void_p(4096 + 64), full, 0) == 3
+    assert lib.esrnn_check_workspace(h, C.c_void_p(4096), prefix, 1) == 0
+    assert lib.esrnn_check_workspace(h, C.c_void_p(4096), prefix, 0) == 3
+    assert lib.esrnn_check_workspace(h, None, full, 0) == 1
+    assert lib.esrnn_check_workspace(None, C.c_void_p(4096), full, 0) == 1
     # null array arguments are refused before anything is launched
     assert lib.esrnn_forward(h, None, None, None, None, None, None, None, None) == 1
     assert lib.esrnn_backward(h, None, None, None, None, None, None, None, None) == 1
