@@ -27,34 +27,34 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 256 MiB copy probe
 # (FETCH x 2.0, WRITE x 1.0): profiles/hbm_traffic_<workload>_B<batch>.txt.  Valid for that workload and batch only.
 MEASURED_TRAFFIC_BYTES = {
-    ("tiny_quarterly", 16): {
-        "es_forward": 1.1e+05, "window_forward": 1.5e+05, "lstm_forward_l0": 1.06e+06, "lstm_forward_l1": 1.24e+06,
-        "lstm_forward_l2": 1.24e+06, "lstm_forward_l3": 1.24e+06, "head_forward_backward": 1.57e+06, "forecasts": 1.4e+05,
+    ('tiny_quarterly', 16): {
+        "es_forward": 1.1e+05, "window_forward": 1.5e+05, "lstm_forward_l0": 1.07e+06, "lstm_forward_l1": 1.23e+06,
+        "lstm_forward_l2": 1.23e+06, "lstm_forward_l3": 1.23e+06, "head_forward_backward": 1.57e+06, "forecasts": 1.4e+05,
         "lstm_backward_l3": 2.55e+06, "lstm_backward_l2": 2.55e+06, "lstm_backward_l1": 2.55e+06, "lstm_backward_l0": 1.33e+06,
         "window_backward": 1.3e+05, "es_backward": 9e+04,
     },
-    ("quarterly", 4096): {
+    ('quarterly', 4096): {
         "es_forward": 6.3e+06, "window_forward": 1.421e+07, "lstm_forward_l0": 2.442e+08, "lstm_forward_l1": 3.077e+08,
         "lstm_forward_l2": 3.077e+08, "lstm_forward_l3": 3.077e+08, "head_forward_backward": 1.171e+08, "forecasts": 1.818e+07,
         "lstm_backward_l3": 3.973e+08, "lstm_backward_l2": 3.973e+08, "lstm_backward_l1": 3.973e+08, "lstm_backward_l0": 2.956e+08,
         "window_backward": 1.56e+07, "es_backward": 6.15e+06,
     },
-    ("monthly", 4096): {
+    ('monthly', 4096): {
         "es_forward": 2.019e+07, "window_forward": 1.18e+08, "lstm_forward_l0": 1.121e+09, "lstm_forward_l1": 1.386e+09,
         "lstm_forward_l2": 1.386e+09, "lstm_forward_l3": 1.386e+09, "head_forward_backward": 5.931e+08, "forecasts": 1.317e+08,
         "lstm_backward_l3": 1.722e+09, "lstm_backward_l2": 1.722e+09, "lstm_backward_l1": 1.722e+09, "lstm_backward_l0": 1.355e+09,
         "window_backward": 2.071e+08, "es_backward": 2.005e+07,
     },
-    ("yearly", 8192): {
-        "es_forward": 5.49e+06, "window_forward": 1.751e+07, "lstm_forward_l0": 1.903e+08, "lstm_forward_l1": 2.341e+08,
-        "lstm_forward_l2": 2.341e+08, "lstm_forward_l3": 2.341e+08, "head_forward_backward": 9.038e+07, "forecasts": 1.245e+07,
+    ('yearly', 8192): {
+        "es_forward": 5.49e+06, "window_forward": 1.751e+07, "lstm_forward_l0": 1.903e+08, "lstm_forward_l1": 2.34e+08,
+        "lstm_forward_l2": 2.34e+08, "lstm_forward_l3": 2.34e+08, "head_forward_backward": 9.038e+07, "forecasts": 1.245e+07,
         "lstm_backward_l3": 2.978e+08, "lstm_backward_l2": 2.978e+08, "lstm_backward_l1": 2.978e+08, "lstm_backward_l0": 2.402e+08,
         "window_backward": 1.543e+07, "es_backward": 4.05e+06,
     },
-    ("hourly", 512): {
-        "es_forward": 9.58e+06, "window_forward": 9.854e+07, "lstm_forward_l0": 4.984e+08, "lstm_forward_l1": 5.34e+08,
+    ('hourly', 512): {
+        "es_forward": 9.58e+06, "window_forward": 9.854e+07, "lstm_forward_l0": 4.23e+08, "lstm_forward_l1": 4.487e+08,
         "lstm_forward_l2": 4.259e+08, "lstm_forward_l3": 4.259e+08, "head_forward_backward": 3.176e+08, "forecasts": 1.318e+08,
-        "lstm_backward_l3": 4.979e+08, "lstm_backward_l2": 4.979e+08, "lstm_backward_l1": 5.615e+08, "lstm_backward_l0": 4.417e+08,
+        "lstm_backward_l3": 4.979e+08, "lstm_backward_l2": 4.979e+08, "lstm_backward_l1": 5.606e+08, "lstm_backward_l0": 4.417e+08,
         "window_backward": 1.949e+08, "es_backward": 9.44e+06,
     },
 }
