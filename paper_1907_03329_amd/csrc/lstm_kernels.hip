@@ -43,17 +43,27 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
 {
     constexpr int KT = KXT + HT;
     constexpr int MTW = (HT + kLstmWaves - 1) / kLstmWaves;   // unit tiles per wave
+    // Waves 0 .. NX-1 own one unit tile more than the others.  Where that is at most two waves, wave s + 2
+    // takes over the input part of the last tile of wave s (bias included) and hands the accumulators over
+    // through LDS one position ahead: the input part does not depend on the recurrence, and the matrix work
+    // per position becomes (nearly) the same on every wave.
+    constexpr int NX = HT - kLstmWaves * (MTW - 1);
+    constexpr bool kHelp = kLstmWaves == 4 && KXT >= 2 && MTW >= 2 && NX <= 2;
     __shared__ float hbuf[2][HT * 64];
+    __shared__ f32x4 xfer[2][kHelp ? 2 : 1][64];
 
     const int lane = threadIdx.x & 63, bt = blockIdx.x;
     const int s = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
     const int Pt = a.pmax[bt];      // positions past the tile's longest series are never computed (nor read later)
+    const bool last_tile = s < NX;                              // this wave's last tile exists
+    const bool helper = kHelp && s >= 2 && s - 2 < NX;          // its last slot holds the input part of wave s-2's last tile
+    const bool last_x = kHelp ? helper : true;                  // input part of the last slot computed here
 
     float wreg[MTW][KT];
     f32x4 bias[MTW];
 #pragma unroll
     for (int j = 0; j < MTW; ++j) {
-        const int mt = s + kLstmWaves * j;
+        const int mt = (helper && j == MTW - 1 ? s - 2 : s) + kLstmWaves * j;
         const bool valid = mt < HT;
 #pragma unroll
         for (int ks = 0; ks < KT; ++ks) wreg[j][ks] = valid ? a.wpack[((size_t)mt * KT + ks) * 64 + lane] : 0.0f;
@@ -83,12 +93,22 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
 #pragma unroll
         for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + ((size_t)r * a.NB + bt) * xtile + ks * 64)[lane];
         f32x4 acc[MTW];
+        // input part (with the bias) of one position; a helper's share first, so that it is complete when it
+        // goes to LDS after the rest
+        auto input_part = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < MTW; ++j) acc[j] = bias[j];
+            for (int j = 0; j < MTW; ++j) acc[j] = bias[j];
+            if (last_x) {
 #pragma unroll
-        for (int ks = 0; ks < KXT; ++ks)
+                for (int ks = 0; ks < KXT; ++ks) acc[MTW - 1] = mfma16(wreg[MTW - 1][ks], bx[ks], acc[MTW - 1]);
+            }
 #pragma unroll
-            for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
+            for (int ks = 0; ks < KXT; ++ks)
+#pragma unroll
+                for (int j = 0; j < MTW - 1; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
+            if (helper) xfer[buf][kHelp ? s - 2 : 0][lane] = acc[MTW - 1];
+        };
+        input_part(0);
         {
             const size_t nb = ((size_t)min(r + a.d, Pt - 1) * a.NB + bt) * xtile;
 #pragma unroll
@@ -116,6 +136,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
             float bh[HT];
 #pragma unroll
             for (int ks = 0; ks < HT; ++ks) bh[ks] = hb[ks * 64 + lane];
+            if (kHelp && last_tile) acc[MTW - 1] = xfer[it & 1][kHelp ? s : 0][lane];
             float *hn_buf = hbuf[(it + 1) & 1];
             // Tile by tile, one tile ahead on the matrix pipe: the MFMAs of tile j+1 are issued before the
             // activations of tile j, whose accumulator is complete by then (no drain of the pipe per tile).
@@ -141,7 +162,6 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                 (a.hid + tile)[lane] = hn;
                 if (a.out) (a.out + tile)[lane] = res[j] + hn;
             };
-            const bool last_tile = s + kLstmWaves * (MTW - 1) < HT;   // this wave's last tile exists
             // (with a one-tile input, KXT = 1, the plain order measured faster and is kept)
             constexpr bool kAhead = KXT >= 2;
             if (kAhead) tile_mfma(0);
@@ -158,12 +178,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
             // recurrence, so it runs on the matrix pipe while the waves meet at
             // the barrier
             if (p + a.d < Pt) {
-#pragma unroll
-                for (int j = 0; j < MTW; ++j) acc[j] = bias[j];
-#pragma unroll
-                for (int ks = 0; ks < KXT; ++ks)
-#pragma unroll
-                    for (int j = 0; j < MTW; ++j) acc[j] = mfma16(wreg[j][ks], bx[ks], acc[j]);
+                input_part((it + 1) & 1);
                 const size_t nb = ((size_t)min(p + 2 * a.d, Pt - 1) * a.NB + bt) * xtile;
 #pragma unroll
                 for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + nb + ks * 64)[lane];
@@ -239,10 +254,15 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
     constexpr int XH_ROWS = (16 * MB > 16 * XH_PER_THREAD) ? 16 * MB : 16 * XH_PER_THREAD;
 
-    __shared__ float da_lds[DA_ROWS * kLdsPad];      // [mt][4*gate + unit][series]
-    __shared__ float xh_lds[XH_ROWS * kLdsPad];      // [row of x ; h][series]; rows past 4*KT are scratch
-    __shared__ float part_lds[W][MB * 4][64];        // partial d[x ; h] of every wave
-    static_assert((DA_ROWS * kLdsPad + XH_ROWS * kLdsPad + W * MB * 4 * 64) * 4 <= 128 * 1024, "LDS budget of the reverse kernel");
+    // With the larger hidden sizes there are two copies of each, used by alternate positions: a wave that is
+    // done reading position p goes on to write position p - d without waiting for the others (one barrier per
+    // position; measured 2 % faster at HT = 13, no faster at HT = 10, slower at HT = 8).
+    constexpr int NBUF = HT >= 13 ? 2 : 1;
+    __shared__ float da_lds[NBUF][DA_ROWS * kLdsPad];   // [mt][4*gate + unit][series]
+    __shared__ float xh_lds[NBUF][XH_ROWS * kLdsPad];   // [row of x ; h][series]; rows past 4*KT are scratch
+    __shared__ float part_lds[NBUF][W][MB * 4][64];     // partial d[x ; h] of every wave
+    static_assert(NBUF * (DA_ROWS * kLdsPad + XH_ROWS * kLdsPad + W * MB * 4 * 64) * 4 <= (HT <= 10 ? 80 : 160) * 1024,
+                  "LDS budget of the reverse kernel");
 
     const int lane = threadIdx.x & 63, bt = blockIdx.x;
     const int s = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
@@ -273,8 +293,8 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 #pragma unroll
         for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    for (int i = threadIdx.x; i < XH_ROWS * kLdsPad; i += NT) xh_lds[i] = 0.0f;
-    for (int i = threadIdx.x; i < DA_ROWS * kLdsPad; i += NT) da_lds[i] = 0.0f;
+    for (int i = threadIdx.x; i < NBUF * XH_ROWS * kLdsPad; i += NT) (&xh_lds[0][0])[i] = 0.0f;
+    for (int i = threadIdx.x; i < NBUF * DA_ROWS * kLdsPad; i += NT) (&da_lds[0][0])[i] = 0.0f;
 
     const size_t xtile = (size_t)KXT * 64, htile = (size_t)HT * 64;
 
@@ -321,7 +341,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     float dcreg[MTW], dhreg[MTW];
     float da[MTW][4];
     // ---- step A, tile j of the fetched position: gate gradients to registers and LDS
-    auto step_a_tile = [&](int j, bool has_prev, int p_cur) {
+    auto step_a_tile = [&](int j, bool has_prev, int p_cur, int buf) {
         const float4 gt = pf_gt[j];
         const float dh = pf_g[j] + g2_scale * pf_g2[j] + dhreg[j];
         const float tc = tanh_f(pf_c[j]);
@@ -333,22 +353,22 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
         da[j][2] = dc * gt.x * (1.0f - gt.z * gt.z);
         da[j][3] = dh * tc * gt.w * (1.0f - gt.w);
         dcreg[j] = dc * gt.y;
-        float *dst = da_lds + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
+        float *dst = da_lds[buf] + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             dst[r * 4 * kLdsPad] = da[j][r];
             dbacc[j][r] += da[j][r];
         }
     };
-    auto store_xh = [&](bool has_prev) {
+    auto store_xh = [&](bool has_prev, int buf) {
 #pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
             const int e = threadIdx.x + i * NT;
-            xh_lds[(e >> 4) * kLdsPad + (e & 15)] = (e < KXT * 64 || has_prev) ? pf_xh[i] : 0.0f;
+            xh_lds[buf][(e >> 4) * kLdsPad + (e & 15)] = (e < KXT * 64 || has_prev) ? pf_xh[i] : 0.0f;
         }
     };
     // ---- step B: partial W^T da over this wave's k-steps, into LDS
-    auto step_b = [&]() {
+    auto step_b = [&](int buf) {
         f32x4 acc[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -368,33 +388,34 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) part_lds[s][mb * 4 + r][lane] = acc[mb][r];
+            for (int r = 0; r < 4; ++r) part_lds[buf][s][mb * 4 + r][lane] = acc[mb][r];
     };
     // ---- end of position p: sum the partials this wave needs (recurrent dh of its
     // units) or stores (input gradient), and pull the operands of step C into registers
     float xb[MB][4], ar[MTW][4], dxv[QXW];
-    auto finish = [&](int p) {
-        lds_barrier();              // partials, da, [x ; h] of position p complete
+    auto finish = [&](int buf) {
+        lds_barrier();              // partials, da, [x ; h] of the position complete
+        const float (*part)[MB * 4][64] = part_lds[buf];
 #pragma unroll
         for (int j = 0; j < MTW; ++j) {
             const int q = min(KXT + s + W * j, KT - 1);   // row of part_lds = unit tile of [x ; h]
-            dhreg[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
+            dhreg[j] = (part[0][q][lane] + part[1][q][lane]) + (part[2][q][lane] + part[3][q][lane]);
         }
 #pragma unroll
         for (int j = 0; j < QXW; ++j) {
             const int q = min(s + W * j, KXT - 1);
-            dxv[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
+            dxv[j] = (part[0][q][lane] + part[1][q][lane]) + (part[2][q][lane] + part[3][q][lane]);
         }
 #pragma unroll
         for (int nbk = 0; nbk < MB; ++nbk)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) xb[nbk][ks] = xh_lds[(nbk * 16 + n) * kLdsPad + 4 * ks + g];
+            for (int ks = 0; ks < 4; ++ks) xb[nbk][ks] = xh_lds[buf][(nbk * 16 + n) * kLdsPad + 4 * ks + g];
 #pragma unroll
         for (int j = 0; j < MTW; ++j)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
-                ar[j][ks] = da_lds[(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
-        lds_barrier();              // everything of position p has been read
+                ar[j][ks] = da_lds[buf][(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
+        if constexpr (NBUF == 1) lds_barrier();   // everything of the position has been read
     };
     // Memory operations complete in order, and the compiler's wait for the operands requested one
     // position ahead counts the stores issued since with the smallest number any wave issues.  When
@@ -422,31 +443,33 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 #pragma unroll
         for (int j = 0; j < MTW; ++j) { dcreg[j] = 0.0f; dhreg[j] = 0.0f; }
         __syncthreads();            // LDS free (previous chain / initial clearing)
+        int buf = 0;                // copy that holds the position to finish next
         fetch(p_last, true);
-        store_xh(p_last >= a.d);
+        store_xh(p_last >= a.d, buf);
 #pragma unroll
-        for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d, p_last);
+        for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d, p_last, buf);
         fetch(max(p_last - a.d, r0), false);
-        step_b();
+        step_b(buf);
 
         for (int p = p_last; p >= a.d; p -= a.d) {
-            finish(p);
+            finish(buf);
+            buf ^= NBUF - 1;        // position p - d goes to the other copy, where there is one
             if (!kDxLate) store_dx(p);
             // gate gradients of position p - d (elementwise) interleaved with the dW MFMAs of p
             const bool has_prev = p >= 2 * a.d;
-            store_xh(has_prev);
+            store_xh(has_prev, buf);
 #pragma unroll
             for (int j = 0; j < MTW - 1; ++j) {
-                step_a_tile(j, has_prev, p - a.d);
+                step_a_tile(j, has_prev, p - a.d, buf);
                 dw_row(j);
             }
-            step_a_tile(MTW - 1, has_prev, p - a.d);
+            step_a_tile(MTW - 1, has_prev, p - a.d, buf);
             if (kDxLate) store_dx(p);
             fetch(max(p - 2 * a.d, r0), false);
             if (last_row_valid) dw_row(MTW - 1);
-            step_b();
+            step_b(buf);
         }
-        finish(r0);
+        finish(buf);
         store_dx(r0);
 #pragma unroll
         for (int j = 0; j < MTW - 1; ++j) dw_row(j);
