@@ -15,6 +15,7 @@ namespace esrnn {
 constexpr int kTileN = 16;       // series per tile (N of the 16x16x4 fp32 MFMA)
 constexpr int kMaxLayers = ESRNN_MAX_BLOCKS * ESRNN_MAX_LAYERS_PER_BLOCK;
 constexpr int kLstmWaves = 4;    // waves per workgroup in the LSTM kernels
+constexpr int kSplitBwdFromHT = 13;   // hidden unit tiles from which the 16-series reverse kernel puts the weight gradient on waves of its own
 constexpr int kReduceSplits = 16; // subsets of producers in the first stage of the weight-gradient reduction
 // Row stride of the LDS arrays [row][16 series] that are read transposed (lane = row n, column 4k + g).  With 18
 // the 32 lanes of a half wave (16 rows x 2 columns) hit 32 different banks: (18 n + g) mod 32 takes every value
@@ -42,6 +43,7 @@ struct LayerPlan {
     int n_gsrc;
     size_t gdst;         // TL(4*KXT) gradient with respect to the layer input
     int chains;          // workgroups per series tile (per 4 series if narrow); each walks the residue classes r, r+chains, ... (mod dil)
+    int chains_bwd;      // the same for the reverse kernel
     int narrow;          // 1: the layer runs on the 4-series kernels (lstm_narrow_kernels.hip): wpack_fwd is
                          // [4][4*(KXT+HT)][64], wpack_bwd [4][NG][4*HT][64], bias_pack unused, and the
                          // weight-gradient partials are indexed by 4*NB*chains workgroups
@@ -87,7 +89,8 @@ struct Plan {
     int head_dw_stride;
     size_t head_dw_reduced;
     int es_blocks;
-    int partial_groups(const LayerPlan &lp) const { return (lp.narrow ? 4 * NB : NB) * lp.chains; }   // producers of weight-gradient partials
+    int partial_groups(const LayerPlan &lp) const { return (lp.narrow ? 4 * NB : NB) * lp.chains_bwd; }   // producers of weight-gradient partials
+    int forward_groups(const LayerPlan &lp) const { return (lp.narrow ? 4 * NB : NB) * lp.chains; }        // workgroups of the forward kernel
     size_t es_window_floats;   // prefix of the workspace used by the smoothing and window stages alone
     size_t total_floats;
 };

@@ -254,15 +254,10 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
     constexpr int XH_ROWS = (16 * MB > 16 * XH_PER_THREAD) ? 16 * MB : 16 * XH_PER_THREAD;
 
-    // With the larger hidden sizes there are two copies of each, used by alternate positions: a wave that is
-    // done reading position p goes on to write position p - d without waiting for the others (one barrier per
-    // position; measured 2 % faster at HT = 13, no faster at HT = 10, slower at HT = 8).
-    constexpr int NBUF = HT >= 13 ? 2 : 1;
-    __shared__ float da_lds[NBUF][DA_ROWS * kLdsPad];   // [mt][4*gate + unit][series]
-    __shared__ float xh_lds[NBUF][XH_ROWS * kLdsPad];   // [row of x ; h][series]; rows past 4*KT are scratch
-    __shared__ float part_lds[NBUF][W][MB * 4][64];     // partial d[x ; h] of every wave
-    static_assert(NBUF * (DA_ROWS * kLdsPad + XH_ROWS * kLdsPad + W * MB * 4 * 64) * 4 <= (HT <= 10 ? 80 : 160) * 1024,
-                  "LDS budget of the reverse kernel");
+    __shared__ float da_lds[DA_ROWS * kLdsPad];      // [mt][4*gate + unit][series]
+    __shared__ float xh_lds[XH_ROWS * kLdsPad];      // [row of x ; h][series]; rows past 4*KT are scratch
+    __shared__ float part_lds[W][MB * 4][64];        // partial d[x ; h] of every wave
+    static_assert((DA_ROWS * kLdsPad + XH_ROWS * kLdsPad + W * MB * 4 * 64) * 4 <= 128 * 1024, "LDS budget of the reverse kernel");
 
     const int lane = threadIdx.x & 63, bt = blockIdx.x;
     const int s = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
@@ -293,8 +288,8 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 #pragma unroll
         for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    for (int i = threadIdx.x; i < NBUF * XH_ROWS * kLdsPad; i += NT) (&xh_lds[0][0])[i] = 0.0f;
-    for (int i = threadIdx.x; i < NBUF * DA_ROWS * kLdsPad; i += NT) (&da_lds[0][0])[i] = 0.0f;
+    for (int i = threadIdx.x; i < XH_ROWS * kLdsPad; i += NT) xh_lds[i] = 0.0f;
+    for (int i = threadIdx.x; i < DA_ROWS * kLdsPad; i += NT) da_lds[i] = 0.0f;
 
     const size_t xtile = (size_t)KXT * 64, htile = (size_t)HT * 64;
 
@@ -341,7 +336,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     float dcreg[MTW], dhreg[MTW];
     float da[MTW][4];
     // ---- step A, tile j of the fetched position: gate gradients to registers and LDS
-    auto step_a_tile = [&](int j, bool has_prev, int p_cur, int buf) {
+    auto step_a_tile = [&](int j, bool has_prev, int p_cur) {
         const float4 gt = pf_gt[j];
         const float dh = pf_g[j] + g2_scale * pf_g2[j] + dhreg[j];
         const float tc = tanh_f(pf_c[j]);
@@ -353,22 +348,22 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
         da[j][2] = dc * gt.x * (1.0f - gt.z * gt.z);
         da[j][3] = dh * tc * gt.w * (1.0f - gt.w);
         dcreg[j] = dc * gt.y;
-        float *dst = da_lds[buf] + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
+        float *dst = da_lds + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             dst[r * 4 * kLdsPad] = da[j][r];
             dbacc[j][r] += da[j][r];
         }
     };
-    auto store_xh = [&](bool has_prev, int buf) {
+    auto store_xh = [&](bool has_prev) {
 #pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
             const int e = threadIdx.x + i * NT;
-            xh_lds[buf][(e >> 4) * kLdsPad + (e & 15)] = (e < KXT * 64 || has_prev) ? pf_xh[i] : 0.0f;
+            xh_lds[(e >> 4) * kLdsPad + (e & 15)] = (e < KXT * 64 || has_prev) ? pf_xh[i] : 0.0f;
         }
     };
     // ---- step B: partial W^T da over this wave's k-steps, into LDS
-    auto step_b = [&](int buf) {
+    auto step_b = [&]() {
         f32x4 acc[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -388,34 +383,33 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) part_lds[buf][s][mb * 4 + r][lane] = acc[mb][r];
+            for (int r = 0; r < 4; ++r) part_lds[s][mb * 4 + r][lane] = acc[mb][r];
     };
     // ---- end of position p: sum the partials this wave needs (recurrent dh of its
     // units) or stores (input gradient), and pull the operands of step C into registers
     float xb[MB][4], ar[MTW][4], dxv[QXW];
-    auto finish = [&](int buf) {
-        lds_barrier();              // partials, da, [x ; h] of the position complete
-        const float (*part)[MB * 4][64] = part_lds[buf];
+    auto finish = [&](int p) {
+        lds_barrier();              // partials, da, [x ; h] of position p complete
 #pragma unroll
         for (int j = 0; j < MTW; ++j) {
             const int q = min(KXT + s + W * j, KT - 1);   // row of part_lds = unit tile of [x ; h]
-            dhreg[j] = (part[0][q][lane] + part[1][q][lane]) + (part[2][q][lane] + part[3][q][lane]);
+            dhreg[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
         }
 #pragma unroll
         for (int j = 0; j < QXW; ++j) {
             const int q = min(s + W * j, KXT - 1);
-            dxv[j] = (part[0][q][lane] + part[1][q][lane]) + (part[2][q][lane] + part[3][q][lane]);
+            dxv[j] = (part_lds[0][q][lane] + part_lds[1][q][lane]) + (part_lds[2][q][lane] + part_lds[3][q][lane]);
         }
 #pragma unroll
         for (int nbk = 0; nbk < MB; ++nbk)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) xb[nbk][ks] = xh_lds[buf][(nbk * 16 + n) * kLdsPad + 4 * ks + g];
+            for (int ks = 0; ks < 4; ++ks) xb[nbk][ks] = xh_lds[(nbk * 16 + n) * kLdsPad + 4 * ks + g];
 #pragma unroll
         for (int j = 0; j < MTW; ++j)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
-                ar[j][ks] = da_lds[buf][(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
-        if constexpr (NBUF == 1) lds_barrier();   // everything of the position has been read
+                ar[j][ks] = da_lds[(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
+        lds_barrier();              // everything of position p has been read
     };
     // Memory operations complete in order, and the compiler's wait for the operands requested one
     // position ahead counts the stores issued since with the smallest number any wave issues.  When
@@ -443,33 +437,31 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 #pragma unroll
         for (int j = 0; j < MTW; ++j) { dcreg[j] = 0.0f; dhreg[j] = 0.0f; }
         __syncthreads();            // LDS free (previous chain / initial clearing)
-        int buf = 0;                // copy that holds the position to finish next
         fetch(p_last, true);
-        store_xh(p_last >= a.d, buf);
+        store_xh(p_last >= a.d);
 #pragma unroll
-        for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d, p_last, buf);
+        for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d, p_last);
         fetch(max(p_last - a.d, r0), false);
-        step_b(buf);
+        step_b();
 
         for (int p = p_last; p >= a.d; p -= a.d) {
-            finish(buf);
-            buf ^= NBUF - 1;        // position p - d goes to the other copy, where there is one
+            finish(p);
             if (!kDxLate) store_dx(p);
             // gate gradients of position p - d (elementwise) interleaved with the dW MFMAs of p
             const bool has_prev = p >= 2 * a.d;
-            store_xh(has_prev, buf);
+            store_xh(has_prev);
 #pragma unroll
             for (int j = 0; j < MTW - 1; ++j) {
-                step_a_tile(j, has_prev, p - a.d, buf);
+                step_a_tile(j, has_prev, p - a.d);
                 dw_row(j);
             }
-            step_a_tile(MTW - 1, has_prev, p - a.d, buf);
+            step_a_tile(MTW - 1, has_prev, p - a.d);
             if (kDxLate) store_dx(p);
             fetch(max(p - 2 * a.d, r0), false);
             if (last_row_valid) dw_row(MTW - 1);
-            step_b(buf);
+            step_b();
         }
-        finish(buf);
+        finish(r0);
         store_dx(r0);
 #pragma unroll
         for (int j = 0; j < MTW - 1; ++j) dw_row(j);
@@ -489,6 +481,265 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
                 for (int rr = 0; rr < 4; ++rr) dst[rr * 64] = dw[j][nbk][rr];
             }
         }
+    }
+#pragma unroll
+    for (int j = 0; j < MTW; ++j) {
+        const int mt = s + W * j;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const float tot = group16_sum(dbacc[j][rr]);
+            if (n == 0 && mt < HT) a.db_partial[(part * HT + mt) * 16 + g * 4 + rr] = tot;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Reverse pass with the weight gradient on waves of its own.  Steps A and B are
+// the recurrence: position p - d cannot start before the recurrent dh of p is
+// summed.  Step C only consumes what A leaves in LDS.  Here four "chain" waves
+// do A and B exactly as above, and four "dW" waves do C one position behind
+// them: after the barrier that completes position p they read da and [x ; h] of
+// p from one LDS copy while the chain waves fill the other copy with p - d.
+// The matrix pipe of a SIMD then has the dW wave's work whenever its chain wave
+// waits (barrier, LDS round trip, accumulator read-out), and the chain waves
+// carry half the MFMAs per position.  One workgroup of eight waves per compute
+// unit; one barrier per position, taken by all eight waves.
+// ---------------------------------------------------------------------------
+template <int HT, int KXT, bool CP>
+__global__ void __launch_bounds__(128 * kLstmWaves, 1) lstm_backward_split_kernel(LstmBwdArgs a)
+{
+    constexpr int W = kLstmWaves;
+    constexpr int KT = KXT + HT;
+    constexpr int MB = (KT + 3) / 4;                 // 16-row tiles of [x ; h]
+    constexpr int MTW = (HT + W - 1) / W;            // unit tiles per wave
+    constexpr int QXW = (KXT + W - 1) / W;           // input unit tiles finalised per wave
+    constexpr int NT = 64 * W;                       // threads of the chain waves
+    constexpr bool kDxLate = (KXT % W) != 0 && HT > 8;
+    constexpr int DA_ROWS = 16 * W * MTW;            // includes dummy rows for tiles past HT
+    constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
+    constexpr int XH_ROWS = (16 * MB > 16 * XH_PER_THREAD) ? 16 * MB : 16 * XH_PER_THREAD;
+
+    __shared__ float da_lds[2][DA_ROWS * kLdsPad];   // [mt][4*gate + unit][series]
+    __shared__ float xh_lds[2][XH_ROWS * kLdsPad];   // [row of x ; h][series]; rows past 4*KT are scratch
+    __shared__ float part_lds[2][W][MB * 4][64];     // partial d[x ; h] of every chain wave
+    static_assert(2 * (DA_ROWS * kLdsPad + XH_ROWS * kLdsPad + W * MB * 4 * 64) * 4 <= 160 * 1024,
+                  "LDS budget of the reverse kernel");
+
+    const int lane = threadIdx.x & 63, bt = blockIdx.x;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known to be uniform
+    const bool chain = wv < W;
+    const int s = wv & (W - 1);
+    const int Pt = a.pmax[bt];      // the chains of this tile stop at its longest series
+    const int g = lane >> 4, n = lane & 15;
+    for (int i = threadIdx.x; i < 2 * XH_ROWS * kLdsPad; i += 2 * NT) (&xh_lds[0][0])[i] = 0.0f;
+    for (int i = threadIdx.x; i < 2 * DA_ROWS * kLdsPad; i += 2 * NT) (&da_lds[0][0])[i] = 0.0f;
+    const size_t part = (size_t)bt * gridDim.y + blockIdx.y;
+
+    if (!chain) {
+        // ---- dW waves: rows (W-1-s) + W*j of the weight gradient, in accumulators for the whole launch
+        const bool last_row_valid = (W - 1 - s) + W * (MTW - 1) < HT;
+        f32x4 dw[MTW][MB];
+#pragma unroll
+        for (int j = 0; j < MTW; ++j)
+#pragma unroll
+            for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = f32x4{0.f, 0.f, 0.f, 0.f};
+        auto accumulate = [&](int buf) {
+            lds_barrier();          // da and [x ; h] of the position are complete in copy `buf`
+            float xb[MB][4], ar[MTW][4];
+#pragma unroll
+            for (int nbk = 0; nbk < MB; ++nbk)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) xb[nbk][ks] = xh_lds[buf][(nbk * 16 + n) * kLdsPad + 4 * ks + g];
+#pragma unroll
+            for (int j = 0; j < MTW; ++j)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    ar[j][ks] = da_lds[buf][(((W - 1 - s) + W * j) * 16 + n) * kLdsPad + 4 * ks + g];
+#pragma unroll
+            for (int j = 0; j < MTW; ++j)
+                if (j < MTW - 1 || last_row_valid) {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                        for (int nbk = 0; nbk < MB; ++nbk) dw[j][nbk] = mfma16(ar[j][ks], xb[nbk][ks], dw[j][nbk]);
+                }
+        };
+        for (int r0 = blockIdx.y; r0 < a.d && r0 < Pt; r0 += gridDim.y) {
+            const int p_last = r0 + ((Pt - 1 - r0) / a.d) * a.d;
+            __syncthreads();
+            int buf = 0;
+            for (int p = p_last; p >= a.d; p -= a.d) {
+                accumulate(buf);
+                buf ^= 1;
+            }
+            accumulate(buf);
+        }
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) {
+            const int row = (W - 1 - s) + W * j;
+            if (row < HT) {
+#pragma unroll
+                for (int nbk = 0; nbk < MB; ++nbk) {
+                    float *dst = a.dw_partial + (part * (HT * MB) + row * MB + nbk) * 256 + lane;
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) dst[rr * 64] = dw[j][nbk][rr];
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- chain waves: steps A and B
+    const bool last_own_valid = s + W * (MTW - 1) < HT;           // unit tile s + 4(MTW-1)
+    const bool last_qx_valid = s + W * (QXW - 1) < KXT;
+    // W^T operands of the k-steps this wave owns: k-step 4*mt + gate, mt = s + 4j
+    float wreg[MB][4 * MTW];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) {
+            const int mt = s + W * j;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float w = a.wpack[((size_t)mb * 4 * HT + 4 * min(mt, HT - 1) + r) * 64 + lane];
+                wreg[mb][4 * j + r] = mt < HT ? w : 0.0f;
+            }
+        }
+    f32x4 dbacc[MTW];
+#pragma unroll
+    for (int j = 0; j < MTW; ++j) dbacc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const size_t xtile = (size_t)KXT * 64, htile = (size_t)HT * 64;
+
+    // operands of one position, requested one position ahead (branch-free, see the kernel above)
+    float4 pf_gt[MTW];
+    float pf_c[MTW], pf_cp[MTW], pf_g[MTW], pf_g2[MTW], pf_xh[XH_PER_THREAD];
+    auto fetch = [&](int p, bool first) {
+        const size_t pb = (size_t)p * a.NB + bt;
+        const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) {
+            const int mt = min(s + W * j, HT - 1);
+            const size_t tile = (pb * HT + mt) * 64;
+            pf_gt[j] = (reinterpret_cast<const float4 *>(a.gates) + tile)[lane];
+            pf_c[j] = first ? (a.c + tile)[lane] : pf_cp[j];
+            pf_cp[j] = (a.c + (pbd * HT + mt) * 64)[lane];
+            pf_g[j] = (a.gsrc[0] + tile)[lane];
+            pf_g2[j] = (a.gsrc[1] + tile)[lane];
+        }
+#pragma unroll
+        for (int i = 0; i < XH_PER_THREAD; ++i) {
+            const int q = min(s + W * i, KT - 1);
+            const float *src = q < KXT ? a.xsrc + pb * xtile + q * 64 : a.hid + pbd * htile + (q - KXT) * 64;
+            pf_xh[i] = src[lane];
+        }
+    };
+    const float g2_scale = a.n_gsrc >= 2 ? 1.0f : 0.0f;
+    int n_valid = 0;
+    float pen = 0.0f;
+    if constexpr (CP) {
+        const int col = bt * kTileN + n;
+        const int len = col < a.B ? min(max(a.lengths[col], 0), a.T) : 0;
+        n_valid = len - a.I - a.H + 1;
+        pen = a.two_lambda_cs * a.sc->inv_n_cs;
+    }
+    float dcreg[MTW], dhreg[MTW];
+    float da[MTW][4];
+    auto step_a_tile = [&](int j, bool has_prev, int p_cur, int buf) {
+        const float4 gt = pf_gt[j];
+        const float dh = pf_g[j] + g2_scale * pf_g2[j] + dhreg[j];
+        const float tc = tanh_f(pf_c[j]);
+        float dc = dcreg[j] + dh * gt.w * (1.0f - tc * tc);
+        if constexpr (CP) dc += p_cur < n_valid ? pen * pf_c[j] : 0.0f;
+        const float cp = has_prev ? pf_cp[j] : 0.0f;
+        da[j][0] = dc * gt.z * gt.x * (1.0f - gt.x);
+        da[j][1] = dc * cp * gt.y * (1.0f - gt.y);
+        da[j][2] = dc * gt.x * (1.0f - gt.z * gt.z);
+        da[j][3] = dh * tc * gt.w * (1.0f - gt.w);
+        dcreg[j] = dc * gt.y;
+        float *dst = da_lds[buf] + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            dst[r * 4 * kLdsPad] = da[j][r];
+            dbacc[j][r] += da[j][r];
+        }
+    };
+    auto store_xh = [&](bool has_prev, int buf) {
+#pragma unroll
+        for (int i = 0; i < XH_PER_THREAD; ++i) {
+            const int e = threadIdx.x + i * NT;
+            xh_lds[buf][(e >> 4) * kLdsPad + (e & 15)] = (e < KXT * 64 || has_prev) ? pf_xh[i] : 0.0f;
+        }
+    };
+    auto step_b = [&](int buf) {
+        f32x4 acc[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < MTW - 1; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) acc[mb] = mfma16(wreg[mb][4 * j + r], da[j][r], acc[mb]);
+        if (last_own_valid) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    acc[mb] = mfma16(wreg[mb][4 * (MTW - 1) + r], da[MTW - 1][r], acc[mb]);
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part_lds[buf][s][mb * 4 + r][lane] = acc[mb][r];
+    };
+    float dxv[QXW];
+    auto finish = [&](int buf) {
+        lds_barrier();              // partials, da, [x ; h] of the position complete
+        const float (*pt)[MB * 4][64] = part_lds[buf];
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) {
+            const int q = min(KXT + s + W * j, KT - 1);   // row of part_lds = unit tile of [x ; h]
+            dhreg[j] = (pt[0][q][lane] + pt[1][q][lane]) + (pt[2][q][lane] + pt[3][q][lane]);
+        }
+#pragma unroll
+        for (int j = 0; j < QXW; ++j) {
+            const int q = min(s + W * j, KXT - 1);
+            dxv[j] = (pt[0][q][lane] + pt[1][q][lane]) + (pt[2][q][lane] + pt[3][q][lane]);
+        }
+    };
+    auto store_dx = [&](int p) {
+        const size_t pb = (size_t)p * a.NB + bt;
+#pragma unroll
+        for (int j = 0; j < QXW; ++j)
+            if (j < QXW - 1 || last_qx_valid) (a.gdst + pb * xtile + (s + W * j) * 64)[lane] = dxv[j];
+    };
+
+    for (int r0 = blockIdx.y; r0 < a.d && r0 < Pt; r0 += gridDim.y) {
+        const int p_last = r0 + ((Pt - 1 - r0) / a.d) * a.d;
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) { dcreg[j] = 0.0f; dhreg[j] = 0.0f; }
+        __syncthreads();            // LDS free (previous chain / initial clearing)
+        int buf = 0;
+        fetch(p_last, true);
+        store_xh(p_last >= a.d, buf);
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) step_a_tile(j, p_last >= a.d, p_last, buf);
+        fetch(max(p_last - a.d, r0), false);
+        step_b(buf);
+        for (int p = p_last; p >= a.d; p -= a.d) {
+            finish(buf);
+            buf ^= 1;               // position p - d goes to the other copy
+            if (!kDxLate) store_dx(p);
+            const bool has_prev = p >= 2 * a.d;
+            store_xh(has_prev, buf);
+#pragma unroll
+            for (int j = 0; j < MTW; ++j) step_a_tile(j, has_prev, p - a.d, buf);
+            if (kDxLate) store_dx(p);
+            fetch(max(p - 2 * a.d, r0), false);
+            step_b(buf);
+        }
+        finish(buf);
+        store_dx(r0);
     }
 #pragma unroll
     for (int j = 0; j < MTW; ++j) {
@@ -528,8 +779,13 @@ hipError_t run_fwd(const LstmFwdArgs &a, int chains, hipStream_t st)
 template <int HT, int KXT>
 hipError_t run_bwd(const LstmBwdArgs &a, int chains, hipStream_t st)
 {
-    if (a.sc) lstm_backward_kernel<HT, KXT, true><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
-    else lstm_backward_kernel<HT, KXT, false><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
+    if constexpr (HT >= kSplitBwdFromHT) {
+        if (a.sc) lstm_backward_split_kernel<HT, KXT, true><<<dim3(a.NB, chains), 128 * kLstmWaves, 0, st>>>(a);
+        else lstm_backward_split_kernel<HT, KXT, false><<<dim3(a.NB, chains), 128 * kLstmWaves, 0, st>>>(a);
+    } else {
+        if (a.sc) lstm_backward_kernel<HT, KXT, true><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
+        else lstm_backward_kernel<HT, KXT, false><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
+    }
     return hipGetLastError();
 }
 
@@ -583,7 +839,7 @@ hipError_t launch_lstm_backward(const Plan &pl, int layer, const int32_t *length
     a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
     a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
     a.pmax = reinterpret_cast<const int32_t *>(ws + pl.pmax);
-#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains, st);
+#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains_bwd, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

@@ -193,6 +193,9 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         // weight-gradient partials than the reduction can read cheaply
         const int max_chains = std::max(1, ceil_div(512, groups));
         lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
+        // the 16-series reverse kernel of the larger hidden sizes runs one workgroup of eight waves per compute unit
+        const bool split_bwd = !lp.narrow && pl.HT >= kSplitBwdFromHT;
+        lp.chains_bwd = split_bwd ? std::min(std::min(lp.dil, pl.P), std::max(1, ceil_div(256, groups))) : lp.chains;
         if (lp.narrow) {
             const int KT4 = 4 * KT, NG = ceil_div(KT4, 64);
             lp.wpack_fwd = ws.take((size_t)4 * KT4 * 64);
@@ -206,8 +209,8 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         lp.gates = ws.take(PN * tileH * 4);
         lp.c = ws.take(PN * tileH);
         lp.hid = ws.take(PN * tileH);
-        lp.dw_partial = ws.take((size_t)groups * lp.chains * pl.HT * MB * 256);
-        lp.db_partial = ws.take((size_t)groups * lp.chains * pl.HT * 16);
+        lp.dw_partial = ws.take((size_t)groups * lp.chains_bwd * pl.HT * MB * 256);
+        lp.db_partial = ws.take((size_t)groups * lp.chains_bwd * pl.HT * 16);
         lp.dw_reduced = ws.take((size_t)kReduceSplits * pl.HT * MB * 256);
         lp.db_reduced = ws.take((size_t)kReduceSplits * pl.HT * 16);
         pl.dx[l] = l > 0 ? ws.take(PN * tileH) : pl.gX;
@@ -220,7 +223,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
             LayerPlan &lp = pl.layer[l];
             if (!lp.first_in_block) continue;
             lp.cs_partial = pl.cs_partial + pl.n_cs_partial;
-            pl.n_cs_partial += pl.partial_groups(lp);
+            pl.n_cs_partial += pl.forward_groups(lp);
         }
     ws.take((size_t)pl.n_cs_partial);
     // block outputs: block 0's is the hidden state of its last layer
