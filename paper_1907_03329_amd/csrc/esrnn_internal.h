@@ -15,7 +15,8 @@ namespace esrnn {
 constexpr int kTileN = 16;       // series per tile (N of the 16x16x4 fp32 MFMA)
 constexpr int kMaxLayers = ESRNN_MAX_BLOCKS * ESRNN_MAX_LAYERS_PER_BLOCK;
 constexpr int kLstmWaves = 4;    // waves per workgroup in the LSTM kernels
-constexpr int kSplitBwdFromHT = 13;   // hidden unit tiles from which the 16-series reverse kernel puts the weight gradient on waves of its own
+constexpr int kSinkLines = 256;  // 256-byte lines of the store sink
+constexpr int kSplitBwdFromHT = 13;   // hidden unit tiles from which the 16-series reverse kernel always puts the weight gradient on waves of its own
 constexpr int kReduceSplits = 16; // subsets of producers in the first stage of the weight-gradient reduction
 // Row stride of the LDS arrays [row][16 series] that are read transposed (lane = row n, column 4k + g).  With 18
 // the 32 lanes of a half wave (16 rows x 2 columns) hit 32 different banks: (18 n + g) mod 32 takes every value
@@ -44,6 +45,7 @@ struct LayerPlan {
     size_t gdst;         // TL(4*KXT) gradient with respect to the layer input
     int chains;          // workgroups per series tile (per 4 series if narrow); each walks the residue classes r, r+chains, ... (mod dil)
     int chains_bwd;      // the same for the reverse kernel
+    int split_bwd;       // 1: 16-series reverse kernel with the weight gradient on waves of its own, one workgroup per compute unit
     int narrow;          // 1: the layer runs on the 4-series kernels (lstm_narrow_kernels.hip): wpack_fwd is
                          // [4][4*(KXT+HT)][64], wpack_bwd [4][NG][4*HT][64], bias_pack unused, and the
                          // weight-gradient partials are indexed by 4*NB*chains workgroups
@@ -71,7 +73,7 @@ struct Plan {
     size_t Wa_off, ba_off, Wo_off, bo_off, n_weights;
     // workspace map (offsets in floats)
     size_t scalars;      // float[16]: see Scalars
-    size_t sink;         // float[64]: where the lanes past the padded batch put their stores
+    size_t sink;         // float[kSinkLines][64]: target of stores whose value nothing reads (a workgroup uses line id % kSinkLines)
     size_t len_ext;      // int32[B]: lengths extended by the horizon (out-of-sample forecasts)
     size_t pmax;         // int32[NB]: window positions the series of a 16-series tile need (max over the tile), by setup
     size_t opt_partial;  // float[512]: sums of squares of the gradients, per workgroup (parameter update)

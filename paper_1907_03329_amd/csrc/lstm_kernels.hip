@@ -229,6 +229,7 @@ struct LstmBwdArgs {
     const float *gsrc[2]; // TL(HP): the gradient arriving at the hidden output is the sum of these
     int n_gsrc;           // 1 or 2; gsrc[1] repeats gsrc[0] when there is one
     float *gdst;          // TL(4*KXT)
+    float *sink;          // [kSinkLines][64] floats that nothing reads: target of the stores a wave has no input tile for
     float *dw_partial;    // [NB*chains][HT*MB][4][64]
     float *db_partial;    // [NB*chains][HT][4][4]
     int P, NB, d;
@@ -249,7 +250,6 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     constexpr int MTW = (HT + W - 1) / W;            // unit tiles per wave
     constexpr int QXW = (KXT + W - 1) / W;           // input unit tiles finalised per wave
     constexpr int NT = 64 * W;
-    constexpr bool kDxLate = (KXT % W) != 0 && HT > 8;   // measured: at HT = 8 the early placement is faster either way
     constexpr int DA_ROWS = 16 * W * MTW;            // includes dummy rows for tiles past HT
     constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
     constexpr int XH_ROWS = (16 * MB > 16 * XH_PER_THREAD) ? 16 * MB : 16 * XH_PER_THREAD;
@@ -266,6 +266,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     const bool last_own_valid = s + W * (MTW - 1) < HT;           // unit tile s + 4(MTW-1)
     const bool last_row_valid = (W - 1 - s) + W * (MTW - 1) < HT; // dW row (3-s) + 4(MTW-1)
     const bool last_qx_valid = s + W * (QXW - 1) < KXT;
+    float *sink_line = a.sink + ((bt + blockIdx.y * 61) % kSinkLines) * 64;
 
     // W^T operands of the k-steps this wave owns: k-step 4*mt + gate, mt = s + 4j
     float wreg[MB][4 * MTW];
@@ -300,20 +301,11 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     float pf_c[MTW], pf_cp[MTW], pf_g[MTW], pf_g2[MTW], pf_xh[XH_PER_THREAD];
     // `first`: the chain's first request.  Later ones follow a request for position p + d, whose predecessor
     // cell state c[p] is still in registers: it is not read from memory a second time.
-    auto fetch = [&](int p, bool first) {
+    // The requests of a position go out piece by piece, each as soon as the registers it fills are free:
+    // [x ; h] after it has gone to LDS, the operands of unit tile j after the elementwise step of tile j.
+    auto fetch_xh = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
         const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
-        // wave-uniform tile bases plus the lane index: scalar address arithmetic
-#pragma unroll
-        for (int j = 0; j < MTW; ++j) {
-            const int mt = min(s + W * j, HT - 1);
-            const size_t tile = (pb * HT + mt) * 64;
-            pf_gt[j] = (reinterpret_cast<const float4 *>(a.gates) + tile)[lane];
-            pf_c[j] = first ? (a.c + tile)[lane] : pf_cp[j];
-            pf_cp[j] = (a.c + (pbd * HT + mt) * 64)[lane];
-            pf_g[j] = (a.gsrc[0] + tile)[lane];
-            pf_g2[j] = (a.gsrc[1] + tile)[lane];    // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
-        }
 #pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
             // unit tile s + W*i of [x ; h]; tiles past the end alias the last one
@@ -321,6 +313,23 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
             const float *src = q < KXT ? a.xsrc + pb * xtile + q * 64 : a.hid + pbd * htile + (q - KXT) * 64;
             pf_xh[i] = src[lane];
         }
+    };
+    auto fetch_tile = [&](int j, int p, bool first) {
+        const size_t pb = (size_t)p * a.NB + bt;
+        const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
+        // wave-uniform tile bases plus the lane index: scalar address arithmetic
+        const int mt = min(s + W * j, HT - 1);
+        const size_t tile = (pb * HT + mt) * 64;
+        pf_gt[j] = (reinterpret_cast<const float4 *>(a.gates) + tile)[lane];
+        pf_c[j] = first ? (a.c + tile)[lane] : pf_cp[j];
+        pf_cp[j] = (a.c + (pbd * HT + mt) * 64)[lane];
+        pf_g[j] = (a.gsrc[0] + tile)[lane];
+        pf_g2[j] = (a.gsrc[1] + tile)[lane];    // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
+    };
+    auto fetch = [&](int p, bool first) {
+        fetch_xh(p);
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) fetch_tile(j, p, first);
     };
 
     const float g2_scale = a.n_gsrc >= 2 ? 1.0f : 0.0f;
@@ -412,17 +421,17 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
         lds_barrier();              // everything of position p has been read
     };
     // Memory operations complete in order, and the compiler's wait for the operands requested one
-    // position ahead counts the stores issued since with the smallest number any wave issues.  When
-    // the waves own different numbers of input tiles (KXT not a multiple of the wave count), a store
-    // placed between request and use would therefore have to complete before that use on the waves
-    // with one tile more; the input gradient then leaves after the elementwise work of the next
-    // position, ahead of the next requests (kDxLate).  With equal counts the wait is exact, and the
-    // stores go out at once, which frees their registers.
+    // position ahead counts the stores issued since with the smallest number any wave issues.  Every
+    // wave therefore issues the same number of stores: one without an input tile for its last store
+    // writes to a sink.  The stores go out right after the sums, behind the requests already in flight
+    // (which then do not wait for them) and a whole position ahead of the next wait.
     auto store_dx = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
 #pragma unroll
-        for (int j = 0; j < QXW; ++j)
-            if (j < QXW - 1 || last_qx_valid) (a.gdst + pb * xtile + (s + W * j) * 64)[lane] = dxv[j];
+        for (int j = 0; j < QXW; ++j) {
+            float *dst = (j < QXW - 1 || last_qx_valid) ? a.gdst + pb * xtile + (s + W * j) * 64 : sink_line;
+            dst[lane] = dxv[j];
+        }
     };
     auto dw_row = [&](int j) {
 #pragma unroll
@@ -446,18 +455,21 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
 
         for (int p = p_last; p >= a.d; p -= a.d) {
             finish(p);
-            if (!kDxLate) store_dx(p);
-            // gate gradients of position p - d (elementwise) interleaved with the dW MFMAs of p
+            store_dx(p);
+            // gate gradients of position p - d (elementwise) interleaved with the dW MFMAs of p and with
+            // the requests for position p - 2d
             const bool has_prev = p >= 2 * a.d;
+            const int p_next = max(p - 2 * a.d, r0);
             store_xh(has_prev);
+            fetch_xh(p_next);
 #pragma unroll
             for (int j = 0; j < MTW - 1; ++j) {
                 step_a_tile(j, has_prev, p - a.d);
+                fetch_tile(j, p_next, false);
                 dw_row(j);
             }
             step_a_tile(MTW - 1, has_prev, p - a.d);
-            if (kDxLate) store_dx(p);
-            fetch(max(p - 2 * a.d, r0), false);
+            fetch_tile(MTW - 1, p_next, false);
             if (last_row_valid) dw_row(MTW - 1);
             step_b();
         }
@@ -514,7 +526,6 @@ __global__ void __launch_bounds__(128 * kLstmWaves, 1) lstm_backward_split_kerne
     constexpr int MTW = (HT + W - 1) / W;            // unit tiles per wave
     constexpr int QXW = (KXT + W - 1) / W;           // input unit tiles finalised per wave
     constexpr int NT = 64 * W;                       // threads of the chain waves
-    constexpr bool kDxLate = (KXT % W) != 0 && HT > 8;
     constexpr int DA_ROWS = 16 * W * MTW;            // includes dummy rows for tiles past HT
     constexpr int XH_PER_THREAD = (KT * 64 + NT - 1) / NT;
     constexpr int XH_ROWS = (16 * MB > 16 * XH_PER_THREAD) ? 16 * MB : 16 * XH_PER_THREAD;
@@ -592,6 +603,7 @@ __global__ void __launch_bounds__(128 * kLstmWaves, 1) lstm_backward_split_kerne
     // ---- chain waves: steps A and B
     const bool last_own_valid = s + W * (MTW - 1) < HT;           // unit tile s + 4(MTW-1)
     const bool last_qx_valid = s + W * (QXW - 1) < KXT;
+    float *sink_line = a.sink + ((bt + blockIdx.y * 61) % kSinkLines) * 64;
     // W^T operands of the k-steps this wave owns: k-step 4*mt + gate, mt = s + 4j
     float wreg[MB][4 * MTW];
 #pragma unroll
@@ -613,25 +625,35 @@ __global__ void __launch_bounds__(128 * kLstmWaves, 1) lstm_backward_split_kerne
     // operands of one position, requested one position ahead (branch-free, see the kernel above)
     float4 pf_gt[MTW];
     float pf_c[MTW], pf_cp[MTW], pf_g[MTW], pf_g2[MTW], pf_xh[XH_PER_THREAD];
-    auto fetch = [&](int p, bool first) {
+    // The requests of a position go out piece by piece, each as soon as the registers it fills are free:
+    // [x ; h] after it has gone to LDS, the operands of unit tile j after the elementwise step of tile j.
+    auto fetch_xh = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
         const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
 #pragma unroll
-        for (int j = 0; j < MTW; ++j) {
-            const int mt = min(s + W * j, HT - 1);
-            const size_t tile = (pb * HT + mt) * 64;
-            pf_gt[j] = (reinterpret_cast<const float4 *>(a.gates) + tile)[lane];
-            pf_c[j] = first ? (a.c + tile)[lane] : pf_cp[j];
-            pf_cp[j] = (a.c + (pbd * HT + mt) * 64)[lane];
-            pf_g[j] = (a.gsrc[0] + tile)[lane];
-            pf_g2[j] = (a.gsrc[1] + tile)[lane];
-        }
-#pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
+            // unit tile s + W*i of [x ; h]; tiles past the end alias the last one
             const int q = min(s + W * i, KT - 1);
             const float *src = q < KXT ? a.xsrc + pb * xtile + q * 64 : a.hid + pbd * htile + (q - KXT) * 64;
             pf_xh[i] = src[lane];
         }
+    };
+    auto fetch_tile = [&](int j, int p, bool first) {
+        const size_t pb = (size_t)p * a.NB + bt;
+        const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
+        // wave-uniform tile bases plus the lane index: scalar address arithmetic
+        const int mt = min(s + W * j, HT - 1);
+        const size_t tile = (pb * HT + mt) * 64;
+        pf_gt[j] = (reinterpret_cast<const float4 *>(a.gates) + tile)[lane];
+        pf_c[j] = first ? (a.c + tile)[lane] : pf_cp[j];
+        pf_cp[j] = (a.c + (pbd * HT + mt) * 64)[lane];
+        pf_g[j] = (a.gsrc[0] + tile)[lane];
+        pf_g2[j] = (a.gsrc[1] + tile)[lane];    // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
+    };
+    auto fetch = [&](int p, bool first) {
+        fetch_xh(p);
+#pragma unroll
+        for (int j = 0; j < MTW; ++j) fetch_tile(j, p, first);
     };
     const float g2_scale = a.n_gsrc >= 2 ? 1.0f : 0.0f;
     int n_valid = 0;
@@ -707,11 +729,13 @@ __global__ void __launch_bounds__(128 * kLstmWaves, 1) lstm_backward_split_kerne
             dxv[j] = (pt[0][q][lane] + pt[1][q][lane]) + (pt[2][q][lane] + pt[3][q][lane]);
         }
     };
-    auto store_dx = [&](int p) {
+    auto store_dx = [&](int p) {     // every wave issues the same number of stores (see the kernel above)
         const size_t pb = (size_t)p * a.NB + bt;
 #pragma unroll
-        for (int j = 0; j < QXW; ++j)
-            if (j < QXW - 1 || last_qx_valid) (a.gdst + pb * xtile + (s + W * j) * 64)[lane] = dxv[j];
+        for (int j = 0; j < QXW; ++j) {
+            float *dst = (j < QXW - 1 || last_qx_valid) ? a.gdst + pb * xtile + (s + W * j) * 64 : sink_line;
+            dst[lane] = dxv[j];
+        }
     };
 
     for (int r0 = blockIdx.y; r0 < a.d && r0 < Pt; r0 += gridDim.y) {
@@ -729,13 +753,16 @@ __global__ void __launch_bounds__(128 * kLstmWaves, 1) lstm_backward_split_kerne
         for (int p = p_last; p >= a.d; p -= a.d) {
             finish(buf);
             buf ^= 1;               // position p - d goes to the other copy
-            if (!kDxLate) store_dx(p);
+            store_dx(p);
             const bool has_prev = p >= 2 * a.d;
+            const int p_next = max(p - 2 * a.d, r0);
             store_xh(has_prev, buf);
+            fetch_xh(p_next);
 #pragma unroll
-            for (int j = 0; j < MTW; ++j) step_a_tile(j, has_prev, p - a.d, buf);
-            if (kDxLate) store_dx(p);
-            fetch(max(p - 2 * a.d, r0), false);
+            for (int j = 0; j < MTW; ++j) {
+                step_a_tile(j, has_prev, p - a.d, buf);
+                fetch_tile(j, p_next, false);
+            }
             step_b(buf);
         }
         finish(buf);
@@ -777,9 +804,9 @@ hipError_t run_fwd(const LstmFwdArgs &a, int chains, hipStream_t st)
 }
 
 template <int HT, int KXT>
-hipError_t run_bwd(const LstmBwdArgs &a, int chains, hipStream_t st)
+hipError_t run_bwd(const LstmBwdArgs &a, int chains, bool split, hipStream_t st)
 {
-    if constexpr (HT >= kSplitBwdFromHT) {
+    if (split) {
         if (a.sc) lstm_backward_split_kernel<HT, KXT, true><<<dim3(a.NB, chains), 128 * kLstmWaves, 0, st>>>(a);
         else lstm_backward_split_kernel<HT, KXT, false><<<dim3(a.NB, chains), 128 * kLstmWaves, 0, st>>>(a);
     } else {
@@ -837,9 +864,10 @@ hipError_t launch_lstm_backward(const Plan &pl, int layer, const int32_t *length
     }
     if (lp.narrow) return launch_lstm_backward_narrow(pl, layer, lengths, ws, st);
     a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
+    a.sink = ws + pl.sink;
     a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
     a.pmax = reinterpret_cast<const int32_t *>(ws + pl.pmax);
-#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains_bwd, st);
+#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_bwd<HT_, KXT_>(a, lp.chains_bwd, lp.split_bwd != 0, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

@@ -165,7 +165,7 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
     pl.es_blocks = pl.Bt / 64;
     // first everything the smoothing and window stages touch (their own entry points need only this prefix)
     pl.scalars = ws.take(64);
-    pl.sink = ws.take(64);
+    pl.sink = ws.take(64 * kSinkLines);
     pl.len_ext = ws.take((size_t)pl.B);
     pl.pmax = ws.take((size_t)pl.NB);
     pl.opt_partial = ws.take(512);
@@ -193,9 +193,11 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         // weight-gradient partials than the reduction can read cheaply
         const int max_chains = std::max(1, ceil_div(512, groups));
         lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
-        // the 16-series reverse kernel of the larger hidden sizes runs one workgroup of eight waves per compute unit
-        const bool split_bwd = !lp.narrow && pl.HT >= kSplitBwdFromHT;
-        lp.chains_bwd = split_bwd ? std::min(std::min(lp.dil, pl.P), std::max(1, ceil_div(256, groups))) : lp.chains;
+        // 16-series reverse kernel: with the larger hidden sizes (a four-wave workgroup would be alone on its
+        // compute unit for its registers), and where the grid has at most one workgroup per compute unit
+        // anyway, the kernel with eight waves and the weight gradient on waves of its own is the faster one
+        lp.split_bwd = !lp.narrow && (pl.HT >= kSplitBwdFromHT || groups * lp.chains <= 256) ? 1 : 0;
+        lp.chains_bwd = lp.split_bwd ? std::min(std::min(lp.dil, pl.P), std::max(1, ceil_div(256, groups))) : lp.chains;
         if (lp.narrow) {
             const int KT4 = 4 * KT, NG = ceil_div(KT4, 64);
             lp.wpack_fwd = ws.take((size_t)4 * KT4 * 64);
