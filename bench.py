@@ -28,33 +28,33 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # (FETCH x 2.0, WRITE x 1.0): profiles/hbm_traffic_<workload>_B<batch>.txt.  Valid for that workload and batch only.
 MEASURED_TRAFFIC_BYTES = {
     ('tiny_quarterly', 16): {
-        "es_forward": 1.1e+05, "window_forward": 1.5e+05, "lstm_forward_l0": 1.07e+06, "lstm_forward_l1": 1.23e+06,
-        "lstm_forward_l2": 1.23e+06, "lstm_forward_l3": 1.23e+06, "head_forward_backward": 1.57e+06, "forecasts": 1.4e+05,
-        "lstm_backward_l3": 2.55e+06, "lstm_backward_l2": 2.55e+06, "lstm_backward_l1": 2.55e+06, "lstm_backward_l0": 1.33e+06,
+        "es_forward": 1.1e+05, "window_forward": 1.5e+05, "lstm_forward_l0": 1.07e+06, "lstm_forward_l1": 1.24e+06,
+        "lstm_forward_l2": 1.24e+06, "lstm_forward_l3": 1.24e+06, "head_forward_backward": 1.57e+06, "forecasts": 1.4e+05,
+        "lstm_backward_l3": 2.56e+06, "lstm_backward_l2": 2.56e+06, "lstm_backward_l1": 2.56e+06, "lstm_backward_l0": 1.34e+06,
         "window_backward": 1.3e+05, "es_backward": 9e+04,
     },
     ('quarterly', 4096): {
-        "es_forward": 6.3e+06, "window_forward": 1.421e+07, "lstm_forward_l0": 2.442e+08, "lstm_forward_l1": 3.077e+08,
-        "lstm_forward_l2": 3.077e+08, "lstm_forward_l3": 3.077e+08, "head_forward_backward": 1.171e+08, "forecasts": 1.818e+07,
-        "lstm_backward_l3": 3.973e+08, "lstm_backward_l2": 3.973e+08, "lstm_backward_l1": 3.973e+08, "lstm_backward_l0": 2.956e+08,
+        "es_forward": 6.3e+06, "window_forward": 1.421e+07, "lstm_forward_l0": 2.442e+08, "lstm_forward_l1": 3.076e+08,
+        "lstm_forward_l2": 3.076e+08, "lstm_forward_l3": 3.076e+08, "head_forward_backward": 1.171e+08, "forecasts": 1.818e+07,
+        "lstm_backward_l3": 3.983e+08, "lstm_backward_l2": 3.983e+08, "lstm_backward_l1": 3.983e+08, "lstm_backward_l0": 2.957e+08,
         "window_backward": 1.56e+07, "es_backward": 6.15e+06,
     },
     ('monthly', 4096): {
         "es_forward": 2.019e+07, "window_forward": 1.18e+08, "lstm_forward_l0": 1.121e+09, "lstm_forward_l1": 1.386e+09,
         "lstm_forward_l2": 1.386e+09, "lstm_forward_l3": 1.386e+09, "head_forward_backward": 5.931e+08, "forecasts": 1.317e+08,
-        "lstm_backward_l3": 1.722e+09, "lstm_backward_l2": 1.722e+09, "lstm_backward_l1": 1.722e+09, "lstm_backward_l0": 1.355e+09,
-        "window_backward": 2.071e+08, "es_backward": 2.005e+07,
+        "lstm_backward_l3": 1.697e+09, "lstm_backward_l2": 1.697e+09, "lstm_backward_l1": 1.697e+09, "lstm_backward_l0": 1.355e+09,
+        "window_backward": 2.07e+08, "es_backward": 2.005e+07,
     },
     ('yearly', 8192): {
-        "es_forward": 5.49e+06, "window_forward": 1.751e+07, "lstm_forward_l0": 1.903e+08, "lstm_forward_l1": 2.34e+08,
-        "lstm_forward_l2": 2.34e+08, "lstm_forward_l3": 2.34e+08, "head_forward_backward": 9.038e+07, "forecasts": 1.245e+07,
-        "lstm_backward_l3": 2.978e+08, "lstm_backward_l2": 2.978e+08, "lstm_backward_l1": 2.978e+08, "lstm_backward_l0": 2.402e+08,
+        "es_forward": 5.49e+06, "window_forward": 1.751e+07, "lstm_forward_l0": 1.903e+08, "lstm_forward_l1": 2.342e+08,
+        "lstm_forward_l2": 2.342e+08, "lstm_forward_l3": 2.342e+08, "head_forward_backward": 9.038e+07, "forecasts": 1.245e+07,
+        "lstm_backward_l3": 2.978e+08, "lstm_backward_l2": 2.978e+08, "lstm_backward_l1": 2.978e+08, "lstm_backward_l0": 2.403e+08,
         "window_backward": 1.543e+07, "es_backward": 4.05e+06,
     },
     ('hourly', 512): {
-        "es_forward": 9.58e+06, "window_forward": 9.854e+07, "lstm_forward_l0": 4.23e+08, "lstm_forward_l1": 4.487e+08,
+        "es_forward": 9.58e+06, "window_forward": 9.854e+07, "lstm_forward_l0": 4.248e+08, "lstm_forward_l1": 4.42e+08,
         "lstm_forward_l2": 4.259e+08, "lstm_forward_l3": 4.259e+08, "head_forward_backward": 3.176e+08, "forecasts": 1.318e+08,
-        "lstm_backward_l3": 4.979e+08, "lstm_backward_l2": 4.979e+08, "lstm_backward_l1": 5.606e+08, "lstm_backward_l0": 4.417e+08,
+        "lstm_backward_l3": 4.99e+08, "lstm_backward_l2": 4.99e+08, "lstm_backward_l1": 5.59e+08, "lstm_backward_l0": 4.417e+08,
         "window_backward": 1.949e+08, "es_backward": 9.44e+06,
     },
 }
@@ -350,6 +350,31 @@ def config_summary(cfg, with_update=False):
             "parameter_update": bool(with_update), "categories": cfg.n_cat}
 
 
+def issue_overlap_probe(torch, binding, iterations=2000):
+    """Times the four modes of esrnn_probe_issue_overlap with one and two workgroups per compute unit."""
+    torch.cuda.set_device(0)
+    out = torch.empty(2 * 256 * 256, dtype=torch.float32, device="cuda")
+    names = {0: "mfma_only", 1: "vector_fma_only", 2: "both_in_every_wave", 3: "mfma_workgroup_beside_fma_workgroup"}
+    res = {}
+    for per_cu in (1, 2):
+        for mode in (0, 1, 2, 3):
+            if mode == 3 and per_cu == 1:
+                continue
+            best = None
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                binding.esrnn_probe_issue_overlap(mode, iterations, per_cu, out)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                best = ms if best is None else min(best, ms)
+            res[f"{names[mode]}_{per_cu}_per_cu"] = round(best * 1e6 / iterations, 1)
+    print(json.dumps({"probe": "issue overlap of fp32 MFMA (16x16x4) and vector FMA on one SIMD",
+                      "unit": "ns per round of 16 MFMAs and/or 64 vector FMAs per wave",
+                      "iterations": iterations, "workgroups": "256 x per_cu, four waves each", **res}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -389,6 +414,9 @@ def main():
     ap.add_argument("--es-window-sweep", default="",
                     help="comma-separated batch sizes: time only the smoothing and window stages (forward and "
                          "adjoint) at each, one JSON line per size, instead of the training-step benchmark")
+    ap.add_argument("--issue-overlap-probe", action="store_true",
+                    help="time the library's synthetic probe kernel (fp32 MFMAs, vector FMAs, both) and print one "
+                         "JSON line: do the two kinds of instruction overlap on a SIMD? (not a benchmark of the method)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (series shard trivially across GPUs, "
@@ -400,6 +428,9 @@ def main():
 
     if args.es_window_sweep:
         es_window_sweep(args, torch, binding, synth)
+        return
+    if args.issue_overlap_probe:
+        issue_overlap_probe(torch, binding)
         return
     cfg = synth.CONFIGS[args.workload]
     if args.batch:

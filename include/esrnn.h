@@ -325,6 +325,21 @@ esrnn_status esrnn_profile_stage_name(const esrnn_handle *h, int32_t i, const ch
 esrnn_status esrnn_profile_collect(esrnn_handle *h);
 esrnn_status esrnn_profile_read(const esrnn_handle *h, double *total_ms, int32_t *launches);
 
+/*
+ * Diagnostic, independent of any handle: a synthetic kernel that tells whether the fp32 matrix
+ * instructions (v_mfma_f32_16x16x4_f32) and the ordinary vector instructions of one SIMD execute at the
+ * same time on this device.  The bound of the LSTM kernels (Section 3.2 network at Table 1 sizes: gate
+ * contraction on the matrix pipe, activations on the vector ALU of the same SIMD) depends on it.
+ * Launches 256 x per_cu workgroups of four waves (per_cu = 1 or 2: workgroups that share a compute
+ * unit); every wave runs `iterations` rounds of
+ *   mode 0: 16 MFMAs;  mode 1: 64 vector FMAs;  mode 2: both, interleaved in every wave;
+ *   mode 3 (per_cu = 2): workgroups of the first half MFMAs only, of the second half FMAs only.
+ * The caller times the launch on `stream`.  If the two kinds overlapped, mode 2 would take the longer
+ * of modes 0 and 1, not their sum.  out: device, 256 * per_cu * 256 floats, overwritten with values of
+ * no meaning.  ESRNN_ERR_CONFIG for arguments outside these ranges (iterations 1 .. 1 << 20).
+ */
+esrnn_status esrnn_probe_issue_overlap(int32_t mode, int32_t iterations, int32_t per_cu, float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -105,6 +105,8 @@ def load_library():
     lib.esrnn_profile_stage_name.argtypes = [vp, C.c_int32, C.POINTER(C.c_char_p)]
     lib.esrnn_profile_collect.argtypes = [vp]
     lib.esrnn_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.esrnn_probe_issue_overlap.argtypes = [C.c_int32, C.c_int32, C.c_int32, fp, vp]
+    lib.esrnn_probe_issue_overlap.restype = C.c_int
     for fn in ("esrnn_profile_enable", "esrnn_profile_stage_count", "esrnn_profile_stage_name",
                "esrnn_profile_collect", "esrnn_profile_read"):
         getattr(lib, fn).restype = C.c_int
@@ -370,6 +372,17 @@ def esrnn_forecast_metrics(handle, forecasts, actuals, y, lengths, m, smape, mas
                                                _ptr(smape, torch.float32), _ptr(mase, torch.float32), _stream(stream))
     if st != ESRNN_OK:
         raise EsrnnError(st, "esrnn_forecast_metrics")
+
+
+def esrnn_probe_issue_overlap(mode: int, iterations: int, per_cu: int, out, stream=None) -> None:
+    """Diagnostic launch (see include/esrnn.h); `out` is a device float32 tensor of 256 * per_cu * 256 elements."""
+    import torch
+    if out.numel() < 256 * per_cu * 256:
+        raise ValueError("out is too small")
+    st = load_library().esrnn_probe_issue_overlap(int(mode), int(iterations), int(per_cu), _ptr(out, torch.float32),
+                                                  _stream(stream))
+    if st != ESRNN_OK:
+        raise EsrnnError(st, "esrnn_probe_issue_overlap")
 
 
 class TrainingStep:

@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libesrnn_hip.so")
 SOURCES = ["esrnn_api.cpp", "plan.cpp", "es_kernels.hip", "lstm_kernels.hip", "lstm_narrow_kernels.hip", "head_kernels.hip", "opt_kernels.hip",
-           "static_scratch.hip"]
+           "static_scratch.hip", "probe_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

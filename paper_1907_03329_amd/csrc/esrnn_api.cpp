@@ -402,6 +402,16 @@ esrnn_status esrnn_profile_read(const esrnn_handle *h, double *total_ms, int32_t
     return ESRNN_OK;
 }
 
+esrnn_status esrnn_probe_issue_overlap(int32_t mode, int32_t iterations, int32_t per_cu, float *out, void *stream)
+{
+    if (!out) return ESRNN_ERR_NULL;
+    if (mode < 0 || mode > 3 || per_cu < 1 || per_cu > 2 || (mode == 3 && per_cu != 2) || iterations < 1 ||
+        iterations > (1 << 20))
+        return ESRNN_ERR_CONFIG;
+    return esrnn::launch_probe_issue_overlap(mode, iterations, per_cu, out, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ESRNN_OK : ESRNN_ERR_HIP;
+}
+
 esrnn_status esrnn_workspace_buffer(const esrnn_handle *h, int32_t which, int32_t index, esrnn_buffer_view *out)
 {
     if (!h || !out) return ESRNN_ERR_NULL;

@@ -113,6 +113,7 @@ struct HeadPack {
     size_t WoT, WaT, bwd_total;
 };
 HeadPack head_pack_layout(const Plan &pl);
+hipError_t launch_probe_issue_overlap(int mode, int iterations, int per_cu, float *out, hipStream_t st);
 
 esrnn_status build_plan(const esrnn_config &cfg, Plan &pl);
 

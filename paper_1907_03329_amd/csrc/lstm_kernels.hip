@@ -3,10 +3,11 @@
 //
 // Parallel structure.  Series never interact, and a layer with dilation d is d
 // independent recurrences over the interleaved position classes p = r (mod d).
-// A workgroup of four waves therefore owns 16 series and one or more residue
-// classes r (grid = series tiles x chains) and walks each class in order with
-// the recurrent state on chip: h through LDS, c in registers.  There is no
-// grid-level synchronisation and no recurrent traffic through global memory.
+// A workgroup of four waves (eight in one variant of the reverse pass, see
+// there) therefore owns 16 series and one or more residue classes r (grid =
+// series tiles x chains) and walks each class in order with the recurrent state
+// on chip: h through LDS, c in registers.  There is no grid-level
+// synchronisation and no recurrent traffic through global memory.
 //
 // Arithmetic.  The gate contraction runs on the 16x16x4 fp32 MFMA with the
 // weights as the A operand, held in registers for the whole launch, and the
@@ -220,7 +221,10 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
 //      count of B plus C.
 // The loop is software-pipelined: the MFMAs of C(p) are issued together with
 // the elementwise work of A(p-d), whose global operands were requested one
-// position earlier.
+// position earlier.  fp32 MFMAs and vector instructions of a SIMD do not run at
+// the same time on this chip (esrnn_probe_issue_overlap measures it): what the
+// elementwise work and the address arithmetic cost is taken from the matrix
+// pipe, so both are kept short.
 // ---------------------------------------------------------------------------
 struct LstmBwdArgs {
     const float *wpack;   // [MB][4*HT][64]
@@ -806,10 +810,10 @@ hipError_t run_fwd(const LstmFwdArgs &a, int chains, hipStream_t st)
 template <int HT, int KXT>
 hipError_t run_bwd(const LstmBwdArgs &a, int chains, bool split, hipStream_t st)
 {
-    if (split) {
+    if (split || HT >= kSplitBwdFromHT) {
         if (a.sc) lstm_backward_split_kernel<HT, KXT, true><<<dim3(a.NB, chains), 128 * kLstmWaves, 0, st>>>(a);
         else lstm_backward_split_kernel<HT, KXT, false><<<dim3(a.NB, chains), 128 * kLstmWaves, 0, st>>>(a);
-    } else {
+    } else if constexpr (HT < kSplitBwdFromHT) {   // (the four-wave kernel is not built for the larger hidden sizes)
         if (a.sc) lstm_backward_kernel<HT, KXT, true><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
         else lstm_backward_kernel<HT, KXT, false><<<dim3(a.NB, chains), 64 * kLstmWaves, 0, st>>>(a);
     }

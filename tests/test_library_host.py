@@ -116,6 +116,10 @@ def test_null_and_order_errors_need_no_device(lib):
     assert lib.esrnn_check_workspace(h, C.c_void_p(4096), prefix, 0) == 3
     assert lib.esrnn_check_workspace(h, None, full, 0) == 1
     assert lib.esrnn_check_workspace(None, C.c_void_p(4096), full, 0) == 1
+    # the diagnostic probe checks its arguments before it launches
+    assert lib.esrnn_probe_issue_overlap(0, 10, 1, None, None) == 1
+    for mode, iters, per_cu in ((4, 10, 1), (-1, 10, 1), (0, 0, 1), (0, 10, 3), (3, 10, 1), (0, (1 << 20) + 1, 1)):
+        assert lib.esrnn_probe_issue_overlap(mode, iters, per_cu, C.c_void_p(4096), None) == 2
     # null array arguments are refused before anything is launched
     assert lib.esrnn_forward(h, None, None, None, None, None, None, None, None) == 1
     assert lib.esrnn_backward(h, None, None, None, None, None, None, None, None) == 1
