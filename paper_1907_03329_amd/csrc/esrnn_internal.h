@@ -45,7 +45,7 @@ struct LayerPlan {
     size_t gdst;         // TL(4*KXT) gradient with respect to the layer input
     int chains;          // workgroups per series tile (per 4 series if narrow); each walks the residue classes r, r+chains, ... (mod dil)
     int chains_bwd;      // the same for the reverse kernel
-    int split_bwd;       // 1: 16-series reverse kernel with the weight gradient on waves of its own, one workgroup per compute unit
+    int split_bwd;       // 1: reverse kernel with eight waves, the weight gradient on waves of its own, one workgroup per compute unit
     int narrow;          // 1: the layer runs on the 4-series kernels (lstm_narrow_kernels.hip): wpack_fwd is
                          // [4][4*(KXT+HT)][64], wpack_bwd [4][NG][4*HT][64], bias_pack unused, and the
                          // weight-gradient partials are indexed by 4*NB*chains workgroups

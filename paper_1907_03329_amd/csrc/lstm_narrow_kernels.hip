@@ -300,8 +300,13 @@ struct NarrowBwdArgs {
 
 // (up to hidden 40 the kernel is held to 256 registers: two workgroups per compute unit, which the chains of a
 // dilated layer need to run side by side)
-template <int HT, int KXT, bool CP>
-__global__ void __launch_bounds__(kNT, HT <= 10 ? 2 : 1) lstm_backward_narrow_kernel(NarrowBwdArgs a)
+// SPLIT: eight waves.  Waves 0-3 carry the recurrence (steps A and B and the sums); waves 4-7 do step C, the
+// weight gradient, which only consumes what step A leaves in LDS, one barrier behind them.  Both kinds take the
+// same barriers (one per position).  For grids of at most one workgroup per compute unit: the chain waves then
+// have half the matrix work per position, and the SIMDs have the weight-gradient waves' work while a chain wave
+// waits.
+template <int HT, int KXT, bool CP, bool SPLIT>
+__global__ void __launch_bounds__(SPLIT ? 2 * kNT : kNT, (!SPLIT && HT <= 10) ? 2 : 1) lstm_backward_narrow_kernel(NarrowBwdArgs a)
 {
     constexpr int KX = 4 * KXT, HP = 4 * HT, KT4 = KX + HP;
     constexpr int CH = 4;                        // positions per chunk of staged operands
@@ -315,7 +320,9 @@ __global__ void __launch_bounds__(kNT, HT <= 10 ? 2 : 1) lstm_backward_narrow_ke
     __shared__ float xhc[2][CH][CT * 64];                        // [column of x_p ; h_{p-d}][series]
 
     const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = SPLIT ? (wv & (kNW - 1)) : wv;
+    const bool dw_wave = SPLIT && wv >= kNW;
     const int blk = lane >> 2, j = lane & 3;
     // The four workgroups of a 16-series tile share every 64-byte row of the tile.  Consecutive workgroup
     // ids go round the 8 XCDs, each with its own L2: ids x, x+8, x+16, x+24 of a group of 32 are the four
@@ -347,6 +354,54 @@ __global__ void __launch_bounds__(kNT, HT <= 10 ? 2 : 1) lstm_backward_narrow_ke
         for (int nb = 0; nb < CT; ++nb) dw[t][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
     f32x4 dbacc = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int e = threadIdx.x; e < 2 * CH * CT * 64; e += kNT) (&xhc[0][0][0])[e] = 0.0f;   // columns past KT4 stay zero
+
+    auto store_dw = [&]() {
+        const size_t partix = (size_t)(4 * bt + q) * gridDim.y + blockIdx.y;
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            const int mt = w + kNW * t;
+            if (mt < HT) {
+#pragma unroll
+                for (int nb = 0; nb < CT; ++nb) {
+                    float *dst = a.dw_partial + (partix * (HT * CT) + mt * CT + nb) * 256 + lane;
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) dst[rr * 64] = dw[t][nb][rr];
+                }
+            }
+        }
+    };
+    if constexpr (SPLIT) {
+        if (dw_wave) {
+            // ---- C: weight gradient of one position, k = the four series; da in da_all[par], [x ; h] in xhc[cpar][ii]
+            auto step_c = [&](int par, int cpar, int ii) {
+                float xb[CT];
+#pragma unroll
+                for (int nb = 0; nb < CT; ++nb) xb[nb] = xhc[cpar][ii][64 * nb + xb_off];
+#pragma unroll
+                for (int t = 0; t < MTW; ++t) {
+                    const int mt = w + kNW * t;
+                    if (mt < HT) {
+                        // row 4*gate + u of the tile is gate `gate` of unit 4*mt + u
+                        const float ar = da_all[par][64 * mt + ar_off];
+#pragma unroll
+                        for (int nb = 0; nb < CT; ++nb) dw[t][nb] = mfma16(ar, xb[nb], dw[t][nb]);
+                    }
+                }
+            };
+            // the same barriers as the chain waves below: start of a chain, first staging, one per position
+            for (int r0 = blockIdx.y; r0 < a.d && r0 < Pt; r0 += gridDim.y) {
+                const int n = (Pt - r0 + a.d - 1) / a.d;
+                __syncthreads();
+                lds_barrier();
+                for (int i = 0; i < n; ++i) {
+                    lds_barrier();
+                    step_c(i & 1, (i / CH) & 1, i % CH);
+                }
+            }
+            store_dw();
+            return;
+        }
+    }
 
     const float g2_scale = a.n_gsrc >= 2 ? 1.0f : 0.0f;
     int n_valid = 0;
@@ -467,8 +522,8 @@ __global__ void __launch_bounds__(kNT, HT <= 10 ? 2 : 1) lstm_backward_narrow_ke
             }
             const float dxv = (part[par][0][dx_el] + part[par][1][dx_el]) + (part[par][2][dx_el] + part[par][3][dx_el]);
             (a.gdst + ((size_t)p * a.NB + bt) * (KX * 16))[(dx_el >> 2) * 16 + 4 * q + (dx_el & 3)] = dxv;
-            // ---- C: weight gradient, k = the four series
-            {
+            // ---- C: weight gradient, k = the four series (on the waves of its own where there are some)
+            if constexpr (!SPLIT) {
                 float xb[CT];
 #pragma unroll
                 for (int nb = 0; nb < CT; ++nb) xb[nb] = xhc[cpar][ii][64 * nb + xb_off];
@@ -502,19 +557,8 @@ __global__ void __launch_bounds__(kNT, HT <= 10 ? 2 : 1) lstm_backward_narrow_ke
         for (int i = c * CH; i < n; ++i) position(i, i - c * CH, c & 1, min(i + 1, n - 1) - c * CH, [] {});
     }
 
+    if constexpr (!SPLIT) store_dw();
     const size_t partix = (size_t)(4 * bt + q) * gridDim.y + blockIdx.y;
-#pragma unroll
-    for (int t = 0; t < MTW; ++t) {
-        const int mt = w + kNW * t;
-        if (mt < HT) {
-#pragma unroll
-            for (int nb = 0; nb < CT; ++nb) {
-                float *dst = a.dw_partial + (partix * (HT * CT) + mt * CT + nb) * 256 + lane;
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) dst[rr * 64] = dw[t][nb][rr];
-            }
-        }
-    }
     // bias gradient: sum over the four series (the lanes of a quad)
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
@@ -548,10 +592,16 @@ hipError_t run_nfwd(const NarrowFwdArgs &a, int chains, hipStream_t st)
 }
 
 template <int HT, int KXT>
-hipError_t run_nbwd(const NarrowBwdArgs &a, int chains, hipStream_t st)
+hipError_t run_nbwd(const NarrowBwdArgs &a, int chains, bool split, hipStream_t st)
 {
-    if (a.sc) lstm_backward_narrow_kernel<HT, KXT, true><<<dim3(narrow_grid_x(a.NB), chains), 64 * kNW, 0, st>>>(a);
-    else lstm_backward_narrow_kernel<HT, KXT, false><<<dim3(narrow_grid_x(a.NB), chains), 64 * kNW, 0, st>>>(a);
+    const dim3 grid(narrow_grid_x(a.NB), chains);
+    if (split) {
+        if (a.sc) lstm_backward_narrow_kernel<HT, KXT, true, true><<<grid, 2 * kNT, 0, st>>>(a);
+        else lstm_backward_narrow_kernel<HT, KXT, false, true><<<grid, 2 * kNT, 0, st>>>(a);
+    } else {
+        if (a.sc) lstm_backward_narrow_kernel<HT, KXT, true, false><<<grid, kNT, 0, st>>>(a);
+        else lstm_backward_narrow_kernel<HT, KXT, false, false><<<grid, kNT, 0, st>>>(a);
+    }
     return hipGetLastError();
 }
 
@@ -591,7 +641,7 @@ hipError_t launch_lstm_backward_narrow(const Plan &pl, int layer, const int32_t 
     a.gdst = ws + lp.gdst; a.dw_partial = ws + lp.dw_partial; a.db_partial = ws + lp.db_partial;
     a.P = pl.P; a.NB = pl.NB; a.d = lp.dil;
     a.pmax = reinterpret_cast<const int32_t *>(ws + pl.pmax);
-#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_nbwd<HT_, KXT_>(a, lp.chains, st);
+#define X(HT_, KXT_) if (pl.HT == HT_ && lp.KXT == KXT_) return run_nbwd<HT_, KXT_>(a, lp.chains, lp.split_bwd != 0, st);
     ESRNN_LSTM_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

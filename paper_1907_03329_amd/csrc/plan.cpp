@@ -193,11 +193,14 @@ esrnn_status build_plan(const esrnn_config &cfg, Plan &pl)
         // weight-gradient partials than the reduction can read cheaply
         const int max_chains = std::max(1, ceil_div(512, groups));
         lp.chains = std::min(std::min(lp.dil, pl.P), max_chains);
-        // 16-series reverse kernel: with the larger hidden sizes (a four-wave workgroup would be alone on its
-        // compute unit for its registers), and where the grid has at most one workgroup per compute unit
-        // anyway, the kernel with eight waves and the weight gradient on waves of its own is the faster one
-        lp.split_bwd = !lp.narrow && (pl.HT >= kSplitBwdFromHT || groups * lp.chains <= 256) ? 1 : 0;
-        lp.chains_bwd = lp.split_bwd ? std::min(std::min(lp.dil, pl.P), std::max(1, ceil_div(256, groups))) : lp.chains;
+        // Reverse kernels with eight waves, the weight gradient on waves of its own: one workgroup per compute
+        // unit.  The faster kind where the grid has at most one workgroup per compute unit anyway, and for the
+        // 16-series kernel with the larger hidden sizes (whose four-wave workgroup would be alone on its
+        // compute unit for its registers).
+        const bool one_per_cu = groups * lp.chains <= 256;
+        lp.split_bwd = (one_per_cu || (!lp.narrow && pl.HT >= kSplitBwdFromHT)) ? 1 : 0;
+        lp.chains_bwd = (lp.split_bwd && !lp.narrow) ? std::min(std::min(lp.dil, pl.P), std::max(1, ceil_div(256, groups)))
+                                                      : lp.chains;
         if (lp.narrow) {
             const int KT4 = 4 * KT, NG = ceil_div(KT4, 64);
             lp.wpack_fwd = ws.take((size_t)4 * KT4 * 64);
