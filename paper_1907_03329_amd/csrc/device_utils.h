@@ -28,6 +28,37 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
+// Buffer addressing for the wave-uniform tiles of the LSTM kernels: the tile's base is a scalar resource (built
+// with scalar instructions from a pointer that is the same in every lane), the tile's offset inside it a scalar
+// byte offset, the lane's share a 32-bit byte offset that never changes.  No address arithmetic is left on the
+// vector ALU, whose cycles the fp32 MFMAs need.  A resource spans 4 GiB from its base (raw buffer, no stride, no
+// range limit): callers rebase it per window position and keep the offsets inside one position.
+typedef __amdgpu_buffer_rsrc_t buf_rsrc;
+__device__ __forceinline__ buf_rsrc make_rsrc(const void *base)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, -1, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(buf_rsrc r, unsigned lane_bytes, unsigned tile_bytes)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, lane_bytes, tile_bytes, 0));
+}
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4 buf_load4(buf_rsrc r, unsigned lane_bytes, unsigned tile_bytes)
+{
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, lane_bytes, tile_bytes, 0));
+}
+// kStream: the value is not read again soon (streaming store)
+template <bool kStream = false>
+__device__ __forceinline__ void buf_store(buf_rsrc r, unsigned lane_bytes, unsigned tile_bytes, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, lane_bytes, tile_bytes, kStream ? 2 : 0);
+}
+template <bool kStream = false>
+__device__ __forceinline__ void buf_store4(buf_rsrc r, unsigned lane_bytes, unsigned tile_bytes, f32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, lane_bytes, tile_bytes, kStream ? 2 : 0);
+}
+
 // Workgroup barrier that orders LDS traffic only: global loads and stores in
 // flight are not waited for.
 __device__ __forceinline__ void lds_barrier()

@@ -93,6 +93,7 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         float bx[KXT];
 #pragma unroll
         for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + ((size_t)r * a.NB + bt) * xtile + ks * 64)[lane];
+        const unsigned lane4 = 4 * lane, lane16 = 16 * lane;   // this lane's bytes inside a tile
         f32x4 acc[MTW];
         // input part (with the bias) of one position; a helper's share first, so that it is complete when it
         // goes to LDS after the rest
@@ -111,9 +112,9 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         };
         input_part(0);
         {
-            const size_t nb = ((size_t)min(r + a.d, Pt - 1) * a.NB + bt) * xtile;
+            const buf_rsrc rx = make_rsrc(a.xsrc + ((size_t)min(r + a.d, Pt - 1) * a.NB + bt) * xtile);
 #pragma unroll
-            for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + nb + ks * 64)[lane];
+            for (int ks = 0; ks < KXT; ++ks) bx[ks] = buf_load(rx, lane4, ks * 256);
         }
         // residual input of the block (last layer of a block >= 1), one position ahead like the input
         float res[MTW];
@@ -125,12 +126,14 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
         int it = 0;
         for (int p = r; p < Pt; p += a.d, ++it) {
             const size_t pb = (size_t)p * a.NB + bt;
+            // this position's tiles of the stash and the outputs: scalar bases, scalar tile offsets
+            const buf_rsrc r_gates = make_rsrc(a.gates + pb * HT * 256), r_c = make_rsrc(a.c + pb * HT * 64);
+            const buf_rsrc r_hid = make_rsrc(a.hid + pb * HT * 64), r_out = make_rsrc(a.out + (a.out ? pb * HT * 64 : 0));
             float res_next[MTW];
             if (a.out) {
-                const size_t nb = ((size_t)min(p + a.d, Pt - 1) * a.NB + bt) * HT;
+                const buf_rsrc rr = make_rsrc(a.resid + ((size_t)min(p + a.d, Pt - 1) * a.NB + bt) * HT * 64);
 #pragma unroll
-                for (int j = 0; j < MTW; ++j)
-                    res_next[j] = (a.resid + (nb + min(s + kLstmWaves * j, HT - 1)) * 64)[lane];
+                for (int j = 0; j < MTW; ++j) res_next[j] = buf_load(rr, lane4, min(s + kLstmWaves * j, HT - 1) * 256);
             }
             // recurrent part
             const float *hb = hbuf[it & 1];
@@ -156,12 +159,11 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
                 creg[j] = cn;
                 if constexpr (CP) csq += p < n_valid ? cn * cn : 0.0f;
                 hn_buf[mt * 64 + lane] = hn;
-                const size_t tile = (pb * HT + mt) * 64;   // wave-uniform: scalar address arithmetic
-                // gates are read again only by the reverse pass: streaming stores
-                __builtin_nontemporal_store(f32x4{gi, gf, gg, go}, reinterpret_cast<f32x4 *>(a.gates) + tile + lane);
-                __builtin_nontemporal_store(cn, a.c + tile + lane);
-                (a.hid + tile)[lane] = hn;
-                if (a.out) (a.out + tile)[lane] = res[j] + hn;
+                // gates and cell state are read again only by the reverse pass: streaming stores
+                buf_store4<true>(r_gates, lane16, mt * 1024, f32x4{gi, gf, gg, go});
+                buf_store<true>(r_c, lane4, mt * 256, cn);
+                buf_store(r_hid, lane4, mt * 256, hn);
+                if (a.out) buf_store(r_out, lane4, mt * 256, res[j] + hn);
             };
             // (with a one-tile input, KXT = 1, the plain order measured faster and is kept)
             constexpr bool kAhead = KXT >= 2;
@@ -180,9 +182,9 @@ __global__ void __launch_bounds__(64 * kLstmWaves, 2) lstm_forward_kernel(LstmFw
             // the barrier
             if (p + a.d < Pt) {
                 input_part((it + 1) & 1);
-                const size_t nb = ((size_t)min(p + 2 * a.d, Pt - 1) * a.NB + bt) * xtile;
+                const buf_rsrc rx = make_rsrc(a.xsrc + ((size_t)min(p + 2 * a.d, Pt - 1) * a.NB + bt) * xtile);
 #pragma unroll
-                for (int ks = 0; ks < KXT; ++ks) bx[ks] = (a.xsrc + nb + ks * 64)[lane];
+                for (int ks = 0; ks < KXT; ++ks) bx[ks] = buf_load(rx, lane4, ks * 256);
             }
             if (a.out) {
 #pragma unroll
