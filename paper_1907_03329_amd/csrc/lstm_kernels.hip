@@ -309,28 +309,31 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     // cell state c[p] is still in registers: it is not read from memory a second time.
     // The requests of a position go out piece by piece, each as soon as the registers it fills are free:
     // [x ; h] after it has gone to LDS, the operands of unit tile j after the elementwise step of tile j.
+    // Buffer addressing: the tiles of a position sit behind scalar bases, a tile is a scalar byte offset, the
+    // lane's share a fixed 32-bit offset - no address arithmetic on the vector ALU.
+    const unsigned lane4 = 4 * lane, lane16 = 16 * lane;
     auto fetch_xh = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
         const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
 #pragma unroll
         for (int i = 0; i < XH_PER_THREAD; ++i) {
-            // unit tile s + W*i of [x ; h]; tiles past the end alias the last one
+            // unit tile s + W*i of [x ; h]; tiles past the end alias the last one.  One request whichever array
+            // the tile is in (a scalar choice of the base, no branch around the request)
             const int q = min(s + W * i, KT - 1);
             const float *src = q < KXT ? a.xsrc + pb * xtile + q * 64 : a.hid + pbd * htile + (q - KXT) * 64;
-            pf_xh[i] = src[lane];
+            pf_xh[i] = buf_load(make_rsrc(src), lane4, 0);
         }
     };
     auto fetch_tile = [&](int j, int p, bool first) {
         const size_t pb = (size_t)p * a.NB + bt;
         const size_t pbd = (size_t)(p >= a.d ? p - a.d : p) * a.NB + bt;
-        // wave-uniform tile bases plus the lane index: scalar address arithmetic
-        const int mt = min(s + W * j, HT - 1);
-        const size_t tile = (pb * HT + mt) * 64;
-        pf_gt[j] = (reinterpret_cast<const float4 *>(a.gates) + tile)[lane];
-        pf_c[j] = first ? (a.c + tile)[lane] : pf_cp[j];
-        pf_cp[j] = (a.c + (pbd * HT + mt) * 64)[lane];
-        pf_g[j] = (a.gsrc[0] + tile)[lane];
-        pf_g2[j] = (a.gsrc[1] + tile)[lane];    // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
+        const int mt = __builtin_amdgcn_readfirstlane(min(s + W * j, HT - 1));   // (known to be uniform)
+        const f32x4 gt = buf_load4(make_rsrc(a.gates + pb * htile * 4), lane16, mt * 1024);
+        pf_gt[j] = make_float4(gt[0], gt[1], gt[2], gt[3]);
+        pf_c[j] = first ? buf_load(make_rsrc(a.c + pb * htile), lane4, mt * 256) : pf_cp[j];
+        pf_cp[j] = buf_load(make_rsrc(a.c + pbd * htile), lane4, mt * 256);
+        pf_g[j] = buf_load(make_rsrc(a.gsrc[0] + pb * htile), lane4, mt * 256);
+        pf_g2[j] = buf_load(make_rsrc(a.gsrc[1] + pb * htile), lane4, mt * 256);   // gsrc[1] repeats gsrc[0] when there is one source (ignored then)
     };
     auto fetch = [&](int p, bool first) {
         fetch_xh(p);
@@ -433,10 +436,11 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
     // (which then do not wait for them) and a whole position ahead of the next wait.
     auto store_dx = [&](int p) {
         const size_t pb = (size_t)p * a.NB + bt;
+        const buf_rsrc r_dx = make_rsrc(a.gdst + pb * xtile), r_sink = make_rsrc(sink_line);
 #pragma unroll
         for (int j = 0; j < QXW; ++j) {
-            float *dst = (j < QXW - 1 || last_qx_valid) ? a.gdst + pb * xtile + (s + W * j) * 64 : sink_line;
-            dst[lane] = dxv[j];
+            if (j < QXW - 1 || last_qx_valid) buf_store(r_dx, lane4, (s + W * j) * 256, dxv[j]);
+            else buf_store(r_sink, lane4, 0, dxv[j]);
         }
     };
     auto dw_row = [&](int j) {
