@@ -543,7 +543,7 @@ __global__ void __launch_bounds__(128 * kLstmWaves, 1) lstm_backward_split_kerne
     __shared__ float da_lds[2][DA_ROWS * kLdsPad];   // [mt][4*gate + unit][series]
     __shared__ float xh_lds[2][XH_ROWS * kLdsPad];   // [row of x ; h][series]; rows past 4*KT are scratch
     __shared__ float part_lds[2][W][MB * 4][64];     // partial d[x ; h] of every chain wave
-    static_assert(2 * (DA_ROWS * kLdsPad + XH_ROWS * kLdsPad + W * MB * 4 * 64) * 4 <= 160 * 1024,
+    static_assert(2 * (DA_ROWS * kLdsPad + XH_ROWS * kLdsPad + W * MB * 4 * 64) * 4 <= 128 * 1024,
                   "LDS budget of the reverse kernel");
 
     const int lane = threadIdx.x & 63, bt = blockIdx.x;
