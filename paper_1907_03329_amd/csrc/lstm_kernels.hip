@@ -358,14 +358,17 @@ __global__ void __launch_bounds__(64 * kLstmWaves, (HT <= 10 ? 2 : 1)) lstm_back
         const float4 gt = pf_gt[j];
         const float dh = pf_g[j] + g2_scale * pf_g2[j] + dhreg[j];
         const float tc = tanh_f(pf_c[j]);
-        float dc = dcreg[j] + dh * gt.w * (1.0f - tc * tc);
+        // (products shared between the terms are formed once: the vector ALU's cycles are the matrix pipe's)
+        const float dh_o = dh * gt.w;
+        float dc = dcreg[j] + dh_o * (1.0f - tc * tc);
         if constexpr (CP) dc += p_cur < n_valid ? pen * pf_c[j] : 0.0f;
         const float cp = has_prev ? pf_cp[j] : 0.0f;
-        da[j][0] = dc * gt.z * gt.x * (1.0f - gt.x);
-        da[j][1] = dc * cp * gt.y * (1.0f - gt.y);
-        da[j][2] = dc * gt.x * (1.0f - gt.z * gt.z);
-        da[j][3] = dh * tc * gt.w * (1.0f - gt.w);
-        dcreg[j] = dc * gt.y;
+        const float dc_i = dc * gt.x, dc_f = dc * gt.y;
+        da[j][0] = dc_i * gt.z * (1.0f - gt.x);
+        da[j][1] = dc_f * cp * (1.0f - gt.y);
+        da[j][2] = dc_i * (1.0f - gt.z * gt.z);
+        da[j][3] = dh_o * tc * (1.0f - gt.w);
+        dcreg[j] = dc_f;
         float *dst = da_lds + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -680,14 +683,17 @@ __global__ void __launch_bounds__(128 * kLstmWaves, 1) lstm_backward_split_kerne
         const float4 gt = pf_gt[j];
         const float dh = pf_g[j] + g2_scale * pf_g2[j] + dhreg[j];
         const float tc = tanh_f(pf_c[j]);
-        float dc = dcreg[j] + dh * gt.w * (1.0f - tc * tc);
+        // (products shared between the terms are formed once: the vector ALU's cycles are the matrix pipe's)
+        const float dh_o = dh * gt.w;
+        float dc = dcreg[j] + dh_o * (1.0f - tc * tc);
         if constexpr (CP) dc += p_cur < n_valid ? pen * pf_c[j] : 0.0f;
         const float cp = has_prev ? pf_cp[j] : 0.0f;
-        da[j][0] = dc * gt.z * gt.x * (1.0f - gt.x);
-        da[j][1] = dc * cp * gt.y * (1.0f - gt.y);
-        da[j][2] = dc * gt.x * (1.0f - gt.z * gt.z);
-        da[j][3] = dh * tc * gt.w * (1.0f - gt.w);
-        dcreg[j] = dc * gt.y;
+        const float dc_i = dc * gt.x, dc_f = dc * gt.y;
+        da[j][0] = dc_i * gt.z * (1.0f - gt.x);
+        da[j][1] = dc_f * cp * (1.0f - gt.y);
+        da[j][2] = dc_i * (1.0f - gt.z * gt.z);
+        da[j][3] = dh_o * tc * (1.0f - gt.w);
+        dcreg[j] = dc_f;
         float *dst = da_lds[buf] + ((s + W * j) * 16 + g) * kLdsPad + n;   // dummy rows for tiles past HT
 #pragma unroll
         for (int r = 0; r < 4; ++r) {

@@ -473,15 +473,17 @@ __global__ void __launch_bounds__(SPLIT ? 2 * kNT : kNT, (!SPLIT && HT <= 10) ? 
             // ---- A: gate gradients of (unit, series)
             const float dh = o[2] + g2_scale * o[3] + dhreg;
             const float tc = tanh_f(o[0]);
-            float dc = dcreg + dh * gt[3] * (1.0f - tc * tc);
+            const float dh_o = dh * gt[3];          // (shared products formed once)
+            float dc = dcreg + dh_o * (1.0f - tc * tc);
             if constexpr (CP) dc += p < n_valid ? pen * o[0] : 0.0f;
             const float cp = has_prev ? o[1] : 0.0f;
+            const float dc_i = dc * gt[0], dc_f = dc * gt[1];
             f32x4 da;
-            da[0] = dc * gt[2] * gt[0] * (1.0f - gt[0]);
-            da[1] = dc * cp * gt[1] * (1.0f - gt[1]);
-            da[2] = dc * gt[0] * (1.0f - gt[2] * gt[2]);
-            da[3] = dh * tc * gt[3] * (1.0f - gt[3]);
-            dcreg = dc * gt[1];
+            da[0] = dc_i * gt[2] * (1.0f - gt[0]);
+            da[1] = dc_f * cp * (1.0f - gt[1]);
+            da[2] = dc_i * (1.0f - gt[2] * gt[2]);
+            da[3] = dh_o * tc * (1.0f - gt[3]);
+            dcreg = dc_f;
             if (valid) dbacc += da;
             *reinterpret_cast<f32x4 *>(&da_all[par][16 * unit + 4 * j]) = da;    // for step C
             // ---- B: partial W^T da over the k-steps (unit, gate) of this wave; da of unit u is
