@@ -28,9 +28,9 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # (FETCH x 2.0, WRITE x 1.0): profiles/hbm_traffic_<workload>_B<batch>.txt.  Valid for that workload and batch only.
 MEASURED_TRAFFIC_BYTES = {
     ('tiny_quarterly', 16): {
-        "es_forward": 1.1e+05, "window_forward": 1.5e+05, "lstm_forward_l0": 1.05e+06, "lstm_forward_l1": 1.25e+06,
-        "lstm_forward_l2": 1.25e+06, "lstm_forward_l3": 1.25e+06, "head_forward_backward": 1.57e+06, "forecasts": 1.4e+05,
-        "lstm_backward_l3": 2.55e+06, "lstm_backward_l2": 2.55e+06, "lstm_backward_l1": 2.55e+06, "lstm_backward_l0": 1.34e+06,
+        "es_forward": 1.1e+05, "window_forward": 1.5e+05, "lstm_forward_l0": 1.05e+06, "lstm_forward_l1": 1.24e+06,
+        "lstm_forward_l2": 1.24e+06, "lstm_forward_l3": 1.24e+06, "head_forward_backward": 1.57e+06, "forecasts": 1.4e+05,
+        "lstm_backward_l3": 2.54e+06, "lstm_backward_l2": 2.54e+06, "lstm_backward_l1": 2.54e+06, "lstm_backward_l0": 1.33e+06,
         "window_backward": 1.3e+05, "es_backward": 9e+04,
     },
     ('quarterly', 4096): {
@@ -43,7 +43,7 @@ MEASURED_TRAFFIC_BYTES = {
         "es_forward": 2.019e+07, "window_forward": 1.18e+08, "lstm_forward_l0": 1.121e+09, "lstm_forward_l1": 1.385e+09,
         "lstm_forward_l2": 1.385e+09, "lstm_forward_l3": 1.385e+09, "head_forward_backward": 5.931e+08, "forecasts": 1.317e+08,
         "lstm_backward_l3": 1.697e+09, "lstm_backward_l2": 1.697e+09, "lstm_backward_l1": 1.697e+09, "lstm_backward_l0": 1.355e+09,
-        "window_backward": 2.07e+08, "es_backward": 2.005e+07,
+        "window_backward": 2.069e+08, "es_backward": 2.005e+07,
     },
     ('yearly', 8192): {
         "es_forward": 5.49e+06, "window_forward": 1.751e+07, "lstm_forward_l0": 1.903e+08, "lstm_forward_l1": 2.341e+08,
@@ -52,9 +52,9 @@ MEASURED_TRAFFIC_BYTES = {
         "window_backward": 1.543e+07, "es_backward": 4.05e+06,
     },
     ('hourly', 512): {
-        "es_forward": 9.58e+06, "window_forward": 9.854e+07, "lstm_forward_l0": 4.246e+08, "lstm_forward_l1": 4.417e+08,
+        "es_forward": 9.58e+06, "window_forward": 9.854e+07, "lstm_forward_l0": 4.217e+08, "lstm_forward_l1": 4.422e+08,
         "lstm_forward_l2": 4.259e+08, "lstm_forward_l3": 4.259e+08, "head_forward_backward": 3.176e+08, "forecasts": 1.318e+08,
-        "lstm_backward_l3": 4.991e+08, "lstm_backward_l2": 4.991e+08, "lstm_backward_l1": 5.59e+08, "lstm_backward_l0": 4.417e+08,
+        "lstm_backward_l3": 4.99e+08, "lstm_backward_l2": 4.99e+08, "lstm_backward_l1": 5.59e+08, "lstm_backward_l0": 4.417e+08,
         "window_backward": 1.949e+08, "es_backward": 9.44e+06,
     },
 }
