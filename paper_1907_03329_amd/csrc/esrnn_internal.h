@@ -128,6 +128,7 @@ hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths
 hipError_t launch_lstm_forward_narrow(const Plan &pl, int layer, const int32_t *lengths, const float *weights,
                                       float *ws, hipStream_t st);
 hipError_t launch_lstm_backward_narrow(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
+hipError_t launch_lstm_backward_narrow_split(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
 // output stage, forward and reverse in one launch (needs the loss normalisers of launch_setup)
 hipError_t launch_head(const Plan &pl, const int32_t *lengths, float *ws, bool reverse, hipStream_t st);
 hipError_t launch_forecasts(const Plan &pl, const int32_t *lengths, float *ws, float *forecasts, hipStream_t st);
