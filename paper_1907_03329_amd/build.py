@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libesrnn_hip.so")
-SOURCES = ["esrnn_api.cpp", "plan.cpp", "es_kernels.hip", "lstm_kernels.hip", "lstm_narrow_kernels.hip", "lstm_narrow_bwd_kernels.hip", "lstm_narrow_bwd_split_kernels.hip", "head_kernels.hip", "opt_kernels.hip",
+SOURCES = ["esrnn_api.cpp", "plan.cpp", "es_kernels.hip", "lstm_kernels.hip", "lstm_narrow_kernels.hip", "lstm_narrow_fwd_residual_kernels.hip", "lstm_narrow_bwd_kernels.hip", "lstm_narrow_bwd_split_kernels.hip", "head_kernels.hip", "opt_kernels.hip",
            "static_scratch.hip", "probe_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",

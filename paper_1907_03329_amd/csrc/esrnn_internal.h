@@ -46,7 +46,7 @@ struct LayerPlan {
     int chains;          // workgroups per series tile (per 4 series if narrow); each walks the residue classes r, r+chains, ... (mod dil)
     int chains_bwd;      // the same for the reverse kernel
     int split_bwd;       // 1: reverse kernel with eight waves, the weight gradient on waves of its own, one workgroup per compute unit
-    int narrow;          // 1: the layer runs on the 4-series kernels (lstm_narrow_kernels.hip): wpack_fwd is
+    int narrow;          // 1: the layer runs on the 4-series kernels (lstm_narrow_fwd.h, lstm_narrow_bwd.h): wpack_fwd is
                          // [4][4*(KXT+HT)][64], wpack_bwd [4][NG][4*HT][64], bias_pack unused, and the
                          // weight-gradient partials are indexed by 4*NB*chains workgroups
     size_t dw_partial;   // [NB*chains][HT*MB][4][64] per-workgroup weight-gradient tiles
@@ -126,6 +126,8 @@ hipError_t launch_lstm_forward(const Plan &pl, int layer, const int32_t *lengths
                                hipStream_t st);
 // 4-series kernels for layers with few workgroups (called by the two launchers above and below)
 hipError_t launch_lstm_forward_narrow(const Plan &pl, int layer, const int32_t *lengths, const float *weights,
+                                      float *ws, hipStream_t st);
+hipError_t launch_lstm_forward_narrow_residual(const Plan &pl, int layer, const int32_t *lengths, const float *weights,
                                       float *ws, hipStream_t st);
 hipError_t launch_lstm_backward_narrow(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
 hipError_t launch_lstm_backward_narrow_split(const Plan &pl, int layer, const int32_t *lengths, float *ws, hipStream_t st);
